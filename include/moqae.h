@@ -1,0 +1,164 @@
+/*
+ * libmoqae -- MoQAE inference hot path on AMD MI355X (gfx950).
+ *
+ * Three operations (arXiv 2506.07533):
+ *   moqae_route_chunks   chunk-wise routing of cached keys to bit-width experts
+ *                        (router MLP Eq. (1), token top-1 + chunk majority vote
+ *                        Eq. (2), Sec. 3.2; routing freezing, Sec. 3.4);
+ *   moqae_quantize_pack  group-wise quantisation of every chunk at its routed
+ *                        bit-width into a packed arena (Sec. 3.1: chunks "are
+ *                        quantized using the bit-width configuration just
+ *                        determined"; the residual shorter than a chunk stays
+ *                        FP16, Sec. 3.2);
+ *   moqae_decode_attn    single-token decode attention over the mixed-precision
+ *                        cache with de-quantisation on the fly and a full-
+ *                        precision softmax (Sec. "Limitations").
+ * Routing sharing (Sec. 3.4) needs no entry point: a follower block passes its
+ * group leader's `expert` table to moqae_quantize_pack.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller unless the comment
+ *     says "host".  `cfg` is a host pointer, read during the call only.
+ *   - Every call only enqueues work on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream): no allocation, no synchronisation.
+ *   - Return value: MOQAE_OK or a negative MOQAE_E_* code.  Argument errors are
+ *     detected on the host before anything is launched.
+ *   - fp16 tensors are IEEE binary16; [B, Hkv, S, D] tensors are addressed by
+ *     element strides with the last dimension contiguous.
+ *
+ * Packed chunk block (bit-width b, N tokens, D = head_dim, G = group):
+ *   b < 16 : [K codes | K meta | V codes | V meta]
+ *            codes area = N*D*b/8 bytes of little-endian 32-bit words, a word
+ *            holds 32/b codes, the code with in-word index e sits at bit
+ *            16*(e%2) + b*(e/2);
+ *            K codes: token-major rows of D*b/32 words, dim d -> word d/(32/b),
+ *                     in-word index d%(32/b);
+ *            V codes: tiles of 64/b tokens, 2*D words per tile; dim d owns
+ *                     words 2d, 2d+1 of its tile, token tau of the tile ->
+ *                     word tau/(32/b), in-word index tau%(32/b);
+ *            meta area = one 32-bit word per (token, group), token-major:
+ *                     fp16 scale | fp16 zero << 16;  x^ = code*scale + zero.
+ *   b = 16 : [K rows | V rows], raw fp16, token-major.
+ * Quantiser (per token, per group of G consecutive dims): zero = min,
+ *   scale = fp16 round-UP of (max-min)/(2^b-1) (1.0 if max == min),
+ *   code = clamp(rint((x-zero) * (1/scale)), 0, 2^b-1), all in binary32 with
+ *   round-to-nearest-even.
+ */
+#ifndef MOQAE_H
+#define MOQAE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOQAE_ABI_VERSION 1u
+#define MOQAE_MAX_EXPERTS 8
+
+enum {
+    MOQAE_OK          =  0,
+    MOQAE_E_INVAL     = -1,  /* bad configuration, null pointer, misalignment, bad range          */
+    MOQAE_E_WORKSPACE = -2,  /* decode workspace smaller than moqae_decode_workspace_bytes()      */
+    MOQAE_E_ARENA     = -3,  /* packed arena too small (reported through the device status word)  */
+    MOQAE_E_HIP       = -4   /* a HIP call or kernel launch failed                                */
+};
+
+typedef struct {
+    int32_t batch;          /* B                                                               */
+    int32_t n_q_heads;      /* Hq;  Hq / Hkv must be 1, 2, 4 or 8; query head hq reads KV head
+                               hq / (Hq/Hkv)                                                   */
+    int32_t n_kv_heads;     /* Hkv                                                             */
+    int32_t head_dim;       /* D, must be 128                                                  */
+    int32_t chunk;          /* N tokens per chunk: a multiple of 32, 32..1024                  */
+    int32_t group;          /* G elements per quantisation group along D: 32 or 64             */
+    int32_t n_experts;      /* M, 1..8                                                         */
+    int32_t expert_bits[MOQAE_MAX_EXPERTS]; /* B_j in {2,4,8,16}; index order = tie-break order */
+    int32_t freeze_chunks;  /* routing freezing (Sec. 3.4): chunks c < freeze_chunks are never
+                               routed and take the first 16-bit expert; the paper uses 1       */
+} moqae_cfg;
+
+/*
+ * Router, Eq. (1)-(2) of Sec. 3.2, for chunks [chunk_begin, chunk_end) of every
+ * (sequence b, KV head h).  Chunk c covers tokens [c*N, (c+1)*N) of K; token s
+ * of (b, h) starts at K + b*stride_b + h*stride_h + s*stride_s (element
+ * strides, stride_s a multiple of 8, base 16-byte aligned).
+ *   logits = SiLU((x W1) * (x W2)) W3 (+ logit_bias), x = one cached key row;
+ *   token expert = first arg-max of the logits; chunk expert = first arg-max of
+ *   the per-expert token counts.  Evaluated in binary32, sums in index order,
+ *   so the result is reproducible bit for bit.
+ * W1, W2: fp16 [D, M] row-major; W3: fp16 [M, M] row-major (hidden j -> logit k
+ * at W3[j*M+k]); logit_bias: fp32 [M] or NULL (Eq. (1) has none).
+ * Out: expert[(b*Hkv+h)*expert_stride + c] = expert index;
+ *      votes[((b*Hkv+h)*expert_stride + c)*M + k] = token count of expert k
+ *      (all zero for frozen chunks); votes may be NULL.
+ * Entries outside [chunk_begin, chunk_end) are not touched.
+ * Errors: MOQAE_E_INVAL (also when freeze_chunks > 0 and no expert has 16 bits).
+ */
+int moqae_route_chunks(const moqae_cfg *cfg,
+                       const void *K, int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                       int32_t chunk_begin, int32_t chunk_end,
+                       const void *W1, const void *W2, const void *W3,
+                       const float *logit_bias,
+                       uint8_t *expert, int64_t expert_stride,
+                       int32_t *votes,
+                       void *stream);
+
+/*
+ * Quantise and pack chunks [chunk_begin, chunk_end) of every (b, h) of K and V
+ * (same strides for both) at the bit-width of expert[...] (this block's own
+ * decisions, or its routing-sharing leader's, Sec. 3.4).
+ * Blocks are appended to `arena` in (b, h, c) order starting at *arena_used
+ * rounded up to 256 bytes; each block start is 256-byte aligned;
+ * chunk_off[(b*Hkv+h)*off_stride + c] receives the block's byte offset and
+ * *arena_used the new end.  `arena` must be 256-byte aligned.
+ * *status (device int32) must be 0 on entry, otherwise the call is a no-op; if
+ * the blocks do not fit below arena_capacity, or an expert index is >= M,
+ * *status becomes MOQAE_E_ARENA / MOQAE_E_INVAL and nothing else is written
+ * (no arena byte, no offset, *arena_used unchanged).
+ */
+int moqae_quantize_pack(const moqae_cfg *cfg,
+                        const void *K, const void *V,
+                        int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                        int32_t chunk_begin, int32_t chunk_end,
+                        const uint8_t *expert, int64_t expert_stride,
+                        void *arena, uint64_t arena_capacity,
+                        uint64_t *arena_used,
+                        uint64_t *chunk_off, int64_t off_stride,
+                        int32_t *status,
+                        void *stream);
+
+/*
+ * Decode attention for one new token per sequence: for every query head,
+ *   out = softmax(softmax_scale * q K^^T) V^
+ * over the n_chunks packed chunks of its KV head followed by the n_tail FP16
+ * residual rows (Sec. 3.2), with K^, V^ the de-quantised cache.  No mask: the
+ * query attends to every cached token.
+ * q: fp16 [B, Hq, D]; expert / chunk_off: the tables written by the two calls
+ * above, row stride desc_stride (>= n_chunks); K_tail, V_tail: fp16
+ * [B, Hkv, N, D] of which rows [0, n_tail) are valid, 0 <= n_tail < N (may be
+ * NULL when n_tail == 0); n_chunks + n_tail must be > 0.
+ * out: fp32 [B, Hq, D].  workspace: at least moqae_decode_workspace_bytes()
+ * bytes, 256-byte aligned, contents irrelevant on entry (split partials).
+ */
+int moqae_decode_attn(const moqae_cfg *cfg,
+                      const void *q,
+                      const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                      int64_t desc_stride, int32_t n_chunks,
+                      const void *K_tail, const void *V_tail, int32_t n_tail,
+                      float softmax_scale,
+                      float *out,
+                      void *workspace, uint64_t workspace_bytes,
+                      void *stream);
+
+/* Host helpers (no GPU work). */
+uint64_t moqae_chunk_block_bytes(const moqae_cfg *cfg, int32_t bits);            /* K+V block of one chunk; 0 if invalid */
+uint64_t moqae_arena_upper_bound(const moqae_cfg *cfg, int64_t n_chunks_total);  /* all-16-bit worst case + alignment    */
+uint64_t moqae_decode_workspace_bytes(const moqae_cfg *cfg, int32_t n_chunks);   /* 0 if cfg invalid                     */
+const char *moqae_strerror(int code);
+uint32_t moqae_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOQAE_H */

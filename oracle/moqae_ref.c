@@ -395,10 +395,12 @@ void moqae_ref_decode_chunk(const moqae_ref_cfg *cfg, int bits, const uint8_t *b
 }
 
 /* Quantise-and-pack chunks [chunk_begin, chunk_end) of every (b, h).
- * Blocks are laid in (b, h, c) order from *arena_used (each block start is a
- * multiple of 256 bytes); chunk_off receives each block's byte offset.
- * If a block would pass arena_capacity nothing of it is written, *status is
- * set to REF_E_ARENA and the call stops there.                            */
+ * Blocks are laid in (b, h, c) order from *arena_used rounded up to 256 bytes
+ * (each block start is a multiple of 256 bytes); chunk_off receives each
+ * block's byte offset and *arena_used the new end.
+ * *status must be 0 on entry, else the call does nothing.  If the blocks do
+ * not fit below arena_capacity (REF_E_ARENA) or an expert index is out of
+ * range (REF_E_INVAL), *status is set and nothing else is written.        */
 int moqae_quantize_pack_ref(const moqae_ref_cfg *cfg,
                             const uint16_t *K, const uint16_t *V,
                             int64_t stride_b, int64_t stride_h, int64_t stride_s,
@@ -411,19 +413,26 @@ int moqae_quantize_pack_ref(const moqae_ref_cfg *cfg,
     if (!cfg_ok(cfg) || !K || !V || !expert || !arena || !arena_used || !chunk_off || !status) return REF_E_INVAL;
     if (chunk_begin < 0 || chunk_end < chunk_begin) return REF_E_INVAL;
     if (expert_stride_bh < chunk_end || off_stride_bh < chunk_end) return REF_E_INVAL;
+    if (*status != 0) return REF_OK;
     const int N = cfg->chunk;
     const int64_t units = (int64_t)cfg->batch * cfg->n_kv_heads;
     const int64_t nc = chunk_end - chunk_begin;
 
-    /* pass 1: the offset plan, in (b, h, c) order */
+    /* pass 0: does everything fit? */
     uint64_t pos = round_up_256(*arena_used);
     for (int64_t u = 0; u < units; u++) for (int c = chunk_begin; c < chunk_end; c++) {
         int e = expert[u * expert_stride_bh + c];
-        if (e >= cfg->n_experts) return REF_E_INVAL;
-        uint64_t sz = round_up_256(moqae_ref_chunk_block_bytes(cfg, cfg->expert_bits[e]));
-        if (pos + sz > arena_capacity) { *status = REF_E_ARENA; return REF_OK; }
+        if (e >= cfg->n_experts) { *status = REF_E_INVAL; return REF_OK; }
+        pos += round_up_256(moqae_ref_chunk_block_bytes(cfg, cfg->expert_bits[e]));
+    }
+    if (pos > arena_capacity) { *status = REF_E_ARENA; return REF_OK; }
+
+    /* pass 1: the offset plan, in (b, h, c) order */
+    pos = round_up_256(*arena_used);
+    for (int64_t u = 0; u < units; u++) for (int c = chunk_begin; c < chunk_end; c++) {
+        int e = expert[u * expert_stride_bh + c];
         chunk_off[u * off_stride_bh + c] = pos;
-        pos += sz;
+        pos += round_up_256(moqae_ref_chunk_block_bytes(cfg, cfg->expert_bits[e]));
     }
     *arena_used = pos;
 

@@ -1,0 +1,183 @@
+"""Thin ctypes binding of libmoqae.so: argument marshalling only.
+
+Every function takes torch tensors that live on the GPU (or raw device
+pointers) and enqueues the library call on torch's current stream.  There is
+no CPU fallback: if the shared library is missing, importing fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import Optional, Sequence
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoqae.so")
+
+OK, E_INVAL, E_WORKSPACE, E_ARENA, E_HIP = 0, -1, -2, -3, -4
+
+
+class MoqaeError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+class _Cfg(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("chunk", C.c_int32), ("group", C.c_int32),
+                ("n_experts", C.c_int32), ("expert_bits", C.c_int32 * 8),
+                ("freeze_chunks", C.c_int32)]
+
+
+@dataclass
+class Cfg:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int = 128
+    chunk: int = 128
+    group: int = 64
+    expert_bits: Sequence[int] = field(default_factory=lambda: (2, 4, 8, 16))
+    freeze_chunks: int = 1
+
+    def c(self) -> _Cfg:
+        bits = list(self.expert_bits) + [0] * (8 - len(self.expert_bits))
+        return _Cfg(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.chunk,
+                    self.group, len(self.expert_bits), (C.c_int32 * 8)(*bits), self.freeze_chunks)
+
+
+_lib = None
+EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "moqae_chunk_block_bytes",
+           "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version"]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2506_07533_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(_LIB_PATH)
+        vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+        L.moqae_route_chunks.restype = C.c_int
+        L.moqae_route_chunks.argtypes = [C.POINTER(_Cfg), vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp]
+        L.moqae_quantize_pack.restype = C.c_int
+        L.moqae_quantize_pack.argtypes = [C.POINTER(_Cfg), vp, vp, i64, i64, i64, i32, i32, vp, i64, vp, u64, vp,
+                                          vp, i64, vp, vp]
+        L.moqae_decode_attn.restype = C.c_int
+        L.moqae_decode_attn.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i64, i32, vp, vp, i32, C.c_float, vp,
+                                        vp, u64, vp]
+        L.moqae_chunk_block_bytes.restype = u64
+        L.moqae_chunk_block_bytes.argtypes = [C.POINTER(_Cfg), i32]
+        L.moqae_arena_upper_bound.restype = u64
+        L.moqae_arena_upper_bound.argtypes = [C.POINTER(_Cfg), i64]
+        L.moqae_decode_workspace_bytes.restype = u64
+        L.moqae_decode_workspace_bytes.argtypes = [C.POINTER(_Cfg), i32]
+        L.moqae_strerror.restype = C.c_char_p
+        L.moqae_strerror.argtypes = [C.c_int]
+        L.moqae_abi_version.restype = C.c_uint32
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().moqae_strerror(code).decode()
+
+
+def abi_version() -> int:
+    return int(lib().moqae_abi_version())
+
+
+def chunk_block_bytes(cfg: Cfg, bits: int) -> int:
+    return int(lib().moqae_chunk_block_bytes(C.byref(cfg.c()), bits))
+
+
+def arena_upper_bound(cfg: Cfg, n_chunks_total: int) -> int:
+    return int(lib().moqae_arena_upper_bound(C.byref(cfg.c()), n_chunks_total))
+
+
+def decode_workspace_bytes(cfg: Cfg, n_chunks: int) -> int:
+    return int(lib().moqae_decode_workspace_bytes(C.byref(cfg.c()), n_chunks))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MoqaeError(rc, what)
+
+
+def _kv_strides(K: torch.Tensor, cfg: Cfg):
+    assert K.is_cuda and K.dtype == torch.float16 and K.dim() == 4 and K.stride(3) == 1
+    assert K.shape[0] == cfg.batch and K.shape[1] == cfg.n_kv_heads and K.shape[3] == cfg.head_dim
+    return K.stride(0), K.stride(1), K.stride(2)
+
+
+def route_chunks(cfg: Cfg, K: torch.Tensor, chunk_begin: int, chunk_end: int,
+                 W1: torch.Tensor, W2: torch.Tensor, W3: torch.Tensor, bias: Optional[torch.Tensor],
+                 expert: torch.Tensor, votes: Optional[torch.Tensor] = None, token0: int = 0) -> None:
+    """expert: uint8 [B*Hkv, Ccap]; votes: int32 [B*Hkv, Ccap, M] or None.
+    `token0`: K holds tokens token0.. of every sequence (e.g. the FP16 residual buffer when it is
+    flushed as chunk token0 / N); the base pointer is shifted so that chunk indices stay absolute."""
+    sb, sh, ss = _kv_strides(K, cfg)
+    assert K.shape[2] + token0 >= chunk_end * cfg.chunk and chunk_begin * cfg.chunk >= token0
+    assert expert.dtype == torch.uint8 and expert.dim() == 2 and expert.is_contiguous() and expert.is_cuda
+    if votes is not None:
+        assert votes.dtype == torch.int32 and votes.is_contiguous() and votes.shape[:2] == expert.shape
+    for w in (W1, W2, W3):
+        assert w.is_cuda and w.dtype == torch.float16 and w.is_contiguous()
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous()
+    kptr = C.c_void_p(K.data_ptr() - token0 * ss * 2)
+    _check(lib().moqae_route_chunks(C.byref(cfg.c()), kptr, sb, sh, ss, chunk_begin, chunk_end,
+                                    _ptr(W1), _ptr(W2), _ptr(W3), _ptr(bias), _ptr(expert), expert.shape[1],
+                                    _ptr(votes), _stream()), "moqae_route_chunks")
+
+
+def quantize_pack(cfg: Cfg, K: torch.Tensor, V: torch.Tensor, chunk_begin: int, chunk_end: int,
+                  expert: torch.Tensor, arena: torch.Tensor, arena_used: torch.Tensor,
+                  chunk_off: torch.Tensor, status: torch.Tensor, token0: int = 0) -> None:
+    """arena: uint8 [capacity]; arena_used: int64 [1]; chunk_off: int64 [B*Hkv, Ccap]; status: int32 [1]."""
+    sb, sh, ss = _kv_strides(K, cfg)
+    assert _kv_strides(V, cfg) == (sb, sh, ss)
+    assert K.shape[2] + token0 >= chunk_end * cfg.chunk and chunk_begin * cfg.chunk >= token0
+    assert expert.dtype == torch.uint8 and expert.dim() == 2 and expert.is_contiguous()
+    assert chunk_off.dtype == torch.int64 and chunk_off.dim() == 2 and chunk_off.is_contiguous()
+    assert arena.dtype == torch.uint8 and arena.is_contiguous() and arena_used.dtype == torch.int64
+    assert status.dtype == torch.int32
+    shift = token0 * ss * 2
+    _check(lib().moqae_quantize_pack(C.byref(cfg.c()), C.c_void_p(K.data_ptr() - shift), C.c_void_p(V.data_ptr() - shift),
+                                     sb, sh, ss, chunk_begin, chunk_end, _ptr(expert), expert.shape[1],
+                                     _ptr(arena), arena.numel(), _ptr(arena_used), _ptr(chunk_off), chunk_off.shape[1],
+                                     _ptr(status), _stream()), "moqae_quantize_pack")
+
+
+def decode_attn(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_off: Optional[torch.Tensor],
+                expert: Optional[torch.Tensor], n_chunks: int,
+                K_tail: Optional[torch.Tensor], V_tail: Optional[torch.Tensor], n_tail: int,
+                softmax_scale: float, out: torch.Tensor, workspace: torch.Tensor) -> None:
+    """q: fp16 [B, Hq, D]; out: fp32 [B, Hq, D]; workspace: uint8, >= decode_workspace_bytes()."""
+    assert q.is_cuda and q.dtype == torch.float16 and q.is_contiguous()
+    assert q.shape == (cfg.batch, cfg.n_q_heads, cfg.head_dim)
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+    stride = 0
+    if n_chunks > 0:
+        assert expert.dtype == torch.uint8 and chunk_off.dtype == torch.int64
+        assert expert.shape == chunk_off.shape and expert.is_contiguous() and chunk_off.is_contiguous()
+        stride = expert.shape[1]
+    if n_tail > 0:
+        for t in (K_tail, V_tail):
+            assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous()
+            assert t.shape == (cfg.batch, cfg.n_kv_heads, cfg.chunk, cfg.head_dim)
+    _check(lib().moqae_decode_attn(C.byref(cfg.c()), _ptr(q), _ptr(arena), _ptr(chunk_off), _ptr(expert), stride,
+                                   n_chunks, _ptr(K_tail), _ptr(V_tail), n_tail, float(softmax_scale), _ptr(out),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "moqae_decode_attn")

@@ -1,0 +1,188 @@
+// C-ABI entry points of libmoqae: argument validation on the host, then kernel launches on the
+// caller's stream.  No allocation and no synchronisation happen here.
+#include "../../include/moqae.h"
+#include "moqae_dev.hpp"
+#include "moqae_kernels.hpp"
+
+using namespace moqae;
+
+namespace {
+
+bool bits_ok(int b) { return b == 2 || b == 4 || b == 8 || b == 16; }
+
+bool cfg_ok(const moqae_cfg *c) {
+    if (!c) return false;
+    if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1) return false;
+    if (c->n_q_heads % c->n_kv_heads) return false;
+    const int rep = c->n_q_heads / c->n_kv_heads;
+    if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return false;
+    if ((int64_t)c->batch * c->n_kv_heads > 65535) return false;          // grid.y
+    if (c->head_dim != kD) return false;
+    if (c->group != 32 && c->group != 64) return false;
+    if (c->chunk < 32 || c->chunk > 256 || c->chunk % 32) return false;
+    if (c->n_experts < 1 || c->n_experts > MOQAE_MAX_EXPERTS) return false;
+    for (int j = 0; j < c->n_experts; j++) if (!bits_ok(c->expert_bits[j])) return false;
+    if (c->freeze_chunks < 0) return false;
+    return true;
+}
+
+int first_16bit(const moqae_cfg *c) {
+    for (int j = 0; j < c->n_experts; j++) if (c->expert_bits[j] == 16) return j;
+    return -1;
+}
+
+bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool strides_ok(const moqae_cfg *c, int64_t sb, int64_t sh, int64_t ss) {
+    (void)c;
+    return ss >= kD && ss % 8 == 0 && sb % 8 == 0 && sh % 8 == 0 && sb >= 0 && sh >= 0;
+}
+
+int cu_count() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+        else cus = 256;                                                   // MI355X
+    }
+    return cus;
+}
+
+// Splits of one (b, h) row: enough workgroups to fill the chip once (4 workgroups of 4
+// wavefronts per CU), never more than one per chunk.
+int choose_splits(const moqae_cfg *c, int n_chunks) {
+    const int64_t rows = (int64_t)c->batch * c->n_kv_heads;
+    const int64_t target = (int64_t)cu_count() * 4;
+    int64_t s = target / rows;
+    if (s > n_chunks) s = n_chunks;
+    if (s < 1) s = 1;
+    if (s > 1024) s = 1024;
+    return (int)s;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t moqae_abi_version(void) { return MOQAE_ABI_VERSION; }
+
+const char *moqae_strerror(int code) {
+    switch (code) {
+        case MOQAE_OK: return "ok";
+        case MOQAE_E_INVAL: return "invalid argument or configuration";
+        case MOQAE_E_WORKSPACE: return "decode workspace too small";
+        case MOQAE_E_ARENA: return "packed arena too small";
+        case MOQAE_E_HIP: return "HIP call or kernel launch failed";
+    }
+    return "unknown error";
+}
+
+uint64_t moqae_chunk_block_bytes(const moqae_cfg *cfg, int32_t bits) {
+    if (!cfg_ok(cfg) || !bits_ok(bits)) return 0;
+    return block_bytes(cfg->chunk, cfg->group, bits);
+}
+
+uint64_t moqae_arena_upper_bound(const moqae_cfg *cfg, int64_t n_chunks_total) {
+    if (!cfg_ok(cfg) || n_chunks_total < 0) return 0;
+    return 256u + (uint64_t)n_chunks_total * ((block_bytes(cfg->chunk, cfg->group, 16) + 255u) & ~255ull);
+}
+
+uint64_t moqae_decode_workspace_bytes(const moqae_cfg *cfg, int32_t n_chunks) {
+    if (!cfg_ok(cfg) || n_chunks < 0) return 0;
+    const uint64_t rows = (uint64_t)cfg->batch * cfg->n_q_heads;
+    return rows * (uint64_t)choose_splits(cfg, n_chunks) * kAttnWaves * (kD + 2) * sizeof(float);
+}
+
+int moqae_route_chunks(const moqae_cfg *cfg,
+                       const void *K, int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                       int32_t chunk_begin, int32_t chunk_end,
+                       const void *W1, const void *W2, const void *W3,
+                       const float *logit_bias,
+                       uint8_t *expert, int64_t expert_stride,
+                       int32_t *votes,
+                       void *stream) {
+    if (!cfg_ok(cfg) || !K || !W1 || !W2 || !W3 || !expert) return MOQAE_E_INVAL;
+    if (chunk_begin < 0 || chunk_end < chunk_begin || expert_stride < chunk_end) return MOQAE_E_INVAL;
+    if (!strides_ok(cfg, stride_b, stride_h, stride_s) || !aligned(K, 16)) return MOQAE_E_INVAL;
+    if (!aligned(W1, 4) || !aligned(W2, 4) || !aligned(W3, 2)) return MOQAE_E_INVAL;
+    const int e16 = first_16bit(cfg);
+    if (cfg->freeze_chunks > 0 && e16 < 0) return MOQAE_E_INVAL;
+    if (chunk_end == chunk_begin) return MOQAE_OK;
+
+    RouteArgs a;
+    a.K = static_cast<const uint16_t *>(K); a.stride_b = stride_b; a.stride_h = stride_h; a.stride_s = stride_s;
+    a.W1 = static_cast<const uint16_t *>(W1); a.W2 = static_cast<const uint16_t *>(W2);
+    a.W3 = static_cast<const uint16_t *>(W3); a.bias = logit_bias;
+    a.expert = expert; a.expert_stride = expert_stride; a.votes = votes;
+    a.chunk_begin = chunk_begin; a.N = cfg->chunk; a.Hkv = cfg->n_kv_heads;
+    a.freeze_chunks = cfg->freeze_chunks; a.e16 = e16 < 0 ? 0 : e16;
+    hipError_t e = launch_route(a, cfg->n_experts, chunk_end - chunk_begin, cfg->batch * cfg->n_kv_heads,
+                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+int moqae_quantize_pack(const moqae_cfg *cfg,
+                        const void *K, const void *V,
+                        int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                        int32_t chunk_begin, int32_t chunk_end,
+                        const uint8_t *expert, int64_t expert_stride,
+                        void *arena, uint64_t arena_capacity,
+                        uint64_t *arena_used,
+                        uint64_t *chunk_off, int64_t off_stride,
+                        int32_t *status,
+                        void *stream) {
+    if (!cfg_ok(cfg) || !K || !V || !expert || !arena || !arena_used || !chunk_off || !status) return MOQAE_E_INVAL;
+    if (chunk_begin < 0 || chunk_end < chunk_begin) return MOQAE_E_INVAL;
+    if (expert_stride < chunk_end || off_stride < chunk_end) return MOQAE_E_INVAL;
+    if (!strides_ok(cfg, stride_b, stride_h, stride_s) || !aligned(K, 16) || !aligned(V, 16)) return MOQAE_E_INVAL;
+    if (!aligned(arena, 256) || !aligned(arena_used, 8) || !aligned(chunk_off, 8) || !aligned(status, 4)) return MOQAE_E_INVAL;
+    if (chunk_end == chunk_begin) return MOQAE_OK;
+
+    PackArgs a;
+    a.K = static_cast<const uint16_t *>(K); a.V = static_cast<const uint16_t *>(V);
+    a.stride_b = stride_b; a.stride_h = stride_h; a.stride_s = stride_s;
+    a.expert = expert; a.expert_stride = expert_stride;
+    a.arena = static_cast<uint8_t *>(arena); a.capacity = arena_capacity; a.arena_used = arena_used;
+    a.chunk_off = chunk_off; a.off_stride = off_stride; a.status = status;
+    a.chunk_begin = chunk_begin; a.n_chunks = chunk_end - chunk_begin;
+    a.BH = cfg->batch * cfg->n_kv_heads; a.N = cfg->chunk; a.G = cfg->group; a.Hkv = cfg->n_kv_heads;
+    a.M = cfg->n_experts;
+    for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;
+    hipError_t e = launch_pack(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+int moqae_decode_attn(const moqae_cfg *cfg,
+                      const void *q,
+                      const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                      int64_t desc_stride, int32_t n_chunks,
+                      const void *K_tail, const void *V_tail, int32_t n_tail,
+                      float softmax_scale,
+                      float *out,
+                      void *workspace, uint64_t workspace_bytes,
+                      void *stream) {
+    if (!cfg_ok(cfg) || !q || !out || !workspace) return MOQAE_E_INVAL;
+    if (n_chunks < 0 || n_tail < 0 || n_tail >= cfg->chunk || n_chunks + n_tail <= 0) return MOQAE_E_INVAL;
+    if (n_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride < n_chunks)) return MOQAE_E_INVAL;
+    if (n_tail > 0 && (!K_tail || !V_tail)) return MOQAE_E_INVAL;
+    if (!aligned(q, 4) || !aligned(out, 8) || !aligned(workspace, 256)) return MOQAE_E_INVAL;
+    if (n_chunks > 0 && (!aligned(arena, 256) || !aligned(chunk_off, 8))) return MOQAE_E_INVAL;
+    if (n_tail > 0 && (!aligned(K_tail, 16) || !aligned(V_tail, 16))) return MOQAE_E_INVAL;
+    if (workspace_bytes < moqae_decode_workspace_bytes(cfg, n_chunks)) return MOQAE_E_WORKSPACE;
+
+    AttnArgs a;
+    a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
+    a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
+    a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
+    a.part = static_cast<float *>(workspace); a.out = out;
+    a.scale_log2 = softmax_scale * 1.4426950408889634f;
+    a.n_chunks = n_chunks; a.n_tail = n_tail; a.n_split = choose_splits(cfg, n_chunks);
+    a.N = cfg->chunk; a.G = cfg->group; a.Hkv = cfg->n_kv_heads; a.rep = cfg->n_q_heads / cfg->n_kv_heads;
+    a.BH = cfg->batch * cfg->n_kv_heads;
+    for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;
+    hipError_t e = launch_attn(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Device-side helpers shared by the three kernels of libmoqae (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moqae {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kD = 128;          // head_dim (the only one supported)
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h16);
+}
+__device__ __forceinline__ uint32_t float_to_half_bits(float f) {      // round-to-nearest-even
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+__device__ __forceinline__ half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
+
+// D(f32) = a.lo*b.lo + a.hi*b.hi + c  (v_dot2_f32_f16; fp16 subnormal inputs are kept)
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2(as_half2(a), as_half2(b), c, false);
+}
+
+// ---- DPP cross-lane moves (all lanes active) -------------------------------------------
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+        __builtin_bit_cast(int, x), __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, 0xF, 0xF, false);
+}
+constexpr int DPP_XOR1 = 0xB1;           // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;           // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;   // lane i <-> 7-i inside 8 lanes
+constexpr int DPP_MIRROR = 0x140;        // lane i <-> 15-i inside a row of 16
+constexpr int DPP_BCAST15 = 0x142;       // lane 15 of a row -> the next row
+constexpr int DPP_BCAST31 = 0x143;       // lane 31 -> rows 2, 3
+
+// Sum over aligned groups of LANES consecutive lanes (2, 4, 8 or 16); every lane gets the sum.
+template <int LANES>
+__device__ __forceinline__ float group_sum(float x) {
+    if constexpr (LANES >= 2)  x += dpp_f<DPP_XOR1>(x);
+    if constexpr (LANES >= 4)  x += dpp_f<DPP_XOR2>(x);
+    if constexpr (LANES >= 8)  x += dpp_f<DPP_HALF_MIRROR>(x);
+    if constexpr (LANES >= 16) x += dpp_f<DPP_MIRROR>(x);
+    return x;
+}
+template <int LANES>
+__device__ __forceinline__ float group_min(float x) {
+    if constexpr (LANES >= 2)  x = fminf(x, dpp_f<DPP_XOR1>(x));
+    if constexpr (LANES >= 4)  x = fminf(x, dpp_f<DPP_XOR2>(x));
+    if constexpr (LANES >= 8)  x = fminf(x, dpp_f<DPP_HALF_MIRROR>(x));
+    if constexpr (LANES >= 16) x = fminf(x, dpp_f<DPP_MIRROR>(x));
+    return x;
+}
+template <int LANES>
+__device__ __forceinline__ float group_max(float x) {
+    if constexpr (LANES >= 2)  x = fmaxf(x, dpp_f<DPP_XOR1>(x));
+    if constexpr (LANES >= 4)  x = fmaxf(x, dpp_f<DPP_XOR2>(x));
+    if constexpr (LANES >= 8)  x = fmaxf(x, dpp_f<DPP_HALF_MIRROR>(x));
+    if constexpr (LANES >= 16) x = fmaxf(x, dpp_f<DPP_MIRROR>(x));
+    return x;
+}
+// Maximum over the whole wavefront, returned wave-uniform.
+__device__ __forceinline__ float wave_max(float x) {
+    x = group_max<16>(x);
+    x = fmaxf(x, dpp_f<DPP_BCAST15, 0xA>(x));
+    x = fmaxf(x, dpp_f<DPP_BCAST31, 0xC>(x));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Bytes of one chunk block (K and V) at bit-width b.
+__host__ __device__ inline uint64_t block_bytes(int N, int G, int b) {
+    return b == 16 ? (uint64_t)N * kD * 4u
+                   : 2u * ((uint64_t)N * kD * (uint64_t)b / 8u + (uint64_t)N * (kD / G) * 4u);
+}
+
+}  // namespace moqae

@@ -1,0 +1,272 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Routing decisions, vote counts, offsets and packed bytes must be bit-exact; attention must
+stay within 2e-3 max-norm relative error per output row against the fp64 oracle.
+"""
+import dataclasses
+import math
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-case] {request.node.nodeid}", file=sys.stderr, flush=True)
+    yield
+
+
+@pytest.fixture(scope="module")
+def mq():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2506_07533_amd import binding
+    binding.lib()
+    return binding
+
+
+def _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, freeze):
+    return (mq.Cfg(B, Hq, Hkv, 128, N, G, bits, freeze), ref.RefCfg(B, Hq, Hkv, 128, N, G, bits, freeze))
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _rand_kv(rng, B, Hkv, S, outliers=True):
+    K = rng.standard_normal((B, Hkv, S, 128), dtype=np.float32)
+    if outliers:
+        for u in range(B * Hkv):
+            K[u // Hkv, u % Hkv][:, rng.choice(128, 4, replace=False)] *= 10
+    V = rng.standard_normal((B, Hkv, S, 128), dtype=np.float32)
+    return K.astype(np.float16), V.astype(np.float16)
+
+
+# ----------------------------------------------------------------------------------------------
+# routing
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,Hkv,N,C,M,freeze,std,use_bias", [
+    (1, 8, 64, 32, 4, 1, 0.02, False),      # the tiny workload's shape
+    (2, 3, 32, 5, 3, 0, 0.3, True),
+    (1, 2, 128, 7, 4, 2, 0.3, False),
+    (1, 1, 256, 3, 8, 1, 0.2, True),
+    (1, 2, 96, 4, 1, 0, 0.3, False),        # one expert; chunk not a multiple of 64
+    (2, 2, 160, 3, 5, 1, 0.5, False),       # two LDS slabs with a ragged second one
+    (1, 4, 128, 6, 2, 0, 1.0, True),
+])
+def test_route_bit_exact(mq, ref, B, Hkv, N, C, M, freeze, std, use_bias):
+    rng = np.random.default_rng(N * 100 + M)
+    bits = ([16, 2, 4, 8, 2, 4, 8, 16])[:M]
+    cfg, rcfg = _cfgs(mq, ref, B, Hkv, Hkv, N, 64, bits, freeze)
+    S = C * N + 11
+    K, _ = _rand_kv(rng, B, Hkv, S)
+    W1 = (rng.standard_normal((128, M)) * std).astype(np.float16)
+    W2 = (rng.standard_normal((128, M)) * std).astype(np.float16)
+    W3 = (rng.standard_normal((M, M)) * max(std, 0.2)).astype(np.float16)
+    bias = (rng.standard_normal(M) * 0.05).astype(np.float32) if use_bias else None
+    e_ref, v_ref = ref.route_chunks(rcfg, K, 0, C, W1, W2, W3, bias)
+    expert = torch.full((B * Hkv, C), 255, dtype=torch.uint8, device="cuda")
+    votes = torch.full((B * Hkv, C, M), -1, dtype=torch.int32, device="cuda")
+    mq.route_chunks(cfg, _dev(K), 0, C, _dev(W1), _dev(W2), _dev(W3), None if bias is None else _dev(bias), expert, votes)
+    torch.cuda.synchronize()
+    assert np.array_equal(votes.cpu().numpy(), v_ref)
+    assert np.array_equal(expert.cpu().numpy(), e_ref)
+    # sub-range call without votes leaves the other entries alone
+    if C >= 3:
+        e2 = torch.full((B * Hkv, C), 255, dtype=torch.uint8, device="cuda")
+        mq.route_chunks(cfg, _dev(K), C - 2, C - 1, _dev(W1), _dev(W2), _dev(W3), None if bias is None else _dev(bias), e2, None)
+        e2 = e2.cpu().numpy()
+        assert np.array_equal(e2[:, C - 2], e_ref[:, C - 2]) and (np.delete(e2, C - 2, 1) == 255).all()
+
+
+def test_route_strided_and_ties(mq, ref):
+    """Keys stored with a padded token stride; all-zero weights (every logit ties -> expert 0)."""
+    rng = np.random.default_rng(5)
+    B, Hkv, N, C, M = 1, 2, 64, 4, 4
+    cfg, rcfg = _cfgs(mq, ref, B, Hkv, Hkv, N, 32, (2, 4, 8, 16), 0)
+    big = rng.standard_normal((B, Hkv, C * N, 256), dtype=np.float32).astype(np.float16)
+    Kd = _dev(big)[..., :128]                                    # token stride 256 elements
+    Kh = big[..., :128]
+    W = [(rng.standard_normal(s) * 0.3).astype(np.float16) for s in [(128, M), (128, M), (M, M)]]
+    e_ref, v_ref = ref.route_chunks(rcfg, Kh, 0, C, *W)
+    expert = torch.zeros((B * Hkv, C), dtype=torch.uint8, device="cuda")
+    votes = torch.zeros((B * Hkv, C, M), dtype=torch.int32, device="cuda")
+    mq.route_chunks(cfg, Kd, 0, C, *[_dev(w) for w in W], None, expert, votes)
+    assert np.array_equal(votes.cpu().numpy(), v_ref) and np.array_equal(expert.cpu().numpy(), e_ref)
+    Z = [np.zeros(s, np.float16) for s in [(128, M), (128, M), (M, M)]]
+    mq.route_chunks(cfg, Kd, 0, C, *[_dev(w) for w in Z], None, expert, votes)
+    assert (expert.cpu().numpy() == 0).all() and (votes.cpu().numpy()[..., 0] == N).all()
+
+
+# ----------------------------------------------------------------------------------------------
+# quantise + pack
+# ----------------------------------------------------------------------------------------------
+
+def _pack_both(mq, ref, cfg, rcfg, K, V, c0, c1, expert, start=0, slack=0):
+    BH, Ccap = expert.shape
+    cap = mq.arena_upper_bound(cfg, BH * (c1 - c0)) + ((start + 255) // 256) * 256 + slack
+    arena_ref = np.zeros(cap, np.uint8); used_ref = np.array([start], np.uint64); off_ref = np.zeros((BH, Ccap), np.uint64)
+    st_ref = ref.quantize_pack(rcfg, K, V, c0, c1, expert, arena_ref, used_ref, off_ref)
+    arena = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+    used = torch.tensor([start], dtype=torch.int64, device="cuda")
+    off = torch.zeros((BH, Ccap), dtype=torch.int64, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    mq.quantize_pack(cfg, _dev(K), _dev(V), c0, c1, _dev(expert), arena, used, off, status)
+    torch.cuda.synchronize()
+    return (arena, used, off, status), (arena_ref, used_ref, off_ref, st_ref)
+
+
+@pytest.mark.parametrize("B,Hkv,N,G,C", [(1, 8, 64, 32, 32), (2, 2, 128, 64, 9), (1, 3, 32, 32, 6),
+                                         (1, 2, 256, 64, 5), (1, 1, 96, 32, 8), (1, 2, 32, 64, 7)])
+def test_pack_bit_exact(mq, ref, B, Hkv, N, G, C):
+    rng = np.random.default_rng(N + G + C)
+    cfg, rcfg = _cfgs(mq, ref, B, Hkv, Hkv, N, G, (2, 4, 8, 16), 1)
+    K, V = _rand_kv(rng, B, Hkv, C * N + 5)
+    # adversarial groups: constants, zeros of both signs, subnormals, huge range, exact ties
+    K[0, 0, 0, :64] = 3.25; K[0, 0, 1, :32] = 0.0; K[0, 0, 1, 5] = -0.0
+    K[0, 0, 2, :64] = (rng.standard_normal(64) * 1e-6).astype(np.float16)
+    K[0, 0, 3, 0] = 65504; K[0, 0, 3, 1] = -65504
+    K[0, 0, 4, :64] = np.arange(64) * 0.5
+    V[0, 0, 0] = K[0, 0, 4]; V[0, 0, 1, :32] = -7.0
+    expert = rng.integers(0, 4, (B * Hkv, C)).astype(np.uint8)
+    expert[:, 0] = np.arange(B * Hkv) % 4                         # every bit-width sees the adversarial rows
+    (arena, used, off, status), (arena_ref, used_ref, off_ref, st_ref) = _pack_both(mq, ref, cfg, rcfg, K, V, 0, C, expert, start=300)
+    assert st_ref == 0 and int(status.item()) == 0
+    assert int(used.item()) == int(used_ref[0])
+    assert np.array_equal(off.cpu().numpy().astype(np.uint64), off_ref)
+    got = arena.cpu().numpy()
+    bad = np.nonzero(got != arena_ref)[0]
+    assert bad.size == 0, f"{bad.size} bytes differ, first at {bad[:5]}"
+
+
+def test_pack_subrange_append_and_status(mq, ref):
+    """Chunks appended by a second call land after the first; capacity and bad ids set the status word."""
+    rng = np.random.default_rng(77)
+    B, Hkv, N, G, C = 1, 3, 64, 64, 6
+    cfg, rcfg = _cfgs(mq, ref, B, Hkv, Hkv, N, G, (2, 4, 8, 16), 1)
+    K, V = _rand_kv(rng, B, Hkv, C * N)
+    expert = rng.integers(0, 4, (B * Hkv, C)).astype(np.uint8)
+    cap = mq.arena_upper_bound(cfg, B * Hkv * C)
+    arena_ref = np.zeros(cap, np.uint8); used_ref = np.zeros(1, np.uint64); off_ref = np.zeros((B * Hkv, C), np.uint64)
+    arena = torch.zeros(cap, dtype=torch.uint8, device="cuda"); used = torch.zeros(1, dtype=torch.int64, device="cuda")
+    off = torch.zeros((B * Hkv, C), dtype=torch.int64, device="cuda"); status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    Kd, Vd, ed = _dev(K), _dev(V), _dev(expert)
+    for c0, c1 in [(0, 4), (4, 5), (5, 6)]:
+        assert ref.quantize_pack(rcfg, K, V, c0, c1, expert, arena_ref, used_ref, off_ref) == 0
+        mq.quantize_pack(cfg, Kd, Vd, c0, c1, ed, arena, used, off, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0 and int(used.item()) == int(used_ref[0])
+    assert np.array_equal(off.cpu().numpy().astype(np.uint64), off_ref)
+    assert np.array_equal(arena.cpu().numpy(), arena_ref)
+    # capacity exceeded: status -3, nothing written
+    small = torch.zeros(int(used_ref[0]) - 256, dtype=torch.uint8, device="cuda")
+    used2 = torch.zeros(1, dtype=torch.int64, device="cuda"); off2 = torch.full((B * Hkv, C), 77, dtype=torch.int64, device="cuda")
+    mq.quantize_pack(cfg, Kd, Vd, 0, C, ed, small, used2, off2, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == mq.E_ARENA and int(used2.item()) == 0
+    assert (off2 == 77).all().item() and not small.any().item()
+    # sticky status: the next call is a no-op
+    mq.quantize_pack(cfg, Kd, Vd, 0, C, ed, arena, used2, off2, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == mq.E_ARENA and int(used2.item()) == 0
+    # an expert index >= M
+    bad = expert.copy(); bad[1, 2] = 4
+    status.zero_()
+    mq.quantize_pack(cfg, Kd, Vd, 0, C, _dev(bad), arena, used2, off2, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == mq.E_INVAL and int(used2.item()) == 0
+
+
+# ----------------------------------------------------------------------------------------------
+# decode attention
+# ----------------------------------------------------------------------------------------------
+
+def _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, bits, seed, scale=None, expert=None, freeze=1):
+    rng = np.random.default_rng(seed)
+    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, freeze)
+    S = C * N + T
+    K, V = _rand_kv(rng, B, Hkv, max(S, 1))
+    q = rng.standard_normal((B, Hq, 128), dtype=np.float32).astype(np.float16)
+    if expert is None:
+        expert = rng.integers(0, len(bits), (B * Hkv, max(C, 1))).astype(np.uint8)
+    scale = 1 / math.sqrt(128) if scale is None else scale
+    Kt = np.zeros((B, Hkv, N, 128), np.float16); Vt = np.zeros_like(Kt)
+    Kt[:, :, :T] = K[:, :, C * N:C * N + T]; Vt[:, :, :T] = V[:, :, C * N:C * N + T]
+    # rows past n_tail hold junk that must not leak into the result
+    Kt[:, :, T:] = np.float16(np.nan); Vt[:, :, T:] = np.float16(np.inf)
+    if C > 0:
+        (arena, used, off, status), (arena_ref, used_ref, off_ref, st_ref) = _pack_both(mq, ref, cfg, rcfg, K, V, 0, C, expert)
+        assert np.array_equal(arena.cpu().numpy(), arena_ref)
+        ed = _dev(expert)
+    else:
+        arena = off = ed = None; arena_ref = off_ref = None
+    o_ref = ref.decode_attn(rcfg, q, arena_ref, off_ref, expert if C else None, C, Kt, Vt, T, scale)
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(mq.decode_workspace_bytes(cfg, C), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                                # workspace contents must not matter
+    mq.decode_attn(cfg, _dev(q), arena, off, ed, C, _dev(Kt) if T else None, _dev(Vt) if T else None, T, scale, out, ws)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(o).all()
+    err = np.abs(o - o_ref).max(-1) / np.abs(o_ref).max(-1)
+    return err.max()
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,G,C,T", [
+    (1, 8, 8, 64, 32, 32, 0),        # tiny workload shape
+    (1, 8, 8, 64, 32, 9, 13),
+    (2, 4, 4, 128, 64, 20, 1),
+    (1, 8, 2, 128, 64, 33, 127),     # GQA x4, long tail
+    (1, 4, 2, 256, 64, 7, 200),      # GQA x2
+    (1, 8, 1, 32, 32, 40, 31),       # GQA x8, smallest chunk
+    (2, 2, 2, 32, 64, 3, 0),
+    (1, 2, 2, 96, 64, 11, 50),
+    (1, 1, 1, 128, 64, 600, 5),      # more chunks than splits*64: several descriptor batches
+])
+def test_attention_mixed_bits(mq, ref, B, Hq, Hkv, N, G, C, T):
+    err = _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, (2, 4, 8, 16), seed=C * 7 + T)
+    assert err <= ATTN_TOL, err
+
+
+@pytest.mark.parametrize("bits", [(2,), (4,), (8,), (16,)])
+@pytest.mark.parametrize("N,G,rep", [(128, 64, 1), (64, 32, 4), (32, 32, 1), (256, 64, 2)])
+def test_attention_single_bit_width(mq, ref, bits, N, G, rep):
+    err = _attn_case(mq, ref, 1, 2 * rep, 2, N, G, 12, 17, bits, seed=bits[0] + N, freeze=0)
+    assert err <= ATTN_TOL, err
+
+
+def test_attention_degenerate_cases(mq, ref):
+    # residual rows only (no packed chunk), down to a single cached token
+    assert _attn_case(mq, ref, 1, 4, 2, 64, 32, 0, 1, (2, 16), seed=1) <= ATTN_TOL
+    assert _attn_case(mq, ref, 2, 2, 2, 128, 64, 0, 97, (2, 16), seed=2) <= ATTN_TOL
+    # one chunk, no residual
+    assert _attn_case(mq, ref, 1, 2, 2, 32, 32, 1, 0, (4, 16), seed=3) <= ATTN_TOL
+    # a sharp softmax (one key dominates) and a flat one
+    assert _attn_case(mq, ref, 1, 2, 2, 64, 64, 8, 3, (2, 4, 8, 16), seed=4, scale=3.0) <= ATTN_TOL
+    assert _attn_case(mq, ref, 1, 2, 2, 64, 64, 8, 3, (2, 4, 8, 16), seed=5, scale=0.0) <= ATTN_TOL
+
+
+def test_argument_errors(mq):
+    cfg = mq.Cfg(1, 2, 2, 128, 64, 32, (2, 4, 8, 16), 1)
+    q = torch.zeros((1, 2, 128), dtype=torch.float16, device="cuda")
+    out = torch.zeros((1, 2, 128), dtype=torch.float32, device="cuda")
+    ws = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    Kt = torch.zeros((1, 2, 64, 128), dtype=torch.float16, device="cuda")
+    with pytest.raises(mq.MoqaeError) as e:
+        mq.decode_attn(cfg, q, None, None, None, 0, Kt, Kt, 5, 0.1, out, ws)
+    assert e.value.code == mq.E_WORKSPACE
+    bad = mq.Cfg(1, 3, 2, 128, 64, 32, (2, 4, 8, 16), 1)                 # Hq not a multiple of Hkv
+    assert mq.decode_workspace_bytes(bad, 4) == 0 and mq.chunk_block_bytes(bad, 2) == 0
+    nofp16 = mq.Cfg(1, 2, 2, 128, 64, 32, (2, 4, 8), 1)                  # freezing needs a 16-bit expert
+    W = torch.zeros((128, 3), dtype=torch.float16, device="cuda")
+    with pytest.raises(mq.MoqaeError) as e:
+        mq.route_chunks(nofp16, Kt, 0, 1, W, W, torch.zeros((3, 3), dtype=torch.float16, device="cuda"), None,
+                        torch.zeros((2, 1), dtype=torch.uint8, device="cuda"))
+    assert e.value.code == mq.E_INVAL

@@ -343,11 +343,19 @@ def test_block_sizes_offsets_and_capacity(ref):
         bits = cfg.expert_bits[expert[u, c]]
         blk = ref.pack_chunk(cfg, bits, K[b, h, c * 128:(c + 1) * 128], V[b, h, c * 128:(c + 1) * 128])
         assert np.array_equal(arena[int(off[u, c]): int(off[u, c]) + blk.size], blk)
-    # too small an arena: status set, counter untouched
+    # too small an arena: status set, nothing else written
     used2 = np.array([0], np.uint64)
     small = np.zeros(int(sizes.sum()) - 256, np.uint8)
-    assert ref.quantize_pack(cfg, K, V, 0, C, expert, small, used2, np.zeros((6, C), np.uint64)) == -3
-    assert used2[0] == 0
+    off2 = np.full((6, C), 77, np.uint64)
+    st = np.zeros(1, np.int32)
+    assert ref.quantize_pack(cfg, K, V, 0, C, expert, small, used2, off2, st) == -3
+    assert used2[0] == 0 and (off2 == 77).all() and not small.any()
+    # a non-zero status on entry makes the call a no-op
+    assert ref.quantize_pack(cfg, K, V, 0, C, expert, arena, used2, off2, st) == -3 and used2[0] == 0
+    # an expert index >= M is reported through the status word
+    bad = expert.copy(); bad[2, 1] = 4
+    st[0] = 0
+    assert ref.quantize_pack(cfg, K, V, 0, C, bad, arena, used2, off2, st) == -1 and used2[0] == 0
 
 
 def test_sanity_numbers_from_the_paper():
