@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoQAE hot path on one MI355X.
+
+A step is one pass of the whole path over one layer of the workload: route every chunk
+(Eq. (1)-(2)), quantise-and-pack K and V at the routed bit-widths, and one decode-attention
+call over the packed cache.  Inputs (fp16 K, V, q, router weights) are resident in HBM before
+the timed region.  The decode call of step i reads the arena packed in step i-1 (two arenas
+alternate), so the 256 MB last-level cache cannot hold what it reads.
+
+Prints ONE JSON line: metric = decode-attention HBM GB/s (algorithmic packed bytes / time of
+the decode call), plus route+pack chunks/s, a roofline object per kernel and the CPU oracle
+timed on a sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama13b_128k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-only", action="store_true",
+                    help="profiling aid: after set-up run only decode calls in the timed loop")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2506_07533_amd import binding as mq, synth
+
+    w = synth.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    BH, C, T, M = w.batch * w.n_kv_heads, w.n_chunks, w.n_tail, len(w.expert_bits)
+    cfg = mq.Cfg(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.chunk, w.group, w.expert_bits, w.freeze_chunks)
+
+    t0 = time.time()
+    d = synth.make_workload(w)
+    log(f"[bench] synthetic {w.name}: K,V {d['K'].shape} generated in {time.time() - t0:.1f}s")
+    K = torch.from_numpy(d["K"]).to(dev); V = torch.from_numpy(d["V"]).to(dev)
+    W1, W2, W3 = (torch.from_numpy(d[k]).to(dev) for k in ("W1", "W2", "W3"))
+    q = torch.from_numpy(d["q"]).to(dev)
+    Kt = torch.zeros((w.batch, w.n_kv_heads, w.chunk, w.head_dim), dtype=torch.float16, device=dev)
+    Vt = torch.zeros_like(Kt)
+    if T:
+        Kt[:, :, :T] = K[:, :, C * w.chunk:]; Vt[:, :, :T] = V[:, :, C * w.chunk:]
+
+    expert = torch.zeros((BH, C), dtype=torch.uint8, device=dev)
+    votes = torch.zeros((BH, C, M), dtype=torch.int32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    # first pass sizes the arenas (realised mix), then two arenas alternate
+    mq.route_chunks(cfg, K, 0, C, W1, W2, W3, None, expert, votes)
+    torch.cuda.synchronize()
+    e_host = expert.cpu().numpy()
+    bits_of = np.array(w.expert_bits)[e_host]
+    blk = {b: mq.chunk_block_bytes(cfg, b) for b in w.expert_bits}
+    packed_bytes = int(sum(blk[b] * int((bits_of == b).sum()) for b in w.expert_bits))
+    mix = {str(b): round(float((bits_of == b).mean()), 4) for b in w.expert_bits}
+    cap = packed_bytes + 4096
+    arenas = [torch.zeros(cap, dtype=torch.uint8, device=dev) for _ in range(2)]
+    useds = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(2)]
+    offs = [torch.zeros((BH, C), dtype=torch.int64, device=dev) for _ in range(2)]
+    out = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device=dev)
+    ws = torch.zeros(mq.decode_workspace_bytes(cfg, C), dtype=torch.uint8, device=dev)
+    scale = 1.0 / float(np.sqrt(w.head_dim))
+
+    def step(i, ev=None):
+        a = i & 1
+        useds[a].zero_()
+        if ev: ev[0].record()
+        if not args.decode_only:
+            mq.route_chunks(cfg, K, 0, C, W1, W2, W3, None, expert, votes)
+        if ev: ev[1].record()
+        if not args.decode_only:
+            mq.quantize_pack(cfg, K, V, 0, C, expert, arenas[a], useds[a], offs[a], status)
+        if ev: ev[2].record()
+        mq.decode_attn(cfg, q, arenas[a ^ 1], offs[a ^ 1], expert, C, Kt if T else None, Vt if T else None, T,
+                       scale, out, ws)
+        if ev: ev[3].record()
+
+    for a in range(2):                                   # both arenas packed before anything is timed
+        useds[a].zero_()
+        mq.quantize_pack(cfg, K, V, 0, C, expert, arenas[a], useds[a], offs[a], status)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0, "arena overflow"
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, evs[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+    assert int(status.item()) == 0, "arena overflow"
+    t_route = np.array([e[0].elapsed_time(e[1]) for e in evs])
+    t_pack = np.array([e[1].elapsed_time(e[2]) for e in evs])
+    t_attn = np.array([e[2].elapsed_time(e[3]) for e in evs])
+    ms_per_step = wall_ms / args.steps
+
+    n_units = BH * C
+    kv_bytes = n_units * w.chunk * w.head_dim * 2
+    attn_bytes = packed_bytes + n_units * 9 + 2 * BH * T * w.head_dim * 2 + q.numel() * 2 + out.numel() * 4
+    route_bytes = kv_bytes + n_units * (1 + 4 * M)
+    pack_bytes = 2 * kv_bytes + packed_bytes + n_units * 9
+
+    def roof(bytes_, t_ms):
+        g = bytes_ / (t_ms.mean() * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(g, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(g / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": int(bytes_), "avg_ms": round(float(t_ms.mean()), 4),
+                "min_ms": round(float(t_ms.min()), 4), "median_ms": round(float(np.median(t_ms)), 4)}
+
+    res = {
+        "metric": "decode_attn_hbm_GBps", "value": None, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "cached_tokens": w.seq, "chunk": w.chunk, "group": w.group,
+                   "expert_bits": list(w.expert_bits), "realised_mix": mix, "chunks": n_units,
+                   "packed_bytes": packed_bytes, "fp16_equiv_bytes": 2 * kv_bytes},
+        "roofline": dict(roof(attn_bytes, t_attn), kernel="attn_split_kernel (+ attn_merge_kernel, timed as one call)"),
+        "pct_of_hbm_peak": None,
+    }
+    res["value"] = res["roofline"]["achieved"]
+    res["pct_of_hbm_peak"] = round(100 * res["roofline"]["frac"], 2)
+    if not args.decode_only:
+        res["roofline_route"] = dict(roof(route_bytes, t_route), kernel="route_kernel")
+        res["roofline_pack"] = dict(roof(pack_bytes, t_pack), kernel="plan_kernel + pack_kernel")
+        res["route_pack_chunks_per_s"] = round(n_units / ((t_route.mean() + t_pack.mean()) * 1e-3), 1)
+        res["route_chunks_per_s"] = round(n_units / (t_route.mean() * 1e-3), 1)
+        res["pack_chunks_per_s"] = round(n_units / (t_pack.mean() * 1e-3), 1)
+
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, d, scale)
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+def cpu_baseline(w, d, scale):
+    """The CPU oracle as it stands, timed on the first KV heads of the same workload."""
+    from oracle import moqae_ref as R
+    threads = R.num_threads()
+    Hs = min(w.batch * w.n_kv_heads if w.batch == 1 else w.n_kv_heads, max(1, 2 * threads))   # two rows per thread
+    rep = w.n_q_heads // w.n_kv_heads
+    C, T = w.n_chunks, w.n_tail
+    rcfg = R.RefCfg(1, Hs * rep, Hs, w.head_dim, w.chunk, w.group, w.expert_bits, w.freeze_chunks)
+    K = d["K"][:1, :Hs]; V = d["V"][:1, :Hs]; q = np.ascontiguousarray(d["q"][:1, :Hs * rep])
+    t0 = time.perf_counter()
+    e, _ = R.route_chunks(rcfg, K, 0, C, d["W1"], d["W2"], d["W3"])
+    t1 = time.perf_counter()
+    sizes = np.array([R.chunk_block_bytes(rcfg, b) for b in w.expert_bits], np.uint64)[e]
+    arena = np.zeros(int(sizes.sum()) + 4096, np.uint8); used = np.zeros(1, np.uint64); off = np.zeros(e.shape, np.uint64)
+    t2 = time.perf_counter()
+    assert R.quantize_pack(rcfg, K, V, 0, C, e, arena, used, off) == 0
+    t3 = time.perf_counter()
+    Kt = np.zeros((1, Hs, w.chunk, w.head_dim), np.float16); Vt = np.zeros_like(Kt)
+    if T:
+        Kt[:, :, :T] = K[:, :, C * w.chunk:]; Vt[:, :, :T] = V[:, :, C * w.chunk:]
+    R.decode_attn(rcfg, q, arena, off, e, C, Kt, Vt, T, scale)
+    t4 = time.perf_counter()
+    n = Hs * C
+    return {"value": round(float(sizes.sum()) / (t4 - t3) / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {Hs} of {w.batch * w.n_kv_heads} (sequence, KV head) rows of the same workload, all "
+                      f"{C} chunks each: route, pack and one decode-attention call",
+            "route_pack_chunks_per_s": round(n / ((t1 - t0) + (t3 - t2)), 1),
+            "route_s": round(t1 - t0, 3), "pack_s": round(t3 - t2, 3), "attn_s": round(t4 - t3, 3)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

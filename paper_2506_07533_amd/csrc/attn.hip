@@ -351,11 +351,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_split_kernel(AttnArgs a) {
                                          | ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(my_off >> 32), i) << 32);
             const uint8_t *blk = a.arena + off;
             const int TT = 64 / bits;
-            const int nsub = min(4, N / TT);
-            const int ut = nsub * TT, nu = N / ut;
+            const int nu = (N + 4 * TT - 1) / (4 * TT);         // units of up to 4 KiB of codes
             for (int s = 0; s < nu; s++) {
                 if (((ucount + s) & (kAttnWaves - 1)) != wave) continue;
-                const int t0 = s * ut;
+                const int t0 = s * 4 * TT;
+                const int nsub = min(4, (N - t0) / TT);          // the last unit of a chunk may be short
+                const int ut = nsub * TT;
                 if (bits == 16) {
                     unit_fp16<G, REP>(blk + (size_t)t0 * 256, blk + (size_t)N * 256 + (size_t)t0 * 256,
                                       nsub, ut, lane, wave, a.scale_log2, L, st);
