@@ -3,6 +3,7 @@
 #include "../../include/moqae.h"
 #include "moqae_dev.hpp"
 #include "moqae_kernels.hpp"
+#include <stdlib.h>
 
 using namespace moqae;
 
@@ -49,11 +50,19 @@ int cu_count() {
     return cus;
 }
 
-// Splits of one (b, h) row: enough workgroups to fill the chip once (4 workgroups of 4
-// wavefronts per CU), never more than one per chunk.
+// Splits of one (b, h) row: as many workgroups as are resident on the chip at once (one full
+// wave of workgroups, no second round), never more than one per chunk.  MOQAE_DECODE_WGS_PER_CU
+// overrides the occupancy query (tuning aid).
 int choose_splits(const moqae_cfg *c, int n_chunks) {
+    static int override_wgs = -1;
+    if (override_wgs < 0) {
+        const char *e = getenv("MOQAE_DECODE_WGS_PER_CU");
+        override_wgs = e ? atoi(e) : 0;
+    }
     const int64_t rows = (int64_t)c->batch * c->n_kv_heads;
-    const int64_t target = (int64_t)cu_count() * 4;
+    const int per_cu = override_wgs > 0 ? override_wgs
+                                        : attn_resident_wgs_per_cu(c->group, c->n_q_heads / c->n_kv_heads);
+    const int64_t target = (int64_t)cu_count() * per_cu;
     int64_t s = target / rows;
     if (s > n_chunks) s = n_chunks;
     if (s < 1) s = 1;

@@ -33,6 +33,7 @@ struct AttnArgs {
     int bits_of[8];
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
+int attn_resident_wgs_per_cu(int G, int rep);   // occupancy of the split kernel (host query, cached)
 
 constexpr int kAttnWaves = 4;   // wavefronts per decode workgroup; each writes its own partial
 

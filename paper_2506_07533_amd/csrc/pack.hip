@@ -27,12 +27,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PackArgs a) {
     const int64_t total = (int64_t)a.BH * a.n_chunks;
     const int64_t per = (total + kPlanThreads - 1) / kPlanThreads;
     const int64_t i0 = min(total, per * tid), i1 = min(total, i0 + per);
+    const int64_t u0 = i0 / a.n_chunks; const int cc0 = (int)(i0 % a.n_chunks);
+    unsigned long long size_of[8];                    // rounded block size per expert
+#pragma unroll
+    for (int e = 0; e < 8; e++) size_of[e] = (block_bytes(a.N, a.G, a.bits_of[e]) + 255u) & ~255ull;
+    auto size_at = [&](int e) {
+        unsigned long long v = 0;
+#pragma unroll
+        for (int k = 0; k < 8; k++) v = (e == k) ? size_of[k] : v;
+        return v;
+    };
     unsigned long long local = 0;
-    for (int64_t i = i0; i < i1; i++) {
-        const int64_t u = i / a.n_chunks; const int c = a.chunk_begin + (int)(i % a.n_chunks);
-        const int e = a.expert[u * a.expert_stride + c];
-        if (e >= a.M) { bad = 1; continue; }
-        local += (block_bytes(a.N, a.G, a.bits_of[e]) + 255u) & ~255ull;
+    {
+        int64_t u = u0; int cc = cc0;
+        for (int64_t i = i0; i < i1; i++) {
+            const int e = a.expert[u * a.expert_stride + a.chunk_begin + cc];
+            if (e >= a.M) bad = 1; else local += size_at(e);
+            if (++cc == a.n_chunks) { cc = 0; u++; }
+        }
     }
     scan[tid] = local;
     __syncthreads();
@@ -47,11 +59,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PackArgs a) {
     if (bad) { if (tid == 0) *a.status = -1; return; }
     if (start + sum > a.capacity) { if (tid == 0) *a.status = -3; return; }
     unsigned long long pos = start + scan[tid] - local;
-    for (int64_t i = i0; i < i1; i++) {
-        const int64_t u = i / a.n_chunks; const int c = a.chunk_begin + (int)(i % a.n_chunks);
-        const int e = a.expert[u * a.expert_stride + c];
-        a.chunk_off[u * a.off_stride + c] = pos;
-        pos += (block_bytes(a.N, a.G, a.bits_of[e]) + 255u) & ~255ull;
+    {
+        int64_t u = u0; int cc = cc0;
+        for (int64_t i = i0; i < i1; i++) {
+            const int e = a.expert[u * a.expert_stride + a.chunk_begin + cc];
+            a.chunk_off[u * a.off_stride + a.chunk_begin + cc] = pos;
+            pos += size_at(e);
+            if (++cc == a.n_chunks) { cc = 0; u++; }
+        }
     }
     __syncthreads();                                  // every thread has read *arena_used
     if (tid == 0) *a.arena_used = start + sum;
