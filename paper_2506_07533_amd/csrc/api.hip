@@ -50,24 +50,33 @@ int cu_count() {
     return cus;
 }
 
-// Splits of one (b, h) row: as many workgroups as are resident on the chip at once (one full
-// wave of workgroups, no second round), never more than one per chunk.  MOQAE_DECODE_WGS_PER_CU
+// Persistent workgroups of the decode kernel: one per resident slot of the chip, but never more
+// than there are tickets of 128 tokens to hand to their wavefronts.  MOQAE_DECODE_WGS_PER_CU
 // overrides the occupancy query (tuning aid).
-int choose_splits(const moqae_cfg *c, int n_chunks) {
+int choose_wgs(const moqae_cfg *c, int n_chunks, int n_tail) {
     static int override_wgs = -1;
     if (override_wgs < 0) {
         const char *e = getenv("MOQAE_DECODE_WGS_PER_CU");
         override_wgs = e ? atoi(e) : 0;
     }
+    const int rep = c->n_q_heads / c->n_kv_heads;
+    const int per_cu = override_wgs > 0 ? override_wgs : attn_resident_wgs_per_cu(c->group, rep);
     const int64_t rows = (int64_t)c->batch * c->n_kv_heads;
-    const int per_cu = override_wgs > 0 ? override_wgs
-                                        : attn_resident_wgs_per_cu(c->group, c->n_q_heads / c->n_kv_heads);
-    const int64_t target = (int64_t)cu_count() * per_cu;
-    int64_t s = target / rows;
-    if (s > n_chunks) s = n_chunks;
-    if (s < 1) s = 1;
-    if (s > 1024) s = 1024;
-    return (int)s;
+    const int64_t tickets = rows * ((int64_t)n_chunks * (c->chunk >= 256 ? c->chunk / 128 : 1) + (n_tail + 127) / 128);
+    int64_t n = (int64_t)cu_count() * per_cu;
+    const int64_t cap = (tickets + attn_waves_per_wg(rep) - 1) / attn_waves_per_wg(rep);
+    if (n > cap) n = cap;
+    if (n < 1) n = 1;
+    return (int)n;
+}
+
+// Workspace: one partial (o[D], m, l) per query head and per workgroup that can touch its row.
+// Sized for the largest residual (n_tail = chunk - 1) so that it does not depend on n_tail.
+uint64_t workspace_bytes(const moqae_cfg *c, int n_chunks) {
+    const int BH = c->batch * c->n_kv_heads;
+    const int n_wg = choose_wgs(c, n_chunks, c->chunk - 1);
+    const uint64_t rows = (uint64_t)c->batch * c->n_q_heads;
+    return rows * (uint64_t)attn_max_partials(n_wg, BH) * (kD + 2) * sizeof(float);
 }
 
 }  // namespace
@@ -99,8 +108,7 @@ uint64_t moqae_arena_upper_bound(const moqae_cfg *cfg, int64_t n_chunks_total) {
 
 uint64_t moqae_decode_workspace_bytes(const moqae_cfg *cfg, int32_t n_chunks) {
     if (!cfg_ok(cfg) || n_chunks < 0) return 0;
-    const uint64_t rows = (uint64_t)cfg->batch * cfg->n_q_heads;
-    return rows * (uint64_t)choose_splits(cfg, n_chunks) * kAttnWaves * (kD + 2) * sizeof(float);
+    return workspace_bytes(cfg, n_chunks);
 }
 
 int moqae_route_chunks(const moqae_cfg *cfg,
@@ -186,7 +194,9 @@ int moqae_decode_attn(const moqae_cfg *cfg,
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
     a.part = static_cast<float *>(workspace); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;
-    a.n_chunks = n_chunks; a.n_tail = n_tail; a.n_split = choose_splits(cfg, n_chunks);
+    a.n_chunks = n_chunks; a.n_tail = n_tail;
+    a.n_wg = choose_wgs(cfg, n_chunks, n_tail);
+    a.max_partials = attn_max_partials(a.n_wg, cfg->batch * cfg->n_kv_heads);
     a.N = cfg->chunk; a.G = cfg->group; a.Hkv = cfg->n_kv_heads; a.rep = cfg->n_q_heads / cfg->n_kv_heads;
     a.BH = cfg->batch * cfg->n_kv_heads;
     for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;

@@ -3,11 +3,12 @@
 // paper: the quantised keys are de-quantised before they meet the query; softmax needs high
 // precision).
 //
-// attn_split_kernel   grid (n_split, B*Hkv), 4 wavefronts per workgroup.  A workgroup owns a
-//                     byte-balanced range of the row's chunks; its wavefronts take "units" of
-//                     that range round-robin.  A unit is up to 4 KiB of K codes plus the
-//                     matching 4 KiB of V codes (128 / 64 / 32 / 16 tokens at 2 / 4 / 8 / 16
-//                     bits), loaded with one 16-byte load per lane per KiB.
+// attn_split_kernel   one persistent workgroup per CU (16 wavefronts; 8 for grouped queries).  A
+//                     workgroup owns a cost-balanced interval of the (sequence, KV head) rows;
+//                     inside a row its wavefronts draw tickets of 128 tokens from an LDS
+//                     counter and stream them "unit" by unit.  A unit is up to 4 KiB of K
+//                     codes plus the matching 4 KiB of V codes (128 / 64 / 32 / 16 tokens at
+//                     2 / 4 / 8 / 16 bits), loaded with one 16-byte load per lane per KiB.
 //                     K: a lane holds 128/b consecutive codes of one token; V: a lane holds the
 //                     codes of dims (2l, 2l+1) for the 64/b tokens of a tile.  Codes are never
 //                     converted: masking a word leaves two codes in the mantissa fields of an
@@ -16,14 +17,13 @@
 //                     of the softmax weight (V), and the zero-points are factored out:
 //                       q.k^   = sum_g scale_g * (sum_d code_d q_d) + zero_g * (sum_{d in g} q_d)
 //                       sum p v^ = sum_t (p_t scale_tg) code_td  +  sum_t p_t zero_tg.
-//                     Every wavefront writes one partial (m, l, o[D]).
+//                     Every workgroup writes one partial (m, l, o[D]) per row it touched.
 // attn_merge_kernel   log-sum-exp merge of the partials of one query head, normalisation.
 #include "moqae_dev.hpp"
 #include "moqae_kernels.hpp"
 
 namespace moqae {
 
-constexpr int kAttnThreads = kAttnWaves * kWave;
 constexpr float kTwo24 = 16777216.0f;
 constexpr float kTwoM24 = 1.0f / 16777216.0f;
 
@@ -39,14 +39,20 @@ template <int BITS> struct BW {
     static constexpr int BI = BITS == 2 ? 0 : (BITS == 4 ? 1 : (BITS == 8 ? 2 : 3));
 };
 
-template <int G, int REP> struct alignas(16) AttnLds {
+constexpr int kDescCap = 1024;                            // chunk descriptors held in LDS at a time
+
+template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     static constexpr int NG = kD / G;
     uint32_t qtab[4][REP][64];                           // q as fp16 pairs, ordered and pre-scaled per bit-width
     float qpart[4][REP][16][2];                          // sum of q over a lane's dims (per group inside the slot)
-    float sc[kAttnWaves][REP][128];                      // scores (log2 domain) / fp16-path weights of a unit
-    uint16_t wl[kAttnWaves][REP][NG][128];               // fp16 softmax weight * V scale, pre-scaled per pair
-    unsigned long long scan[kAttnThreads];
+    float sc[NWV][REP][128];                             // scores (log2 domain) / fp16-path weights of a unit
+    uint16_t wl[NWV][REP][NG][128];                      // fp16 softmax weight * V scale, pre-scaled per pair
+    float comb[NWV][REP][kD + 2];                        // per-wavefront (o, m, l) at the end of a row segment
+    uint32_t qraw[REP * 64];                             // the row's queries as loaded (fp16 pairs)
+    unsigned long long desc[kDescCap];                   // chunk descriptors of the current pass: offset | expert
+    uint32_t wsum[NWV], wscan[NWV];
     int range[2];
+    int ticket;
 };
 
 // Orders this wavefront's LDS traffic between phases that exchange data across lanes.
@@ -121,10 +127,10 @@ __device__ __forceinline__ void load_k(const Unit &u, int lane, KRegs<G> &k) {
 }
 
 // ---- one unit of a quantised chunk -----------------------------------------------------------
-template <int BITS, int G, int REP, class Prefetch>
+template <int BITS, int G, int REP, int NWV, class Prefetch>
 __device__ __forceinline__ void unit_quant(const Unit &u, KRegs<G> &k, Prefetch &&prefetch,
                                            int lane, int wave, float scale_log2,
-                                           AttnLds<G, REP> &L, WaveState<REP> &st) {
+                                           AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
     using B = BW<BITS>;
     constexpr int NG = kD / G;
     constexpr int GS = (B::E > G) ? B::E / G : 1;        // groups inside one slot
@@ -223,10 +229,10 @@ __device__ __forceinline__ void unit_quant(const Unit &u, KRegs<G> &k, Prefetch 
 }
 
 // ---- one unit of raw fp16 rows (16-bit chunks and the FP16 residual) -----------------------
-template <int G, int REP, class Prefetch>
+template <int G, int REP, int NWV, class Prefetch>
 __device__ __forceinline__ void unit_fp16(const Unit &u, KRegs<G> &k, Prefetch &&prefetch,
                                           int lane, int wave, float scale_log2,
-                                          AttnLds<G, REP> &L, WaveState<REP> &st) {
+                                          AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
     const int part = lane & 15, tok_l = lane >> 4;
     const int nvalid = u.nvalid;                          // an fp16 unit always spans 16 rows
     uint32_t vv[16];
@@ -280,16 +286,42 @@ __device__ __forceinline__ void unit_fp16(const Unit &u, KRegs<G> &k, Prefetch &
     wave_sync();
 }
 
-template <int G, int REP>
-__global__ __launch_bounds__(kAttnThreads, (REP == 1 ? 4 : 2)) void attn_split_kernel(AttnArgs a) {
-    __shared__ AttnLds<G, REP> L;
+// ---- work distribution ----------------------------------------------------------------------
+// One persistent workgroup per CU slot.  Workgroup w of NW owns the interval
+// [w*BH/NW, (w+1)*BH/NW) of the row axis, where a fraction of a row means that fraction of the
+// row's estimated cost (so a workgroup covers part of a row, or several rows).  Inside a row
+// segment the workgroup's wavefronts draw tickets (up to 128 tokens of one chunk, or 128 rows of
+// the FP16 residual) from a counter in LDS: a wavefront that runs faster -- the SIMD arbiter
+// favours the oldest ones -- just takes more tickets, and all of them finish the segment
+// together.  The workgroup then folds its wavefronts' softmax states into ONE partial per row.
+__host__ __device__ inline void wg_interval(int w, int NW, int BH, int &r0, int &f0, int &r1, int &f1) {
+    const long long a0 = (long long)w * BH, a1 = (long long)(w + 1) * BH;
+    r0 = (int)(a0 / NW); f0 = (int)(a0 % NW); r1 = (int)(a1 / NW); f1 = (int)(a1 % NW);
+}
+// Workgroups that touch row r: first = the one containing the row's start, last = the one
+// containing its end; partial slot of workgroup w in row r = w - first.
+__host__ __device__ inline int wg_first_of_row(int r, int NW, int BH) { return (int)(((long long)r * NW) / BH); }
+__host__ __device__ inline int wg_last_of_row(int r, int NW, int BH) {
+    return (int)((((long long)(r + 1) * NW) + BH - 1) / BH) - 1;
+}
+int attn_max_partials(int NW, int BH) { return NW / BH + 2; }
+
+// relative cost of one chunk at a bit-width (measured instruction counts of the four paths)
+__device__ __forceinline__ uint32_t chunk_cost(int bits) {
+    return bits == 2 ? 760u : (bits == 4 ? 1010u : (bits == 8 ? 1500u : 2480u));
+}
+
+template <int G, int REP, int NWV>
+__global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
+    __shared__ AttnLds<G, REP, NWV> L;
     constexpr int NG = kD / G;
+    constexpr int NT = NWV * 64;
     const int tid = (int)threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // wave-uniform, kept scalar
-    const int split = (int)blockIdx.x, u = (int)blockIdx.y;
+    const int w = (int)blockIdx.x, NW = (int)gridDim.x;
     const int N = a.N, C = a.n_chunks;
-    const uint8_t *erow = a.expert + (int64_t)u * a.desc_stride;
-    const uint64_t *orow = a.chunk_off + (int64_t)u * a.desc_stride;
+    const int PC = N >= 256 ? N / 128 : 1;               // tickets per chunk
+    const int TKN = N / PC;                              // tokens per ticket
 
     auto bits_of = [&](int e) {
         int b = 0;
@@ -298,191 +330,245 @@ __global__ __launch_bounds__(kAttnThreads, (REP == 1 ? 4 : 2)) void attn_split_k
         return b;
     };
 
-    // ---- byte-balanced chunk range of this split: chunk c belongs to the split that contains
-    //      the byte position where its block starts in the row's concatenated blocks
-    {
-        const int per = (C + kAttnThreads - 1) / kAttnThreads;
-        const int i0 = min(C, per * tid), i1 = min(C, i0 + per);
-        unsigned long long local = 0;
-        for (int c = i0; c < i1; c++) local += block_bytes(N, G, bits_of(erow[c]));
-        unsigned long long incl = local;                   // inclusive scan inside the wavefront
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const unsigned long long v = __shfl_up(incl, o);
-            if (lane >= o) incl += v;
-        }
-        if (lane == 63) L.scan[wave] = incl;
-        if (tid == 0) { L.range[0] = C; L.range[1] = C; }
-        __syncthreads();
-        unsigned long long base = 0, total = 0;
-#pragma unroll
-        for (int wv = 0; wv < kAttnWaves; wv++) { if (wv < wave) base += L.scan[wv]; total += L.scan[wv]; }
-        const unsigned long long lo = total / a.n_split * split + total % a.n_split * split / a.n_split;
-        const unsigned long long hi = (split == a.n_split - 1) ? total
-                                    : total / a.n_split * (split + 1) + total % a.n_split * (split + 1) / a.n_split;
-        unsigned long long pos = base + incl - local;
-        int f0 = C, f1 = C;
-        for (int c = i0; c < i1; c++) {
-            if (f0 == C && pos >= lo) f0 = c;
-            if (f1 == C && pos >= hi) f1 = c;
-            pos += block_bytes(N, G, bits_of(erow[c]));
-        }
-        if (f0 < C) atomicMin(&L.range[0], f0);
-        if (f1 < C) atomicMin(&L.range[1], f1);
-    }
+    int r0, f0, r1, f1;
+    wg_interval(w, NW, a.BH, r0, f0, r1, f1);
+    for (int u = r0; u <= r1 && u < a.BH; u++) {
+        if (u == r1 && f1 == 0) break;
+        const uint32_t lo_num = (u == r0) ? (uint32_t)f0 : 0u, hi_num = (u == r1) ? (uint32_t)f1 : (uint32_t)NW;
+        const uint8_t *erow = a.expert + (int64_t)u * a.desc_stride;
+        const uint64_t *orow = a.chunk_off + (int64_t)u * a.desc_stride;
 
-    // ---- q tables: per bit-width the pairs in the order the unpacking produces them
-    {
-        const int b = u / a.Hkv, h = u % a.Hkv;
-        const uint16_t *qrow = a.q + ((int64_t)b * a.Hkv * REP + (int64_t)h * REP) * kD;
-        for (int i = tid; i < 4 * REP * 64; i += kAttnThreads) {
-            const int bi = i / (REP * 64), r = (i / 64) % REP, ent = i % 64;
-            const int BITSv = 2 << bi;
-            const int ps = 64 / BITSv, ppw = bi == 3 ? 1 : 16 / BITSv, kd = bi == 0 ? 5 : (bi == 1 ? 2 : 1);
-            const int part = ent / ps, ii = ent % ps, j = ii / ppw, k = ii % ppw;
-            const int d0 = part * (128 / BITSv) + j * 2 * ppw + 2 * k;
-            const int kp = bi == 3 ? 0 : BITSv * (k < kd ? k : k - kd);
-            const float f = __builtin_bit_cast(float, (uint32_t)(127 - kp) << 23);
-            const uint32_t lo16 = float_to_half_bits(half_bits_to_float(qrow[r * kD + d0]) * f);
-            const uint32_t hi16 = float_to_half_bits(half_bits_to_float(qrow[r * kD + d0 + 1]) * f);
-            L.qtab[bi][r][ent] = lo16 | (hi16 << 16);
-        }
-        for (int i = tid; i < 4 * REP * 16 * 2; i += kAttnThreads) {
-            const int bi = i / (REP * 32), r = (i / 32) % REP, part = (i / 2) % 16, gi = i % 2;
-            const int BITSv = 2 << bi, E = 128 / BITSv;
-            float s = 0.0f;
-            if (part < BITSv) {
-                const int gs = E > G ? E / G : 1;
-                if (gi < gs) {
-                    const int len = E / gs, d0 = part * E + gi * len;
-                    for (int d = 0; d < len; d++) s += half_bits_to_float(qrow[r * kD + d0 + d]);
+        // ---- (a) row set-up: raw q, cost scan -> chunk range [c0, c1) of this segment, q tables.
+        //      All global loads are issued before the first barrier.
+        const int n_tiles = (C + NT - 1) / NT;
+        {
+            const int bq = u / a.Hkv, hq0 = (u % a.Hkv) * REP;
+            const uint32_t *qrow32 = reinterpret_cast<const uint32_t *>(a.q + ((int64_t)bq * a.Hkv * REP + hq0) * kD);
+            __syncthreads();                             // LDS of the previous segment is free
+            for (int i = tid; i < REP * 64; i += NT) L.qraw[i] = qrow32[i];
+            if (tid == 0) { L.range[0] = C; L.range[1] = C; }
+            // pass 1 (only when the row has more chunks than threads): the row total
+            unsigned long long total = 0;
+            if (n_tiles > 1) {
+                uint32_t sum = 0;
+                for (int tile = 0; tile < n_tiles; tile++) {
+                    const int c = tile * NT + tid;
+                    if (c < C) sum += chunk_cost(bits_of(erow[c]));
                 }
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+                if (lane == 0) L.wsum[wave] = sum;
+                __syncthreads();
+#pragma unroll
+                for (int wv = 0; wv < NWV; wv++) total += L.wsum[wv];
             }
-            L.qpart[bi][r][part][gi] = s;
-        }
-    }
-    __syncthreads();
-    const int c0 = __builtin_amdgcn_readfirstlane(L.range[0]), c1 = __builtin_amdgcn_readfirstlane(L.range[1]);
-
-    WaveState<REP> st;
+            unsigned long long base = 0;
+            int g0 = C, g1 = C;
+            for (int tile = 0; tile < n_tiles; tile++) {
+                const int c = tile * NT + tid;
+                const uint32_t cst = c < C ? chunk_cost(bits_of(erow[c])) : 0u;
+                uint32_t incl = cst;                                  // inclusive scan inside the wavefront
 #pragma unroll
-    for (int r = 0; r < REP; r++) { st.m[r] = -INFINITY; st.lsum[r] = 0.0f; st.z[r] = 0.0f; st.acc[r][0] = 0.0f; st.acc[r][1] = 0.0f; }
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t v = __shfl_up(incl, o);
+                    if (lane >= o) incl += v;
+                }
+                if (tile > 0) __syncthreads();
+                if (lane == 63) L.wscan[wave] = incl;
+                __syncthreads();
+                unsigned long long pos = base + incl - cst, tile_total = 0;
+#pragma unroll
+                for (int wv = 0; wv < NWV; wv++) { if (wv < wave) pos += L.wscan[wv]; tile_total += L.wscan[wv]; }
+                if (n_tiles == 1) total = tile_total;
+                // chunk c belongs to the segment iff lo_num/NW <= pos_c/total < hi_num/NW
+                if (c < C) {
+                    if (pos * (unsigned)NW >= total * lo_num) g0 = min(g0, c);
+                    if (hi_num < (uint32_t)NW && pos * (unsigned)NW >= total * hi_num) g1 = min(g1, c);
+                }
+                base += tile_total;
+            }
+            if (g0 < C) atomicMin(&L.range[0], g0);
+            if (g1 < C) atomicMin(&L.range[1], g1);
 
-    // ---- this wavefront's units: every 4th unit of the range (and of the FP16 residual, which
-    //      the last split takes), enumerated chunk by chunk
-    const bool has_tail = split == a.n_split - 1 && a.n_tail > 0;
-    int ci = c0, cbase = c0, nbatch = 0, s_next = 0, ucount = 0, my_bits = 0;
-    unsigned long long my_off = 0;
-    bool in_tail = false;
-    auto next_unit = [&](Unit &un) -> bool {
-        for (;;) {
-            if (!in_tail) {
-                if (ci >= c1) {
-                    if (!has_tail) return false;
-                    in_tail = true; s_next = 0;
-                    continue;
-                }
-                if (ci >= cbase + nbatch) {                 // next batch of 64 chunk descriptors
-                    cbase = ci; nbatch = min(64, c1 - cbase);
-                    my_bits = 0; my_off = 0;
-                    if (lane < nbatch) { my_bits = bits_of(erow[cbase + lane]); my_off = orow[cbase + lane]; }
-                }
-                const int i = ci - cbase;
-                const int bits = __builtin_amdgcn_readlane(my_bits, i);
-                const int TT = 64 / bits;
-                const int nu = (N + 4 * TT - 1) / (4 * TT);
-                const int s = s_next + ((wave - (ucount + s_next)) & (kAttnWaves - 1));
-                if (s < nu) {
-                    const unsigned long long off =
-                        (unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)my_off, i) |
-                        ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(my_off >> 32), i) << 32);
-                    const uint8_t *blk = a.arena + off;
-                    const int t0 = s * 4 * TT;
-                    un.bits = bits; un.nsub = min(4, (N - t0) / TT); un.nvalid = un.nsub * TT;
-                    if (bits == 16) {
-                        un.kc = blk + (size_t)t0 * 256; un.vc = blk + (size_t)N * 256 + (size_t)t0 * 256;
-                        un.km = reinterpret_cast<const uint32_t *>(un.kc); un.vm = un.km;   // no meta: see load_k
-                    } else {
-                        const size_t cb = (size_t)N * 16 * bits, mb = (size_t)N * NG * 4;
-                        un.kc = blk + (size_t)t0 * 16 * bits;
-                        un.km = reinterpret_cast<const uint32_t *>(blk + cb) + t0 * NG;
-                        un.vc = blk + cb + mb + (size_t)t0 * 16 * bits;
-                        un.vm = reinterpret_cast<const uint32_t *>(blk + 2 * cb + mb) + t0 * NG;
+            const uint16_t *qraw = reinterpret_cast<const uint16_t *>(L.qraw);
+            for (int i = tid; i < 4 * REP * 64; i += NT) {
+                const int bi = i / (REP * 64), r = (i / 64) % REP, ent = i % 64;
+                const int BITSv = 2 << bi;
+                const int ps = 64 / BITSv, ppw = bi == 3 ? 1 : 16 / BITSv, kd = bi == 0 ? 5 : (bi == 1 ? 2 : 1);
+                const int part = ent / ps, ii = ent % ps, j = ii / ppw, k = ii % ppw;
+                const int d0 = part * (128 / BITSv) + j * 2 * ppw + 2 * k;
+                const int kp = bi == 3 ? 0 : BITSv * (k < kd ? k : k - kd);
+                const float f = __builtin_bit_cast(float, (uint32_t)(127 - kp) << 23);
+                const uint32_t lo16 = float_to_half_bits(half_bits_to_float(qraw[r * kD + d0]) * f);
+                const uint32_t hi16 = float_to_half_bits(half_bits_to_float(qraw[r * kD + d0 + 1]) * f);
+                L.qtab[bi][r][ent] = lo16 | (hi16 << 16);
+            }
+            for (int i = tid; i < 4 * REP * 16 * 2; i += NT) {
+                const int bi = i / (REP * 32), r = (i / 32) % REP, part = (i / 2) % 16, gi = i % 2;
+                const int BITSv = 2 << bi, E = 128 / BITSv;
+                float sq = 0.0f;
+                if (part < BITSv) {
+                    const int gs = E > G ? E / G : 1;
+                    if (gi < gs) {
+                        const int len = E / gs, d0 = part * E + gi * len;
+                        for (int d = 0; d < len; d++) sq += half_bits_to_float(qraw[r * kD + d0 + d]);
                     }
-                    s_next = s + 1;
-                    return true;
                 }
-                ucount += nu; ci++; s_next = 0;
-            } else {
-                const int nu = (a.n_tail + 15) / 16;
-                const int s = s_next + ((wave - (ucount + s_next)) & (kAttnWaves - 1));
-                if (s >= nu) return false;
-                const size_t rowb = ((size_t)u * N + (size_t)16 * s) * 256;
-                un.bits = 16; un.nsub = 4; un.nvalid = min(16, a.n_tail - 16 * s);
-                un.kc = reinterpret_cast<const uint8_t *>(a.K_tail) + rowb;
-                un.vc = reinterpret_cast<const uint8_t *>(a.V_tail) + rowb;
-                un.km = reinterpret_cast<const uint32_t *>(un.kc); un.vm = un.km;
-                s_next = s + 1;
-                return true;
+                L.qpart[bi][r][part][gi] = sq;
             }
+            __syncthreads();
         }
-    };
+        const int c0 = __builtin_amdgcn_readfirstlane(L.range[0]), c1 = __builtin_amdgcn_readfirstlane(L.range[1]);
 
-    Unit cur, nxt;
-    KRegs<G> kr;
-    bool have = next_unit(cur);
-    if (have) load_k<G>(cur, lane, kr);
-    while (have) {
-        const bool have_next = next_unit(nxt);
-        const Unit &pf = have_next ? nxt : cur;          // nothing left: re-read the current unit (ignored)
-        auto prefetch = [&]() { load_k<G>(pf, lane, kr); };
-        if (cur.bits == 2)      unit_quant<2, G, REP>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
-        else if (cur.bits == 4) unit_quant<4, G, REP>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
-        else if (cur.bits == 8) unit_quant<8, G, REP>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
-        else                    unit_fp16<G, REP>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
-        cur = nxt; have = have_next;
-    }
+        WaveState<REP> st;
+#pragma unroll
+        for (int r = 0; r < REP; r++) { st.m[r] = -INFINITY; st.lsum[r] = 0.0f; st.z[r] = 0.0f; st.acc[r][0] = 0.0f; st.acc[r][1] = 0.0f; }
 
-    // ---- the wavefront's partial: o[d] = acc[d] * 2^24 + sum_t p_t zero_{t,g(d)}, plus (m, l)
-    const int P = a.n_split * kAttnWaves;
+        // ---- (b) the segment in passes of at most kDescCap chunks whose descriptors
+        //      (block offset | expert index) sit in LDS; wavefronts draw tickets from LDS
+        for (int cs = c0; cs < c1 || (cs == c0 && c0 >= c1); cs += kDescCap) {
+            const int ce = min(c1, cs + kDescCap);
+            const bool last_pass = ce >= c1;
+            if (cs > c0) __syncthreads();                // previous pass's descriptors consumed
+            for (int c = cs + tid; c < ce; c += NT) L.desc[c - cs] = orow[c] | (unsigned long long)erow[c];
+            if (tid == 0) L.ticket = 0;
+            __syncthreads();
+            const int n_chunk_tickets = max(0, ce - cs) * PC;
+            const int TK = n_chunk_tickets + ((last_pass && hi_num == (uint32_t)NW) ? (a.n_tail + 127) / 128 : 0);
+
+            auto draw = [&]() -> int {
+                int t = 0;
+                if (lane == 0) t = atomicAdd(&L.ticket, 1);
+                return __builtin_amdgcn_readfirstlane(t);
+            };
+            int c_bits = 0, c_t0 = 0, c_tend = 0, s_next = 0, c_nu = 0, c_tail0 = -1;
+            const uint8_t *c_blk = nullptr;
+            auto resolve = [&](int tk) {                 // ticket tk -> scalars
+                if (tk < n_chunk_tickets) {
+                    const unsigned long long dsc = L.desc[tk / PC];
+                    const unsigned long long dsc_u =
+                        (unsigned long long)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dsc) |
+                        ((unsigned long long)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dsc >> 32)) << 32);
+                    c_bits = bits_of((int)(dsc_u & 0xffu));
+                    c_blk = a.arena + (dsc_u & ~0xffull);
+                    c_t0 = (tk % PC) * TKN; c_tend = c_t0 + TKN; c_tail0 = -1;
+                    const int TT = 64 / c_bits;
+                    c_nu = (TKN + 4 * TT - 1) / (4 * TT);
+                } else {                                 // FP16 residual rows [c_tail0, c_tend)
+                    c_bits = 16; c_tail0 = (tk - n_chunk_tickets) * 128; c_tend = min(a.n_tail, c_tail0 + 128);
+                    c_nu = (c_tend - c_tail0 + 15) / 16;
+                }
+                s_next = 0;
+            };
+            int tk_cur = draw();
+            bool have_ticket = tk_cur < TK;
+            if (have_ticket) resolve(tk_cur);
+            auto next_unit = [&](Unit &un) -> bool {
+                for (;;) {
+                    if (!have_ticket) return false;
+                    if (s_next < c_nu) {
+                        const int s = s_next++;
+                        un.bits = c_bits;
+                        if (c_tail0 >= 0) {
+                            const size_t rowb = ((size_t)u * N + (size_t)(c_tail0 + 16 * s)) * 256;
+                            un.nsub = 4; un.nvalid = min(16, c_tend - c_tail0 - 16 * s);
+                            un.kc = reinterpret_cast<const uint8_t *>(a.K_tail) + rowb;
+                            un.vc = reinterpret_cast<const uint8_t *>(a.V_tail) + rowb;
+                            un.km = reinterpret_cast<const uint32_t *>(un.kc); un.vm = un.km;   // no meta: see load_k
+                        } else {
+                            const int TT = 64 / c_bits;
+                            const int t0 = c_t0 + s * 4 * TT;
+                            un.nsub = min(4, (c_tend - t0) / TT); un.nvalid = un.nsub * TT;
+                            if (c_bits == 16) {
+                                un.kc = c_blk + (size_t)t0 * 256; un.vc = c_blk + (size_t)N * 256 + (size_t)t0 * 256;
+                                un.km = reinterpret_cast<const uint32_t *>(un.kc); un.vm = un.km;
+                            } else {
+                                const size_t cb = (size_t)N * 16 * c_bits, mb = (size_t)N * NG * 4;
+                                un.kc = c_blk + (size_t)t0 * 16 * c_bits;
+                                un.km = reinterpret_cast<const uint32_t *>(c_blk + cb) + t0 * NG;
+                                un.vc = c_blk + cb + mb + (size_t)t0 * 16 * c_bits;
+                                un.vm = reinterpret_cast<const uint32_t *>(c_blk + 2 * cb + mb) + t0 * NG;
+                            }
+                        }
+                        return true;
+                    }
+                    tk_cur = draw();                     // ticket finished: take the next one
+                    have_ticket = tk_cur < TK;
+                    if (!have_ticket) return false;
+                    resolve(tk_cur);
+                }
+            };
+
+            Unit cur, nxt;
+            KRegs<G> kr;
+            bool have = next_unit(cur);
+            if (have) load_k<G>(cur, lane, kr);
+            while (have) {
+                const bool have_next = next_unit(nxt);
+                const Unit &pf = have_next ? nxt : cur;  // nothing left: re-read the current unit (ignored)
+                auto prefetch = [&]() { load_k<G>(pf, lane, kr); };
+                if (cur.bits == 2)      unit_quant<2, G, REP, NWV>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
+                else if (cur.bits == 4) unit_quant<4, G, REP, NWV>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
+                else if (cur.bits == 8) unit_quant<8, G, REP, NWV>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
+                else                    unit_fp16<G, REP, NWV>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
+                cur = nxt; have = have_next;
+            }
+            if (c0 >= c1) break;                         // empty chunk range: the single pass is done
+        }
+
+        // ---- (c) fold the wavefronts' states: o[d] = acc[d] * 2^24 + sum_t p_t zero_{t,g(d)}
 #pragma unroll
-    for (int r = 0; r < REP; r++) {
-        float lt = st.lsum[r], zt = st.z[r];
+        for (int r = 0; r < REP; r++) {
+            float lt = st.lsum[r], zt = st.z[r];
 #pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) lt += __shfl_xor(lt, o);
+            for (int o = 32; o >= 1; o >>= 1) lt += __shfl_xor(lt, o);
 #pragma unroll
-        for (int o = 32; o >= NG; o >>= 1) zt += __shfl_xor(zt, o);   // lanes with equal lane % NG
-        const float zg = __shfl(zt, (2 * lane) / G);
-        float *dst = a.part + (((int64_t)u * REP + r) * P + (int64_t)split * kAttnWaves + wave) * (kD + 2);
-        float2 o2; o2.x = fmaf(st.acc[r][0], kTwo24, zg); o2.y = fmaf(st.acc[r][1], kTwo24, zg);
-        *reinterpret_cast<float2 *>(dst + 2 * lane) = o2;
-        if (lane == 0) { dst[kD] = st.m[r]; dst[kD + 1] = lt; }
+            for (int o = 32; o >= NG; o >>= 1) zt += __shfl_xor(zt, o);   // lanes with equal lane % NG
+            const float zg = __shfl(zt, (2 * lane) / G);
+            float *dst = &L.comb[wave][r][0];
+            dst[2 * lane] = fmaf(st.acc[r][0], kTwo24, zg);
+            dst[2 * lane + 1] = fmaf(st.acc[r][1], kTwo24, zg);
+            if (lane == 0) { dst[kD] = st.m[r]; dst[kD + 1] = lt; }
+        }
+        __syncthreads();
+        const int slot = w - wg_first_of_row(u, NW, a.BH);
+        for (int i = tid; i < REP * kD; i += NT) {
+            const int r = i / kD, d = i % kD;
+            float M = -INFINITY;
+#pragma unroll
+            for (int wv = 0; wv < NWV; wv++) M = fmaxf(M, L.comb[wv][r][kD]);
+            float num = 0.0f, den = 0.0f;
+#pragma unroll
+            for (int wv = 0; wv < NWV; wv++) {
+                const float f = (L.comb[wv][r][kD] == -INFINITY) ? 0.0f : fast_exp2(L.comb[wv][r][kD] - M);
+                num = fmaf(L.comb[wv][r][d], f, num);
+                den = fmaf(L.comb[wv][r][kD + 1], f, den);
+            }
+            float *dst = a.part + (((int64_t)u * REP + r) * a.max_partials + slot) * (kD + 2);
+            dst[d] = num;
+            if (d == 0) { dst[kD] = M; dst[kD + 1] = den; }
+        }
     }
 }
 
-// out[b, hq, :] = sum_p o_p 2^(m_p - M) / sum_p l_p 2^(m_p - M) over the P partials of the row.
-constexpr int kMergeGroups = 4;
+// out[b, hq, :] = sum_p o_p 2^(m_p - M) / sum_p l_p 2^(m_p - M) over the partials of the row
+// (one per workgroup that touched the row's KV head).
+constexpr int kMergeGroups = 2;
 __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const float *__restrict__ part,
-                                                                       float *__restrict__ out, int P) {
-    __shared__ float red[kD * kMergeGroups];
+                                                                       float *__restrict__ out, int rep, int NW,
+                                                                       int BH, int max_partials) {
     __shared__ float numl[kMergeGroups][kD];
     __shared__ float denl[kMergeGroups];
     const int row = (int)blockIdx.x, tid = (int)threadIdx.x, d = tid & (kD - 1), grp = tid >> 7;
-    const float *p0 = part + (int64_t)row * P * (kD + 2);
-    float mx = -INFINITY;
-    for (int p = tid; p < P; p += kD * kMergeGroups) mx = fmaxf(mx, p0[(int64_t)p * (kD + 2) + kD]);
-    red[tid] = mx;
-    __syncthreads();
-    for (int o = kD * kMergeGroups / 2; o >= 1; o >>= 1) {
-        if (tid < o) red[tid] = fmaxf(red[tid], red[tid + o]);
-        __syncthreads();
-    }
-    const float M = red[0];
+    const int u = row / rep;
+    const int P = wg_last_of_row(u, NW, BH) - wg_first_of_row(u, NW, BH) + 1;
+    const float *p0 = part + (int64_t)row * max_partials * (kD + 2);
+    float M = -INFINITY;
+    for (int p = 0; p < P; p++) M = fmaxf(M, p0[(int64_t)p * (kD + 2) + kD]);
     float num = 0.0f, den = 0.0f;
-#pragma unroll 4
     for (int p = grp; p < P; p += kMergeGroups) {
         const float *pp = p0 + (int64_t)p * (kD + 2);
-        const float f = fast_exp2(pp[kD] - M);               // empty partial: m = -inf -> 0
+        const float f = (pp[kD] == -INFINITY) ? 0.0f : fast_exp2(pp[kD] - M);   // empty partial
         num = fmaf(pp[d], f, num);
         den = fmaf(pp[kD + 1], f, den);
     }
@@ -497,12 +583,15 @@ __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const floa
     }
 }
 
+template <int REP> constexpr int waves_per_wg() { return REP == 1 ? 16 : 8; }
+
 template <int G, int REP>
 static int resident_wgs_per_cu() {
     static int cached = 0;
     if (cached == 0) {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_split_kernel<G, REP>, kAttnThreads, 0) != hipSuccess || n < 1)
+        constexpr int NWV = waves_per_wg<REP>();
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_split_kernel<G, REP, NWV>, NWV * 64, 0) != hipSuccess || n < 1)
             n = 1;
         cached = n;
     }
@@ -511,11 +600,12 @@ static int resident_wgs_per_cu() {
 
 template <int G, int REP>
 static hipError_t launch_gr(const AttnArgs &a, hipStream_t s) {
-    hipLaunchKernelGGL((attn_split_kernel<G, REP>), dim3((unsigned)a.n_split, (unsigned)a.BH), dim3(kAttnThreads), 0, s, a);
+    constexpr int NWV = waves_per_wg<REP>();
+    hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)(a.BH * a.rep)), dim3(kD * kMergeGroups), 0, s,
-                       (const float *)a.part, a.out, a.n_split * kAttnWaves);
+                       (const float *)a.part, a.out, a.rep, a.n_wg, a.BH, a.max_partials);
     return hipGetLastError();
 }
 
@@ -527,6 +617,7 @@ int attn_resident_wgs_per_cu(int G, int rep) {
 #undef MOQAE_CASE
     return 1;
 }
+int attn_waves_per_wg(int rep) { return rep == 1 ? 16 : 8; }
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
 #define MOQAE_CASE(GV, RV) if (a.G == GV && a.rep == RV) return launch_gr<GV, RV>(a, s);

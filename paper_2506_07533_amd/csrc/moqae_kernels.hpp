@@ -29,12 +29,13 @@ struct AttnArgs {
     const uint16_t *K_tail, *V_tail;
     float *part; float *out;
     float scale_log2;           // softmax_scale * log2(e)
-    int n_chunks, n_tail, n_split, N, G, Hkv, rep, BH;
+    int n_chunks, n_tail, n_wg, max_partials, N, G, Hkv, rep, BH;
     int bits_of[8];
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
 int attn_resident_wgs_per_cu(int G, int rep);   // occupancy of the split kernel (host query, cached)
+int attn_waves_per_wg(int rep);
+int attn_max_partials(int n_wg, int BH);        // partial slots per row
 
-constexpr int kAttnWaves = 4;   // wavefronts per decode workgroup; each writes its own partial
 
 }  // namespace moqae
