@@ -62,7 +62,7 @@ __device__ __forceinline__ void wave_sync() {
 }
 
 template <int REP> struct WaveState {
-    float m[REP], lsum[REP], z[REP], acc[REP][2];
+    float m[REP], lsum[REP], z[REP], acc[REP][2];        // acc: dims (2l, 2l+1), in units of 2^-24
 };
 
 // scale of the k-th pair of a word after masking: 2^(BITS*k') with k' counted from the shift
@@ -104,11 +104,16 @@ template <int G> struct KRegs {
     uint4 c[4];
     uint32_t m[4][GSMAX];
 };
+template <int G> struct VRegs {
+    static constexpr int MV = 2 * (kD / G);              // V meta words per lane of the largest unit (2 bits)
+    uint4 c[4];
+    uint32_t m[MV];
+};
 
 // Loads the K side of a unit whatever its bit-width: lane l takes the 16-byte slot 64*j + l of
 // each KiB and the meta word(s) of the (token, group) that slot belongs to.  Branch-free: a
-// short unit (nsub < 4) re-reads its last KiB and an fp16 unit reads four words of its own rows
-// in place of the meta words it does not have; both are ignored by the consumer.
+// short unit (nsub < 4) re-reads its last KiB and an fp16 unit reads words of its own rows in
+// place of the meta words it does not have; both are ignored by the consumer.
 template <int G>
 __device__ __forceinline__ void load_k(const Unit &u, int lane, KRegs<G> &k) {
     constexpr int NG = kD / G;
@@ -125,57 +130,74 @@ __device__ __forceinline__ void load_k(const Unit &u, int lane, KRegs<G> &k) {
         if constexpr (KRegs<G>::GSMAX == 2) k.m[j][1] = u.km[g0 + (E > G ? 1 : 0)];
     }
 }
+// The V side: the 16-byte slots 64*j + l of the unit's V KiBs and its (token, group) meta
+// words 64*jj + l, same conventions.
+template <int G>
+__device__ __forceinline__ void load_v(const Unit &u, int lane, VRegs<G> &v) {
+    constexpr int NG = kD / G;
+#pragma unroll
+    for (int j = 0; j < 4; j++) v.c[j] = reinterpret_cast<const uint4 *>(u.vc)[64 * min(j, u.nsub - 1) + lane];
+    const int nvm = u.bits == 16 ? 1 : (u.nsub * (64 / u.bits) * NG) / 64;   // >= 1
+#pragma unroll
+    for (int jj = 0; jj < VRegs<G>::MV; jj++) v.m[jj] = u.vm[64 * min(jj, nvm - 1) + lane];
+}
 
 // ---- one unit of a quantised chunk -----------------------------------------------------------
-template <int BITS, int G, int REP, int NWV, class Prefetch>
-__device__ __forceinline__ void unit_quant(const Unit &u, KRegs<G> &k, Prefetch &&prefetch,
-                                           int lane, int wave, float scale_log2,
-                                           AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
+// Two phases so that the caller can issue its memory requests between them, in code common to all
+// bit-widths (the compiler's wait-count bookkeeping stays exact that way).
+template <int BITS, int G, int REP, int NWV>
+__device__ __forceinline__ void quant_scores(const Unit &u, const KRegs<G> &k,
+                                             int lane, int wave, float scale24,
+                                             AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
     using B = BW<BITS>;
-    constexpr int NG = kD / G;
     constexpr int GS = (B::E > G) ? B::E / G : 1;        // groups inside one slot
-    constexpr int MAXVM = (4 * B::TT * NG / 64) > 0 ? (4 * B::TT * NG / 64) : 1;
     const int part = lane % B::SPR, tok_l = lane / B::SPR;
     const int nsub = u.nsub;
 
-    uint4 vbuf[4];
-    uint32_t vmeta[MAXVM];
-    const int nvm = nsub * B::TT * NG / 64;              // >= 1
-#pragma unroll
-    for (int j = 0; j < 4; j++) vbuf[j] = reinterpret_cast<const uint4 *>(u.vc)[64 * min(j, nsub - 1) + lane];
-#pragma unroll
-    for (int jj = 0; jj < MAXVM; jj++) vmeta[jj] = u.vm[64 * min(jj, nvm - 1) + lane];
-
-    // ---- scores
+    // ---- scores, word by word so that only one word's worth of q pairs is live
 #pragma unroll
     for (int r = 0; r < REP; r++) {
-        uint32_t qv[B::PS];
+        float isum[4][GS];
 #pragma unroll
-        for (int i = 0; i < B::PS; i += 4) {
-            const uint4 t = *reinterpret_cast<const uint4 *>(&L.qtab[B::BI][r][part * B::PS + i]);
-            qv[i] = t.x; qv[i + 1] = t.y; qv[i + 2] = t.z; qv[i + 3] = t.w;
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int gi = 0; gi < GS; gi++) isum[j][gi] = 0.0f;
+#pragma unroll
+        for (int wd = 0; wd < 4; wd++) {
+            uint32_t qv[B::PPW];
+            const uint32_t *qsrc = &L.qtab[B::BI][r][part * B::PS + wd * B::PPW];
+            if constexpr (B::PPW == 8) {
+                const uint4 t0 = *reinterpret_cast<const uint4 *>(qsrc), t1 = *reinterpret_cast<const uint4 *>(qsrc + 4);
+                qv[0] = t0.x; qv[1] = t0.y; qv[2] = t0.z; qv[3] = t0.w; qv[4] = t1.x; qv[5] = t1.y; qv[6] = t1.z; qv[7] = t1.w;
+            } else if constexpr (B::PPW == 4) {
+                const uint4 t0 = *reinterpret_cast<const uint4 *>(qsrc);
+                qv[0] = t0.x; qv[1] = t0.y; qv[2] = t0.z; qv[3] = t0.w;
+            } else {
+                const uint2 t0 = *reinterpret_cast<const uint2 *>(qsrc);
+                qv[0] = t0.x; qv[1] = t0.y;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const uint32_t w = wd == 0 ? k.c[j].x : (wd == 1 ? k.c[j].y : (wd == 2 ? k.c[j].z : k.c[j].w));
+                isum[j][wd / (4 / GS)] = word_dot<BITS>(w, qv, isum[j][wd / (4 / GS)]);
+            }
         }
         float qp[GS];
 #pragma unroll
-        for (int gi = 0; gi < GS; gi++) qp[gi] = L.qpart[B::BI][r][part][gi];
+        for (int gi = 0; gi < GS; gi++) qp[gi] = L.qpart[B::BI][r][part][gi];     // already times 2^-24
         float s4[4], lmax = -INFINITY;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            const uint32_t w[4] = {k.c[j].x, k.c[j].y, k.c[j].z, k.c[j].w};
             float ps = 0.0f;
 #pragma unroll
             for (int gi = 0; gi < GS; gi++) {
-                float isum = 0.0f;
-#pragma unroll
-                for (int wd = gi * (4 / GS); wd < (gi + 1) * (4 / GS); wd++)
-                    isum = word_dot<BITS>(w[wd], &qv[wd * B::PPW], isum);
-                const float sK = half_bits_to_float(k.m[j][gi] & 0xffffu) * kTwo24;
+                const float sK = half_bits_to_float(k.m[j][gi] & 0xffffu);
                 const float zK = half_bits_to_float(k.m[j][gi] >> 16);
-                ps = fmaf(sK, isum, ps);
+                ps = fmaf(sK, isum[j][gi], ps);
                 ps = fmaf(zK, qp[gi], ps);
             }
             ps = group_sum<B::SPR>(ps);
-            s4[j] = (j < nsub) ? ps * scale_log2 : -INFINITY;     // KiB past a short unit: ignored
+            s4[j] = (j < nsub) ? ps * scale24 : -INFINITY;            // KiB past a short unit: ignored
             lmax = fmaxf(lmax, s4[j]);
         }
         rescale(st, r, wave_max(lmax));
@@ -184,16 +206,22 @@ __device__ __forceinline__ void unit_quant(const Unit &u, KRegs<G> &k, Prefetch 
             for (int j = 0; j < 4; j++) L.sc[wave][r][j * B::TT + tok_l] = s4[j];
         }
     }
-    prefetch();                                          // K side of the wavefront's next unit
-
     wave_sync();
+}
+
+template <int BITS, int G, int REP, int NWV>
+__device__ __forceinline__ void quant_values(const VRegs<G> &v, int lane, int wave,
+                                             AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
+    using B = BW<BITS>;
+    constexpr int NG = kD / G;
+    constexpr int MAXVM = (4 * B::TT * NG / 64) > 0 ? (4 * B::TT * NG / 64) : 1;
     // ---- softmax weights, one lane per V (token, group) meta word
     constexpr int n = 32 / BITS;
 #pragma unroll
     for (int jj = 0; jj < MAXVM; jj++) {
         const int idx = 64 * jj + lane, tv = idx / NG, g = idx % NG;
-        const float sV = half_bits_to_float(vmeta[jj] & 0xffffu);
-        const float zV = half_bits_to_float(vmeta[jj] >> 16);
+        const float sV = half_bits_to_float(v.m[jj] & 0xffffu);
+        const float zV = half_bits_to_float(v.m[jj] >> 16);
         const int kk = (tv % n) >> 1;
         const int kp = BITS * (kk < B::KD ? kk : kk - B::KD);
         const float pre = sV * __builtin_bit_cast(float, (uint32_t)(127 - kp) << 23);
@@ -211,34 +239,40 @@ __device__ __forceinline__ void unit_quant(const Unit &u, KRegs<G> &k, Prefetch 
     const int gl = (2 * lane) / G;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-        const uint32_t w[4] = {vbuf[j].x, vbuf[j].y, vbuf[j].z, vbuf[j].w};
+        const uint32_t w[4] = {v.c[j].x, v.c[j].y, v.c[j].z, v.c[j].w};
 #pragma unroll
         for (int r = 0; r < REP; r++) {
-            uint32_t wp[2 * B::PPW];
 #pragma unroll
-            for (int i = 0; i < 2 * B::PPW; i += 4) {
-                const uint4 t = *reinterpret_cast<const uint4 *>(&L.wl[wave][r][gl][j * B::TT + 2 * i]);
-                wp[i] = t.x; wp[i + 1] = t.y; wp[i + 2] = t.z; wp[i + 3] = t.w;
+            for (int hw = 0; hw < 2; hw++) {             // first / second half of the tile's tokens
+                uint32_t wp[B::PPW];
+                const uint16_t *src = &L.wl[wave][r][gl][j * B::TT + hw * 2 * B::PPW];
+                if constexpr (B::PPW == 8) {
+                    const uint4 t0 = *reinterpret_cast<const uint4 *>(src), t1 = *reinterpret_cast<const uint4 *>(src + 8);
+                    wp[0] = t0.x; wp[1] = t0.y; wp[2] = t0.z; wp[3] = t0.w; wp[4] = t1.x; wp[5] = t1.y; wp[6] = t1.z; wp[7] = t1.w;
+                } else if constexpr (B::PPW == 4) {
+                    const uint4 t0 = *reinterpret_cast<const uint4 *>(src);
+                    wp[0] = t0.x; wp[1] = t0.y; wp[2] = t0.z; wp[3] = t0.w;
+                } else {
+                    const uint2 t0 = *reinterpret_cast<const uint2 *>(src);
+                    wp[0] = t0.x; wp[1] = t0.y;
+                }
+                st.acc[r][0] = word_dot<BITS>(w[hw], wp, st.acc[r][0]);        // dim 2l
+                st.acc[r][1] = word_dot<BITS>(w[2 + hw], wp, st.acc[r][1]);    // dim 2l+1
             }
-#pragma unroll
-            for (int wd = 0; wd < 4; wd++)
-                st.acc[r][wd >> 1] = word_dot<BITS>(w[wd], &wp[(wd & 1) * B::PPW], st.acc[r][wd >> 1]);
         }
     }
     wave_sync();
 }
 
 // ---- one unit of raw fp16 rows (16-bit chunks and the FP16 residual) -----------------------
-template <int G, int REP, int NWV, class Prefetch>
-__device__ __forceinline__ void unit_fp16(const Unit &u, KRegs<G> &k, Prefetch &&prefetch,
-                                          int lane, int wave, float scale_log2,
-                                          AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
+// 16 rows: lane l holds dims 8*(l%16)..+7 of row 4*j + l/16, for K and for V alike.  Every lane of
+// a row ends up with the row's score, so the weights need no trip through LDS: the score phase
+// leaves p[r][j] in registers for the value phase.
+template <int G, int REP, int NWV>
+__device__ __forceinline__ void fp16_scores(const Unit &u, const KRegs<G> &k, int lane, float scale_log2,
+                                            AttnLds<G, REP, NWV> &L, WaveState<REP> &st, float (&p4)[REP][4]) {
     const int part = lane & 15, tok_l = lane >> 4;
     const int nvalid = u.nvalid;                          // an fp16 unit always spans 16 rows
-    uint32_t vv[16];
-#pragma unroll
-    for (int t = 0; t < 16; t++) vv[t] = reinterpret_cast<const uint32_t *>(u.vc)[64 * t + lane];
-
 #pragma unroll
     for (int r = 0; r < REP; r++) {
         const uint4 qv = *reinterpret_cast<const uint4 *>(&L.qtab[3][r][part * 4]);
@@ -254,36 +288,54 @@ __device__ __forceinline__ void unit_fp16(const Unit &u, KRegs<G> &k, Prefetch &
             lmax = fmaxf(lmax, s4[j]);
         }
         rescale(st, r, wave_max(lmax));
-        if (part == 0) {
 #pragma unroll
-            for (int j = 0; j < 4; j++) L.sc[wave][r][4 * j + tok_l] = s4[j];
+        for (int j = 0; j < 4; j++) {
+            p4[r][j] = fast_exp2(s4[j] - st.m[r]);                    // masked rows: exp2(-inf) = 0
+            if (part == 0) st.lsum[r] += p4[r][j];
         }
     }
-    prefetch();
-
-    wave_sync();
+}
+template <int G, int REP, int NWV>
+__device__ __forceinline__ void fp16_values(const Unit &u, const VRegs<G> &v, int lane, int wave,
+                                            AttnLds<G, REP, NWV> &L, WaveState<REP> &st, const float (&p4)[REP][4]) {
+    const int tok_l = lane >> 4;
+    const int nvalid = u.nvalid;
 #pragma unroll
     for (int r = 0; r < REP; r++) {
-        const float p = fast_exp2(L.sc[wave][r][lane & 15] - st.m[r]);   // masked rows: exp2(-inf) = 0
+        float acc8[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc8[e] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const float p24 = p4[r][j] * kTwoM24;                     // accumulators carry a factor 2^-24
+            const bool ok = 4 * j + tok_l < nvalid;                   // rows past nvalid may hold NaN / Inf
+            const uint32_t w[4] = {v.c[j].x, v.c[j].y, v.c[j].z, v.c[j].w};
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const float x = ok ? half_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xffffu) : 0.0f;
+                acc8[e] = fmaf(p24, x, acc8[e]);
+            }
+        }
+        // fold the four row groups, then hand every dim to the lane that owns it (2l, 2l+1)
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            acc8[e] += __shfl_xor(acc8[e], 16);
+            acc8[e] += __shfl_xor(acc8[e], 32);
+        }
+        wave_sync();
         if (lane < 16) {
-            st.lsum[r] += p;
-            L.sc[wave][r][lane] = p * kTwoM24;                        // accumulators carry a factor 2^-24
+            float4 t0, t1;
+            t0.x = acc8[0]; t0.y = acc8[1]; t0.z = acc8[2]; t0.w = acc8[3];
+            t1.x = acc8[4]; t1.y = acc8[5]; t1.z = acc8[6]; t1.w = acc8[7];
+            *reinterpret_cast<float4 *>(&L.sc[wave][r][8 * lane]) = t0;
+            *reinterpret_cast<float4 *>(&L.sc[wave][r][8 * lane + 4]) = t1;
         }
+        wave_sync();
+        const float2 mine = *reinterpret_cast<const float2 *>(&L.sc[wave][r][2 * lane]);
+        st.acc[r][0] += mine.x;
+        st.acc[r][1] += mine.y;
+        wave_sync();
     }
-    wave_sync();
-#pragma unroll
-    for (int t = 0; t < 16; t++) {
-        // rows past nvalid may hold anything (NaN, Inf): select, do not multiply by zero
-        const float v0 = (t < nvalid) ? half_bits_to_float(vv[t] & 0xffffu) : 0.0f;
-        const float v1 = (t < nvalid) ? half_bits_to_float(vv[t] >> 16) : 0.0f;
-#pragma unroll
-        for (int r = 0; r < REP; r++) {
-            const float p = L.sc[wave][r][t];
-            st.acc[r][0] = fmaf(p, v0, st.acc[r][0]);
-            st.acc[r][1] = fmaf(p, v1, st.acc[r][1]);
-        }
-    }
-    wave_sync();
 }
 
 // ---- work distribution ----------------------------------------------------------------------
@@ -389,6 +441,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             }
             if (g0 < C) atomicMin(&L.range[0], g0);
             if (g1 < C) atomicMin(&L.range[1], g1);
+            if (n_tiles == 0) __syncthreads();           // no chunk at all: the scan's barrier did not run (qraw)
 
             const uint16_t *qraw = reinterpret_cast<const uint16_t *>(L.qraw);
             for (int i = tid; i < 4 * REP * 64; i += NT) {
@@ -414,7 +467,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                         for (int d = 0; d < len; d++) sq += half_bits_to_float(qraw[r * kD + d0 + d]);
                     }
                 }
-                L.qpart[bi][r][part][gi] = sq;
+                L.qpart[bi][r][part][gi] = bi == 3 ? sq : sq * kTwoM24;   // quantised paths work in units of 2^-24
             }
             __syncthreads();
         }
@@ -422,7 +475,9 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
 
         WaveState<REP> st;
 #pragma unroll
-        for (int r = 0; r < REP; r++) { st.m[r] = -INFINITY; st.lsum[r] = 0.0f; st.z[r] = 0.0f; st.acc[r][0] = 0.0f; st.acc[r][1] = 0.0f; }
+        for (int r = 0; r < REP; r++) {
+            st.m[r] = -INFINITY; st.lsum[r] = 0.0f; st.z[r] = 0.0f; st.acc[r][0] = 0.0f; st.acc[r][1] = 0.0f;
+        }
 
         // ---- (b) the segment in passes of at most kDescCap chunks whose descriptors
         //      (block offset | expert index) sit in LDS; wavefronts draw tickets from LDS
@@ -499,19 +554,35 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 }
             };
 
+            // K is requested half a unit ahead (right after the scores of the current unit), V a
+            // whole unit ahead into the buffer the current unit does not use.
             Unit cur, nxt;
             KRegs<G> kr;
+            VRegs<G> va, vb;
             bool have = next_unit(cur);
-            if (have) load_k<G>(cur, lane, kr);
-            while (have) {
+            if (have) { load_k<G>(cur, lane, kr); load_v<G>(cur, lane, va); }
+            const float scale24 = a.scale_log2 * kTwo24;
+            auto step = [&](const VRegs<G> &vc, VRegs<G> &vn) {
                 const bool have_next = next_unit(nxt);
                 const Unit &pf = have_next ? nxt : cur;  // nothing left: re-read the current unit (ignored)
-                auto prefetch = [&]() { load_k<G>(pf, lane, kr); };
-                if (cur.bits == 2)      unit_quant<2, G, REP, NWV>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
-                else if (cur.bits == 4) unit_quant<4, G, REP, NWV>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
-                else if (cur.bits == 8) unit_quant<8, G, REP, NWV>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
-                else                    unit_fp16<G, REP, NWV>(cur, kr, prefetch, lane, wave, a.scale_log2, L, st);
+                const int bits = cur.bits;
+                float p4[REP][4];                         // fp16 units: weights handed from scores to values
+                load_v<G>(pf, lane, vn);                  // a whole unit ahead
+                if (bits == 2)      quant_scores<2, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                else if (bits == 4) quant_scores<4, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                else if (bits == 8) quant_scores<8, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
+                load_k<G>(pf, lane, kr);                  // half a unit ahead
+                if (bits == 2)      quant_values<2, G, REP, NWV>(vc, lane, wave, L, st);
+                else if (bits == 4) quant_values<4, G, REP, NWV>(vc, lane, wave, L, st);
+                else if (bits == 8) quant_values<8, G, REP, NWV>(vc, lane, wave, L, st);
+                else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
                 cur = nxt; have = have_next;
+            };
+            while (have) {
+                step(va, vb);
+                if (!have) break;
+                step(vb, va);
             }
             if (c0 >= c1) break;                         // empty chunk range: the single pass is done
         }
@@ -583,7 +654,7 @@ __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const floa
     }
 }
 
-template <int REP> constexpr int waves_per_wg() { return REP == 1 ? 16 : 8; }
+template <int REP> constexpr int waves_per_wg() { return REP == 1 ? 12 : 8; }
 
 template <int G, int REP>
 static int resident_wgs_per_cu() {
@@ -617,7 +688,7 @@ int attn_resident_wgs_per_cu(int G, int rep) {
 #undef MOQAE_CASE
     return 1;
 }
-int attn_waves_per_wg(int rep) { return rep == 1 ? 16 : 8; }
+int attn_waves_per_wg(int rep) { return rep == 1 ? 12 : 8; }
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
 #define MOQAE_CASE(GV, RV) if (a.G == GV && a.rep == RV) return launch_gr<GV, RV>(a, s);
