@@ -41,7 +41,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-only", action="store_true",
                     help="profiling aid: after set-up run only decode calls in the timed loop")
+    ap.add_argument("--force-bits", type=int, default=0,
+                    help="sweep aid (implies --decode-only): every chunk takes the expert of this bit-width")
     args = ap.parse_args()
+    if args.force_bits:
+        args.decode_only = True
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
@@ -71,6 +75,8 @@ def main() -> int:
     status = torch.zeros(1, dtype=torch.int32, device=dev)
     # first pass sizes the arenas (realised mix), then two arenas alternate
     mq.route_chunks(cfg, K, 0, C, W1, W2, W3, None, expert, votes)
+    if args.force_bits:
+        expert.fill_(list(w.expert_bits).index(args.force_bits))
     torch.cuda.synchronize()
     e_host = expert.cpu().numpy()
     bits_of = np.array(w.expert_bits)[e_host]

@@ -84,6 +84,22 @@ __device__ __forceinline__ float word_dot(uint32_t w, const uint32_t *pairs, flo
     return acc;
 }
 
+// N consecutive 32-bit words from LDS with the widest reads
+template <int N>
+__device__ __forceinline__ void lds_load_words(const void *src, uint32_t (&dst)[N]) {
+    if constexpr (N == 8) {
+        const uint4 t0 = *reinterpret_cast<const uint4 *>(src), t1 = *(reinterpret_cast<const uint4 *>(src) + 1);
+        dst[0] = t0.x; dst[1] = t0.y; dst[2] = t0.z; dst[3] = t0.w; dst[4] = t1.x; dst[5] = t1.y; dst[6] = t1.z; dst[7] = t1.w;
+    } else if constexpr (N == 4) {
+        const uint4 t0 = *reinterpret_cast<const uint4 *>(src);
+        dst[0] = t0.x; dst[1] = t0.y; dst[2] = t0.z; dst[3] = t0.w;
+    } else {
+        static_assert(N == 2, "2, 4 or 8 words");
+        const uint2 t0 = *reinterpret_cast<const uint2 *>(src);
+        dst[0] = t0.x; dst[1] = t0.y;
+    }
+}
+
 template <int REP>
 __device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_max) {
     const float m_new = fmaxf(st.m[r], unit_max);
@@ -92,11 +108,12 @@ __device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_ma
     st.lsum[r] *= alpha; st.z[r] *= alpha; st.acc[r][0] *= alpha; st.acc[r][1] *= alpha;
 }
 
-// A unit: up to 4 KiB of K codes (nsub KiB) with the matching V codes; wave-uniform.
+// A unit: up to 4 KiB of K codes (nsub KiB) with the matching V codes.  All fields are
+// wave-uniform and live in scalar registers; lgb = log2(bit-width) (1, 2, 3; 4 = raw fp16).
 struct Unit {
-    int bits, nsub, nvalid;                              // nvalid: valid rows of an fp16 unit
+    int lgb, nsub, nvalid;                               // nvalid: valid rows of an fp16 unit
     const uint8_t *kc, *vc;
-    const uint32_t *km, *vm;
+    const uint8_t *km, *vm;
 };
 
 template <int G> struct KRegs {
@@ -110,6 +127,15 @@ template <int G> struct VRegs {
     uint32_t m[MV];
 };
 
+// Loads through a scalar base plus a 32-bit per-lane byte offset (no 64-bit vector address
+// arithmetic: the base of every KiB is computed on the scalar unit).
+__device__ __forceinline__ uint4 ld16(const uint8_t *sbase, uint32_t voff) {
+    return *reinterpret_cast<const uint4 *>(sbase + voff);
+}
+__device__ __forceinline__ uint32_t ld4(const uint8_t *sbase, uint32_t voff) {
+    return *reinterpret_cast<const uint32_t *>(sbase + voff);
+}
+
 // Loads the K side of a unit whatever its bit-width: lane l takes the 16-byte slot 64*j + l of
 // each KiB and the meta word(s) of the (token, group) that slot belongs to.  Branch-free: a
 // short unit (nsub < 4) re-reads its last KiB and an fp16 unit reads words of its own rows in
@@ -117,17 +143,19 @@ template <int G> struct VRegs {
 template <int G>
 __device__ __forceinline__ void load_k(const Unit &u, int lane, KRegs<G> &k) {
     constexpr int NG = kD / G;
-    const int lg = u.bits == 2 ? 1 : (u.bits == 4 ? 2 : 3);          // log2(lanes per token row)
-    const int TT = 64 >> lg, E = 128 >> lg;
-    const int tok_l = lane >> lg, part = lane & ((1 << lg) - 1);
-    const int g_in_row = part * E / G;
+    constexpr int LGG = G == 64 ? 6 : 5;
+    const int lg = min(u.lgb, 3);                         // log2(lanes per token row) of the quantised layouts
+    const uint32_t tok_l = (uint32_t)lane >> lg, part = (uint32_t)lane & ((1u << lg) - 1u);
+    const uint32_t voffm = (tok_l * NG + ((part << (7 - lg)) >> LGG)) * 4u;
+    const uint32_t tile_meta = (uint32_t)((64 >> lg) * NG * 4);          // meta bytes per KiB of codes
+    const bool two = (7 - lg) > LGG;                      // slot wider than a group (2 bits, G = 32)
 #pragma unroll
     for (int j = 0; j < 4; j++) {
         const int jc = min(j, u.nsub - 1);
-        k.c[j] = reinterpret_cast<const uint4 *>(u.kc)[64 * jc + lane];
-        const int g0 = (jc * TT + tok_l) * NG + g_in_row;
-        k.m[j][0] = u.km[g0];
-        if constexpr (KRegs<G>::GSMAX == 2) k.m[j][1] = u.km[g0 + (E > G ? 1 : 0)];
+        k.c[j] = ld16(u.kc + jc * 1024, (uint32_t)lane * 16u);
+        const uint8_t *mb = u.km + jc * tile_meta;
+        k.m[j][0] = ld4(mb, voffm);
+        if constexpr (KRegs<G>::GSMAX == 2) k.m[j][1] = ld4(mb, voffm + (two ? 4u : 0u));
     }
 }
 // The V side: the 16-byte slots 64*j + l of the unit's V KiBs and its (token, group) meta
@@ -136,10 +164,10 @@ template <int G>
 __device__ __forceinline__ void load_v(const Unit &u, int lane, VRegs<G> &v) {
     constexpr int NG = kD / G;
 #pragma unroll
-    for (int j = 0; j < 4; j++) v.c[j] = reinterpret_cast<const uint4 *>(u.vc)[64 * min(j, u.nsub - 1) + lane];
-    const int nvm = u.bits == 16 ? 1 : (u.nsub * (64 / u.bits) * NG) / 64;   // >= 1
+    for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vc + min(j, u.nsub - 1) * 1024, (uint32_t)lane * 16u);
+    const int nvm = u.lgb == 4 ? 1 : (u.nsub * NG) >> u.lgb;              // >= 1
 #pragma unroll
-    for (int jj = 0; jj < VRegs<G>::MV; jj++) v.m[jj] = u.vm[64 * min(jj, nvm - 1) + lane];
+    for (int jj = 0; jj < VRegs<G>::MV; jj++) v.m[jj] = ld4(u.vm + min(jj, nvm - 1) * 256, (uint32_t)lane * 4u);
 }
 
 // ---- one unit of a quantised chunk -----------------------------------------------------------
@@ -154,34 +182,35 @@ __device__ __forceinline__ void quant_scores(const Unit &u, const KRegs<G> &k,
     const int part = lane % B::SPR, tok_l = lane / B::SPR;
     const int nsub = u.nsub;
 
-    // ---- scores, word by word so that only one word's worth of q pairs is live
+    // ---- scores, word by word (one word's worth of q pairs at a time); the q pairs of the next
+    //      word are requested from LDS before the current word is consumed, so that the LDS latency
+    //      hides behind the dot products instead of stalling the wavefront four times per unit
+    float isum[REP][4][GS];
 #pragma unroll
-    for (int r = 0; r < REP; r++) {
-        float isum[4][GS];
+    for (int r = 0; r < REP; r++)
 #pragma unroll
         for (int j = 0; j < 4; j++)
 #pragma unroll
-            for (int gi = 0; gi < GS; gi++) isum[j][gi] = 0.0f;
+            for (int gi = 0; gi < GS; gi++) isum[r][j][gi] = 0.0f;
+    {
+        uint32_t qbuf[2][B::PPW];
+        lds_load_words<B::PPW>(&L.qtab[B::BI][0][part * B::PS], qbuf[0]);
 #pragma unroll
-        for (int wd = 0; wd < 4; wd++) {
-            uint32_t qv[B::PPW];
-            const uint32_t *qsrc = &L.qtab[B::BI][r][part * B::PS + wd * B::PPW];
-            if constexpr (B::PPW == 8) {
-                const uint4 t0 = *reinterpret_cast<const uint4 *>(qsrc), t1 = *reinterpret_cast<const uint4 *>(qsrc + 4);
-                qv[0] = t0.x; qv[1] = t0.y; qv[2] = t0.z; qv[3] = t0.w; qv[4] = t1.x; qv[5] = t1.y; qv[6] = t1.z; qv[7] = t1.w;
-            } else if constexpr (B::PPW == 4) {
-                const uint4 t0 = *reinterpret_cast<const uint4 *>(qsrc);
-                qv[0] = t0.x; qv[1] = t0.y; qv[2] = t0.z; qv[3] = t0.w;
-            } else {
-                const uint2 t0 = *reinterpret_cast<const uint2 *>(qsrc);
-                qv[0] = t0.x; qv[1] = t0.y;
-            }
+        for (int s = 0; s < REP * 4; s++) {
+            const int r = s / 4, wd = s % 4;
+            if (s + 1 < REP * 4)
+                lds_load_words<B::PPW>(&L.qtab[B::BI][(s + 1) / 4][part * B::PS + ((s + 1) % 4) * B::PPW], qbuf[(s + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < 4; j++) {
                 const uint32_t w = wd == 0 ? k.c[j].x : (wd == 1 ? k.c[j].y : (wd == 2 ? k.c[j].z : k.c[j].w));
-                isum[j][wd / (4 / GS)] = word_dot<BITS>(w, qv, isum[j][wd / (4 / GS)]);
+                isum[r][j][wd / (4 / GS)] = word_dot<BITS>(w, qbuf[s & 1], isum[r][j][wd / (4 / GS)]);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
+    }
+#pragma unroll
+    for (int r = 0; r < REP; r++) {
         float qp[GS];
 #pragma unroll
         for (int gi = 0; gi < GS; gi++) qp[gi] = L.qpart[B::BI][r][part][gi];     // already times 2^-24
@@ -193,7 +222,7 @@ __device__ __forceinline__ void quant_scores(const Unit &u, const KRegs<G> &k,
             for (int gi = 0; gi < GS; gi++) {
                 const float sK = half_bits_to_float(k.m[j][gi] & 0xffffu);
                 const float zK = half_bits_to_float(k.m[j][gi] >> 16);
-                ps = fmaf(sK, isum[j][gi], ps);
+                ps = fmaf(sK, isum[r][j][gi], ps);
                 ps = fmaf(zK, qp[gi], ps);
             }
             ps = group_sum<B::SPR>(ps);
@@ -237,28 +266,24 @@ __device__ __forceinline__ void quant_values(const VRegs<G> &v, int lane, int wa
     wave_sync();
     // ---- weighted value sum: lane owns dims (2*lane, 2*lane+1)
     const int gl = (2 * lane) / G;
+    // steps (tile j, head r, tile half hw); the weight pairs of the next step are requested from
+    // LDS before the current step's dot products
+    {
+        uint32_t wbuf[2][B::PPW];
+        lds_load_words<B::PPW>(&L.wl[wave][0][gl][0], wbuf[0]);
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-        const uint32_t w[4] = {v.c[j].x, v.c[j].y, v.c[j].z, v.c[j].w};
-#pragma unroll
-        for (int r = 0; r < REP; r++) {
-#pragma unroll
-            for (int hw = 0; hw < 2; hw++) {             // first / second half of the tile's tokens
-                uint32_t wp[B::PPW];
-                const uint16_t *src = &L.wl[wave][r][gl][j * B::TT + hw * 2 * B::PPW];
-                if constexpr (B::PPW == 8) {
-                    const uint4 t0 = *reinterpret_cast<const uint4 *>(src), t1 = *reinterpret_cast<const uint4 *>(src + 8);
-                    wp[0] = t0.x; wp[1] = t0.y; wp[2] = t0.z; wp[3] = t0.w; wp[4] = t1.x; wp[5] = t1.y; wp[6] = t1.z; wp[7] = t1.w;
-                } else if constexpr (B::PPW == 4) {
-                    const uint4 t0 = *reinterpret_cast<const uint4 *>(src);
-                    wp[0] = t0.x; wp[1] = t0.y; wp[2] = t0.z; wp[3] = t0.w;
-                } else {
-                    const uint2 t0 = *reinterpret_cast<const uint2 *>(src);
-                    wp[0] = t0.x; wp[1] = t0.y;
-                }
-                st.acc[r][0] = word_dot<BITS>(w[hw], wp, st.acc[r][0]);        // dim 2l
-                st.acc[r][1] = word_dot<BITS>(w[2 + hw], wp, st.acc[r][1]);    // dim 2l+1
+        for (int s = 0; s < 4 * REP * 2; s++) {
+            const int j = s / (REP * 2), r = (s / 2) % REP, hw = s % 2;
+            if (s + 1 < 4 * REP * 2) {
+                const int jn = (s + 1) / (REP * 2), rn = ((s + 1) / 2) % REP, hn = (s + 1) % 2;
+                lds_load_words<B::PPW>(&L.wl[wave][rn][gl][jn * B::TT + hn * 2 * B::PPW], wbuf[(s + 1) & 1]);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            const uint32_t w0 = hw == 0 ? v.c[j].x : v.c[j].y;         // dim 2l,   this half of the tile's tokens
+            const uint32_t w1 = hw == 0 ? v.c[j].z : v.c[j].w;         // dim 2l+1
+            st.acc[r][0] = word_dot<BITS>(w0, wbuf[s & 1], st.acc[r][0]);
+            st.acc[r][1] = word_dot<BITS>(w1, wbuf[s & 1], st.acc[r][1]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     wave_sync();
@@ -358,9 +383,10 @@ __host__ __device__ inline int wg_last_of_row(int r, int NW, int BH) {
 }
 int attn_max_partials(int NW, int BH) { return NW / BH + 2; }
 
-// relative cost of one chunk at a bit-width (measured instruction counts of the four paths)
+// Relative cost of one chunk at a bit-width: kernel time per chunk measured on caches of one
+// bit-width (2-bit chunks are bound by instruction issue, 16-bit ones by bytes).
 __device__ __forceinline__ uint32_t chunk_cost(int bits) {
-    return bits == 2 ? 760u : (bits == 4 ? 1010u : (bits == 8 ? 1500u : 2480u));
+    return bits == 2 ? 215u : (bits == 4 ? 330u : (bits == 8 ? 600u : 1090u));
 }
 
 template <int G, int REP, int NWV>
@@ -372,8 +398,8 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // wave-uniform, kept scalar
     const int w = (int)blockIdx.x, NW = (int)gridDim.x;
     const int N = a.N, C = a.n_chunks;
-    const int PC = N >= 256 ? N / 128 : 1;               // tickets per chunk
-    const int TKN = N / PC;                              // tokens per ticket
+    const int LGPC = N >= 256 ? 1 : 0, PC = 1 << LGPC;   // tickets per chunk (N <= 256)
+    const int TKN = N >> LGPC;                           // tokens per ticket
 
     auto bits_of = [&](int e) {
         int b = 0;
@@ -485,72 +511,72 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             const int ce = min(c1, cs + kDescCap);
             const bool last_pass = ce >= c1;
             if (cs > c0) __syncthreads();                // previous pass's descriptors consumed
-            for (int c = cs + tid; c < ce; c += NT) L.desc[c - cs] = orow[c] | (unsigned long long)erow[c];
+            for (int c = cs + tid; c < ce; c += NT) {
+                const int bits = bits_of(erow[c]);
+                const unsigned long long lgb = bits == 2 ? 1 : (bits == 4 ? 2 : (bits == 8 ? 3 : 4));
+                L.desc[c - cs] = orow[c] | lgb;          // block offsets are multiples of 256
+            }
             if (tid == 0) L.ticket = 0;
             __syncthreads();
-            const int n_chunk_tickets = max(0, ce - cs) * PC;
+            const int n_chunk_tickets = max(0, ce - cs) << LGPC;
             const int TK = n_chunk_tickets + ((last_pass && hi_num == (uint32_t)NW) ? (a.n_tail + 127) / 128 : 0);
 
-            auto draw = [&]() -> int {
-                int t = 0;
-                if (lane == 0) t = atomicAdd(&L.ticket, 1);
-                return __builtin_amdgcn_readfirstlane(t);
-            };
-            int c_bits = 0, c_t0 = 0, c_tend = 0, s_next = 0, c_nu = 0, c_tail0 = -1;
+            // tickets: the draw for the next ticket is issued when the current one starts
+            int pend = 0;
+            auto issue_draw = [&]() { if (lane == 0) pend = atomicAdd(&L.ticket, 1); };
+            int c_lgb = 0, c_t0 = 0, c_tend = 0, s_next = 0, c_nu = 0, c_tail0 = -1;
             const uint8_t *c_blk = nullptr;
-            auto resolve = [&](int tk) {                 // ticket tk -> scalars
+            bool have_ticket = false;
+            auto begin_ticket = [&]() {                  // the pending draw becomes the current ticket
+                const int tk = __builtin_amdgcn_readfirstlane(pend);
+                have_ticket = tk < TK;
+                if (!have_ticket) return;
+                issue_draw();
                 if (tk < n_chunk_tickets) {
-                    const unsigned long long dsc = L.desc[tk / PC];
-                    const unsigned long long dsc_u =
-                        (unsigned long long)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dsc) |
-                        ((unsigned long long)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dsc >> 32)) << 32);
-                    c_bits = bits_of((int)(dsc_u & 0xffu));
-                    c_blk = a.arena + (dsc_u & ~0xffull);
-                    c_t0 = (tk % PC) * TKN; c_tend = c_t0 + TKN; c_tail0 = -1;
-                    const int TT = 64 / c_bits;
-                    c_nu = (TKN + 4 * TT - 1) / (4 * TT);
+                    const unsigned long long dsc = L.desc[tk >> LGPC];
+                    const uint32_t dlo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dsc);
+                    const uint32_t dhi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dsc >> 32));
+                    c_lgb = (int)(dlo & 7u);
+                    c_blk = a.arena + (((unsigned long long)dhi << 32) | (dlo & ~0xffu));
+                    c_t0 = (tk & (PC - 1)) * TKN; c_tend = c_t0 + TKN; c_tail0 = -1;
+                    c_nu = (TKN + (256 >> c_lgb) - 1) >> (8 - c_lgb);    // units of 4 KiB of codes
                 } else {                                 // FP16 residual rows [c_tail0, c_tend)
-                    c_bits = 16; c_tail0 = (tk - n_chunk_tickets) * 128; c_tend = min(a.n_tail, c_tail0 + 128);
-                    c_nu = (c_tend - c_tail0 + 15) / 16;
+                    c_lgb = 4; c_tail0 = (tk - n_chunk_tickets) * 128; c_tend = min(a.n_tail, c_tail0 + 128);
+                    c_nu = (c_tend - c_tail0 + 15) >> 4;
                 }
                 s_next = 0;
             };
-            int tk_cur = draw();
-            bool have_ticket = tk_cur < TK;
-            if (have_ticket) resolve(tk_cur);
+            issue_draw();
+            begin_ticket();
             auto next_unit = [&](Unit &un) -> bool {
                 for (;;) {
                     if (!have_ticket) return false;
                     if (s_next < c_nu) {
                         const int s = s_next++;
-                        un.bits = c_bits;
+                        un.lgb = c_lgb;
                         if (c_tail0 >= 0) {
                             const size_t rowb = ((size_t)u * N + (size_t)(c_tail0 + 16 * s)) * 256;
                             un.nsub = 4; un.nvalid = min(16, c_tend - c_tail0 - 16 * s);
                             un.kc = reinterpret_cast<const uint8_t *>(a.K_tail) + rowb;
                             un.vc = reinterpret_cast<const uint8_t *>(a.V_tail) + rowb;
-                            un.km = reinterpret_cast<const uint32_t *>(un.kc); un.vm = un.km;   // no meta: see load_k
+                            un.km = un.kc; un.vm = un.kc;            // no meta: see load_k
                         } else {
-                            const int TT = 64 / c_bits;
-                            const int t0 = c_t0 + s * 4 * TT;
-                            un.nsub = min(4, (c_tend - t0) / TT); un.nvalid = un.nsub * TT;
-                            if (c_bits == 16) {
-                                un.kc = c_blk + (size_t)t0 * 256; un.vc = c_blk + (size_t)N * 256 + (size_t)t0 * 256;
-                                un.km = reinterpret_cast<const uint32_t *>(un.kc); un.vm = un.km;
+                            const int t0 = c_t0 + (s << (8 - c_lgb));
+                            un.nsub = min(4, (c_tend - t0) >> (6 - c_lgb)); un.nvalid = un.nsub << (6 - c_lgb);
+                            if (c_lgb == 4) {
+                                un.kc = c_blk + ((size_t)t0 << 8); un.vc = un.kc + ((size_t)N << 8);
+                                un.km = un.kc; un.vm = un.kc;
                             } else {
-                                const size_t cb = (size_t)N * 16 * c_bits, mb = (size_t)N * NG * 4;
-                                un.kc = c_blk + (size_t)t0 * 16 * c_bits;
-                                un.km = reinterpret_cast<const uint32_t *>(c_blk + cb) + t0 * NG;
-                                un.vc = c_blk + cb + mb + (size_t)t0 * 16 * c_bits;
-                                un.vm = reinterpret_cast<const uint32_t *>(c_blk + 2 * cb + mb) + t0 * NG;
+                                const size_t cb = (size_t)N << (4 + c_lgb), mb = (size_t)N * NG * 4;
+                                un.kc = c_blk + ((size_t)t0 << (4 + c_lgb));
+                                un.km = c_blk + cb + (size_t)t0 * NG * 4;
+                                un.vc = un.kc + cb + mb;
+                                un.vm = un.km + cb + mb;
                             }
                         }
                         return true;
                     }
-                    tk_cur = draw();                     // ticket finished: take the next one
-                    have_ticket = tk_cur < TK;
-                    if (!have_ticket) return false;
-                    resolve(tk_cur);
+                    begin_ticket();                      // ticket finished: take the next one
                 }
             };
 
@@ -565,17 +591,17 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             auto step = [&](const VRegs<G> &vc, VRegs<G> &vn) {
                 const bool have_next = next_unit(nxt);
                 const Unit &pf = have_next ? nxt : cur;  // nothing left: re-read the current unit (ignored)
-                const int bits = cur.bits;
+                const int lgb = cur.lgb;
                 float p4[REP][4];                         // fp16 units: weights handed from scores to values
                 load_v<G>(pf, lane, vn);                  // a whole unit ahead
-                if (bits == 2)      quant_scores<2, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
-                else if (bits == 4) quant_scores<4, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
-                else if (bits == 8) quant_scores<8, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                if (lgb == 1)      quant_scores<2, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                else if (lgb == 2) quant_scores<4, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                else if (lgb == 3) quant_scores<8, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
                 else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
                 load_k<G>(pf, lane, kr);                  // half a unit ahead
-                if (bits == 2)      quant_values<2, G, REP, NWV>(vc, lane, wave, L, st);
-                else if (bits == 4) quant_values<4, G, REP, NWV>(vc, lane, wave, L, st);
-                else if (bits == 8) quant_values<8, G, REP, NWV>(vc, lane, wave, L, st);
+                if (lgb == 1)      quant_values<2, G, REP, NWV>(vc, lane, wave, L, st);
+                else if (lgb == 2) quant_values<4, G, REP, NWV>(vc, lane, wave, L, st);
+                else if (lgb == 3) quant_values<8, G, REP, NWV>(vc, lane, wave, L, st);
                 else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
                 cur = nxt; have = have_next;
             };

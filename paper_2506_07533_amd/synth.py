@@ -138,3 +138,33 @@ def make_workload(w: Workload, layer: int = 0, seq: Optional[int] = None):
     W1, W2, W3 = make_router(w.head_dim, M, w.seed, directions=dirs)
     q = make_q(w.batch, w.n_q_heads, w.head_dim, seed)
     return dict(K=K, V=V, W1=W1, W2=W2, W3=W3, q=q, classes=classes)
+
+
+def make_layer_device(w: Workload, layer: int, device, seq: Optional[int] = None):
+    """One layer of workload `w` drawn directly on the GPU (for layers too large to stage through
+    the host).  Same recipe as make_workload; the bits differ from the host generator's, parity
+    tests copy back the slices they check.  Returns torch tensors."""
+    import torch
+    S = w.seq if seq is None else seq
+    M = len(w.expert_bits)
+    seed = w.seed * 1000 + layer
+    B, H, D, N = w.batch, w.n_kv_heads, w.head_dim, w.chunk
+    C = S // N
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    K = torch.randn((B, H, S, D), generator=g, device=device, dtype=torch.float16)
+    V = torch.randn((B, H, S, D), generator=g, device=device, dtype=torch.float16)
+    chans = outlier_channels(np.random.default_rng([seed, 5]), B * H, D)
+    scale = np.ones((B * H, D), np.float32)
+    np.put_along_axis(scale, chans, 10.0, axis=1)
+    K.mul_(torch.from_numpy(scale).to(device=device, dtype=torch.float16).view(B, H, 1, D))
+    classes = dirs = None
+    if w.mix is not None:
+        dirs = planted_directions(M, D, w.seed)
+        classes = make_classes(B * H, C, w.mix, seed)
+        shift = torch.from_numpy(6.0 * dirs[classes]).to(device=device, dtype=torch.float16)     # [B*H, C, D]
+        K[:, :, : C * N].view(B, H, C, N, D).add_(shift.view(B, H, C, 1, D))
+    W1, W2, W3 = make_router(D, M, w.seed, directions=dirs)
+    q = make_q(B, w.n_q_heads, D, seed)
+    return dict(K=K, V=V, W1=torch.from_numpy(W1).to(device), W2=torch.from_numpy(W2).to(device),
+                W3=torch.from_numpy(W3).to(device), q=torch.from_numpy(q).to(device), classes=classes)
