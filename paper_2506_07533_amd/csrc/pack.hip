@@ -40,10 +40,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PackArgs a) {
     unsigned long long local = 0;
     {
         int64_t u = u0; int cc = cc0;
-        for (int64_t i = i0; i < i1; i++) {
-            const int e = a.expert[u * a.expert_stride + a.chunk_begin + cc];
-            if (e >= a.M) bad = 1; else local += size_at(e);
-            if (++cc == a.n_chunks) { cc = 0; u++; }
+        for (int64_t i = i0; i < i1; i += 8) {            // eight independent loads in flight
+            int e[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                e[k] = (i + k < i1) ? a.expert[u * a.expert_stride + a.chunk_begin + cc] : 0;
+                if (++cc == a.n_chunks) { cc = 0; u++; }
+            }
+#pragma unroll
+            for (int k = 0; k < 8; k++) if (i + k < i1) { if (e[k] >= a.M) bad = 1; else local += size_at(e[k]); }
         }
     }
     scan[tid] = local;
@@ -61,11 +66,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PackArgs a) {
     unsigned long long pos = start + scan[tid] - local;
     {
         int64_t u = u0; int cc = cc0;
-        for (int64_t i = i0; i < i1; i++) {
-            const int e = a.expert[u * a.expert_stride + a.chunk_begin + cc];
-            a.chunk_off[u * a.off_stride + a.chunk_begin + cc] = pos;
-            pos += size_at(e);
-            if (++cc == a.n_chunks) { cc = 0; u++; }
+        for (int64_t i = i0; i < i1; i += 8) {
+            int e[8]; int64_t at[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                at[k] = u * a.off_stride + a.chunk_begin + cc;
+                e[k] = (i + k < i1) ? a.expert[u * a.expert_stride + a.chunk_begin + cc] : 0;
+                if (++cc == a.n_chunks) { cc = 0; u++; }
+            }
+#pragma unroll
+            for (int k = 0; k < 8; k++) if (i + k < i1) { a.chunk_off[at[k]] = pos; pos += size_at(e[k]); }
         }
     }
     __syncthreads();                                  // every thread has read *arena_used

@@ -1,8 +1,8 @@
 // moqae_route_chunks: router MLP (Eq. (1), Sec. 3.2), token top-1 and chunk majority vote
 // (Eq. (2)), routing freezing (Sec. 3.4).
 //
-// One workgroup per (sequence, KV head, chunk).  The chunk's key rows are staged through LDS
-// with coalesced 16-byte loads (128 rows at a time); one lane then owns one token and runs
+// One wavefront per (sequence, KV head, chunk).  A lane owns one token: it requests its whole
+// 256-byte key row at once (no LDS, no barrier in the loop) and runs
 // the 2*M length-D dot products as sequential binary32 sums (the products of two fp16 values
 // are exact in binary32, so a fused multiply-add rounds exactly like multiply-then-add), which
 // is what makes the integer result reproducible bit for bit.  The router weights are
@@ -33,13 +33,10 @@ __device__ __forceinline__ float exp_pinned(float x) {
     return __fmul_rn(p, s);
 }
 
-constexpr int kRouteThreads = 128;
-constexpr int kRowU4 = 17;       // 16 x 16-byte pieces per key row + one of padding (LDS bank spread)
+constexpr int kRouteThreads = 64;         // one wavefront per workgroup, one lane per token
 
 template <int M>
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a) {
-    __shared__ uint4 tile[kRouteThreads * kRowU4];
-    __shared__ int cnt[8];
     __shared__ float w3f[72];                        // W3 as binary32, then the optional bias
 
     const int c = a.chunk_begin + (int)blockIdx.x;
@@ -52,85 +49,108 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a) {
         if (a.votes && tid < M) a.votes[eidx * M + tid] = 0;
         return;
     }
-    if (tid < 8) cnt[tid] = 0;
     if (tid < M * M) w3f[tid] = half_bits_to_float(a.W3[tid]);
     if (a.bias && tid < M) w3f[64 + tid] = a.bias[tid];
+    __syncthreads();
 
     const int b = u / a.Hkv, h = u % a.Hkv;
     const uint16_t *Kc = a.K + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h + (int64_t)c * a.N * a.stride_s;
     const uint32_t *W1w = reinterpret_cast<const uint32_t *>(a.W1);
     const uint32_t *W2w = reinterpret_cast<const uint32_t *>(a.W2);
 
-    for (int row0 = 0; row0 < a.N; row0 += kRouteThreads) {
-        const int rows = min(kRouteThreads, a.N - row0);
-        __syncthreads();                             // previous slab fully consumed (and cnt zeroed)
-#pragma unroll 4
-        for (int i = tid; i < rows * 16; i += kRouteThreads) {
-            const int r = i >> 4, p = i & 15;
-            tile[r * kRowU4 + p] = *reinterpret_cast<const uint4 *>(Kc + (int64_t)(row0 + r) * a.stride_s + p * 8);
+    int cnt[M];                                      // votes, identical in every lane
+#pragma unroll
+    for (int k = 0; k < M; k++) cnt[k] = 0;
+
+    float accA[M], accB[M];
+    // The loop runs over half rows (64 dims = one 128-byte line per lane); the next half row is
+    // requested before the current one is consumed, across the 64-token passes too.
+    const int n_half = 2 * ((a.N + kRouteThreads - 1) / kRouteThreads);
+    auto half_ptr = [&](int hr) {
+        const int row = (hr >> 1) * kRouteThreads + tid;
+        return reinterpret_cast<const uint4 *>(Kc + (int64_t)(row < a.N ? row : 0) * a.stride_s) + (hr & 1) * 8;
+    };
+    uint4 xn[8];
+    {
+        const uint4 *hp = half_ptr(0);
+#pragma unroll
+        for (int p = 0; p < 8; p++) xn[p] = hp[p];
+    }
+#pragma unroll 1
+    for (int hr = 0; hr < n_half; hr++) {
+        const int row0 = (hr >> 1) * kRouteThreads;
+        const bool active = row0 + tid < a.N;        // N is a multiple of 32: the last pass may be half empty
+        uint4 xr[8];
+#pragma unroll
+        for (int p = 0; p < 8; p++) xr[p] = xn[p];
+        if (hr + 1 < n_half) {
+            const uint4 *hp = half_ptr(hr + 1);
+#pragma unroll
+            for (int p = 0; p < 8; p++) xn[p] = hp[p];
         }
-        __syncthreads();
-        if (tid < rows) {
-            float accA[M], accB[M];
+        if (!(hr & 1)) {
 #pragma unroll
             for (int m = 0; m < M; m++) { accA[m] = 0.0f; accB[m] = 0.0f; }
-            // two key rows of the weight matrices per step so that the fp16 pairs fall on 32-bit words
-            for (int p = 0; p < 16; p++) {
-                const uint4 xv = tile[tid * kRowU4 + p];
-                const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
+        }
+        // two key dims (two rows of the weight matrices) per step so that the fp16 pairs fall on 32-bit words
+        const int dbase = (hr & 1) * 64;
 #pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const int d = p * 8 + e;          // even; rows d, d+1 of W = 2*M halves = M words
-                    const float x0 = half_bits_to_float(xw[e >> 1] & 0xffffu);
-                    const float x1 = half_bits_to_float(xw[e >> 1] >> 16);
-                    uint32_t w1[M], w2[M];
+        for (int p = 0; p < 8; p++) {
+            const uint32_t xw[4] = {xr[p].x, xr[p].y, xr[p].z, xr[p].w};
 #pragma unroll
-                    for (int m = 0; m < M; m++) { w1[m] = W1w[d / 2 * M + m]; w2[m] = W2w[d / 2 * M + m]; }
+            for (int e = 0; e < 8; e += 2) {
+                const int d = dbase + p * 8 + e;      // even; rows d, d+1 of W = 2*M halves = M words
+                const float x0 = half_bits_to_float(xw[e >> 1] & 0xffffu);
+                const float x1 = half_bits_to_float(xw[e >> 1] >> 16);
+                uint32_t w1[M], w2[M];
 #pragma unroll
-                    for (int m = 0; m < M; m++) {     // row d: halves 0..M-1 of the 2*M block
-                        const int i0 = m, i1 = M + m; // half index inside the two-row block
-                        const float wa0 = half_bits_to_float((w1[i0 >> 1] >> (16 * (i0 & 1))) & 0xffffu);
-                        const float wb0 = half_bits_to_float((w2[i0 >> 1] >> (16 * (i0 & 1))) & 0xffffu);
-                        accA[m] = fmaf(x0, wa0, accA[m]);
-                        accB[m] = fmaf(x0, wb0, accB[m]);
-                        const float wa1 = half_bits_to_float((w1[i1 >> 1] >> (16 * (i1 & 1))) & 0xffffu);
-                        const float wb1 = half_bits_to_float((w2[i1 >> 1] >> (16 * (i1 & 1))) & 0xffffu);
-                        accA[m] = fmaf(x1, wa1, accA[m]);
-                        accB[m] = fmaf(x1, wb1, accB[m]);
-                    }
+                for (int m = 0; m < M; m++) { w1[m] = W1w[d / 2 * M + m]; w2[m] = W2w[d / 2 * M + m]; }
+#pragma unroll
+                for (int m = 0; m < M; m++) {
+                    const int i0 = m, i1 = M + m;     // half index inside the two-row block
+                    const float wa0 = half_bits_to_float((w1[i0 >> 1] >> (16 * (i0 & 1))) & 0xffffu);
+                    const float wb0 = half_bits_to_float((w2[i0 >> 1] >> (16 * (i0 & 1))) & 0xffffu);
+                    accA[m] = fmaf(x0, wa0, accA[m]);
+                    accB[m] = fmaf(x0, wb0, accB[m]);
+                    const float wa1 = half_bits_to_float((w1[i1 >> 1] >> (16 * (i1 & 1))) & 0xffffu);
+                    const float wb1 = half_bits_to_float((w2[i1 >> 1] >> (16 * (i1 & 1))) & 0xffffu);
+                    accA[m] = fmaf(x1, wa1, accA[m]);
+                    accB[m] = fmaf(x1, wb1, accB[m]);
                 }
             }
-            float hid[M];
-#pragma unroll
-            for (int m = 0; m < M; m++) {
-                const float z = __fmul_rn(accA[m], accB[m]);
-                const float e = exp_pinned(-z);
-                hid[m] = __fdiv_rn(z, __fadd_rn(1.0f, e));          // SiLU(z) = z / (1 + exp(-z))
-            }
-            int top = 0; float ptop = 0.0f;
-#pragma unroll
-            for (int k = 0; k < M; k++) {
-                float acc = 0.0f;
-#pragma unroll
-                for (int j = 0; j < M; j++) acc = __fadd_rn(acc, __fmul_rn(hid[j], w3f[j * M + k]));
-                if (a.bias) acc = __fadd_rn(acc, w3f[64 + k]);
-                if (k == 0) ptop = acc;
-                else if (acc > ptop) { top = k; ptop = acc; }       // strict: the first maximum wins
-            }
-#pragma unroll
-            for (int k = 0; k < M; k++) {
-                const unsigned long long mask = __ballot(top == k);
-                if ((tid & 63) == 0 && mask) atomicAdd(&cnt[k], __popcll(mask));
-            }
+            __builtin_amdgcn_sched_barrier(0);        // keeps the uniform weight loads of later steps from piling up
         }
+        if (!(hr & 1)) continue;
+        float hid[M];
+#pragma unroll
+        for (int m = 0; m < M; m++) {
+            const float z = __fmul_rn(accA[m], accB[m]);
+            const float e = exp_pinned(-z);
+            hid[m] = __fdiv_rn(z, __fadd_rn(1.0f, e));              // SiLU(z) = z / (1 + exp(-z))
+        }
+        int top = 0; float ptop = 0.0f;
+#pragma unroll
+        for (int k = 0; k < M; k++) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int j = 0; j < M; j++) acc = __fadd_rn(acc, __fmul_rn(hid[j], w3f[j * M + k]));
+            if (a.bias) acc = __fadd_rn(acc, w3f[64 + k]);
+            if (k == 0) ptop = acc;
+            else if (acc > ptop) { top = k; ptop = acc; }           // strict: the first maximum wins
+        }
+#pragma unroll
+        for (int k = 0; k < M; k++) cnt[k] += __popcll(__ballot(active && top == k));
     }
-    __syncthreads();
     if (tid == 0) {
-        int best = 0;
-        for (int k = 1; k < M; k++) if (cnt[k] > cnt[best]) best = k;
+        int best = 0, cbest = cnt[0];
+#pragma unroll
+        for (int k = 1; k < M; k++) if (cnt[k] > cbest) { best = k; cbest = cnt[k]; }
         a.expert[eidx] = (uint8_t)best;
     }
-    if (a.votes && tid < M) a.votes[eidx * M + tid] = cnt[tid];
+    if (a.votes) {
+#pragma unroll
+        for (int k = 0; k < M; k++) if (tid == k) a.votes[eidx * M + k] = cnt[k];
+    }
 }
 
 template <int M>
