@@ -43,7 +43,19 @@ def main() -> int:
                     help="profiling aid: after set-up run only decode calls in the timed loop")
     ap.add_argument("--force-bits", type=int, default=0,
                     help="sweep aid (implies --decode-only): every chunk takes the expert of this bit-width")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="counter calibration: run a plain elementwise kernel that reads 1 GiB and writes 1 GiB, "
+                         "five times, and exit (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE are scaled by what they read for it)")
     args = ap.parse_args()
+    if args.copy_probe:
+        import torch
+        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe": "torch add(int32, 1)", "read_bytes": 1 << 30, "write_bytes": 1 << 30, "launches": 5}))
+        return 0
     if args.force_bits:
         args.decode_only = True
     if args.gpus != 1:

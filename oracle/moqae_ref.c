@@ -299,11 +299,18 @@ void moqae_ref_quantize_group(const uint16_t *x, int G, int bits, uint8_t *codes
  *
  * K codes: token-major rows.  Row t holds D*b/32 words; in-row word d / n,
  *          in-word index d % n.
- * V codes: tiles of TT = 64/b tokens (one tile = 2*D words).  In a tile,
- *          dimension d owns two consecutive words at word offset 2*d
- *          (so dims 2l, 2l+1 form the 16-byte slot l); the TT codes of the
- *          dimension are indexed by the token: word tau / n, in-word index
- *          tau % n.                                                        */
+ * V codes: dimension-major inside blocks of tokens, cut into 1-KiB tiles of
+ *          64 slots x 4 words.  With TW = 32/b tokens per word, a slot holds
+ *          a slice of TQ = max(TW, 8) consecutive tokens of one dimension
+ *          (WD = TQ/TW words) for CPK = 4/WD dimensions that lie 16 apart.
+ *          A token block is TB = 4*TQ tokens; token t of the chunk sits in
+ *          block t / TB, slice qd = (t % TB) / TQ, and inside the slice in
+ *          word w = (t % TQ) / TW at in-word index e = t % TW.
+ *          Dimension d = 16*ct + j belongs to tile cg = ct / CPK of its
+ *          block (D / (16*CPK) tiles per block), slot 16*qd + j, word
+ *          n = (ct % CPK) * WD + w of the slot:
+ *              word index = ((block * D/(16*CPK) + cg) * 64 + 16*qd + j) * 4 + n.
+ *          Needs D % 64 == 0 and N % 64 == 0.                              */
 static void k_code_pos(int t, int d, int D, int b, uint32_t *word, int *bit)
 {
     int n = 32 / b, e = d % n;
@@ -312,9 +319,18 @@ static void k_code_pos(int t, int d, int D, int b, uint32_t *word, int *bit)
 }
 static void v_code_pos(int t, int d, int D, int b, uint32_t *word, int *bit)
 {
-    int n = 32 / b, TT = 64 / b, tile = t / TT, tau = t % TT, e = tau % n;
-    *word = (uint32_t)tile * (uint32_t)(2 * D) + (uint32_t)(2 * d) + (uint32_t)(tau / n);
+    int TW = 32 / b, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, TB = 4 * TQ;
+    int block = t / TB, qd = (t % TB) / TQ, w = (t % TQ) / TW, e = t % TW;
+    int ct = d / 16, j = d % 16, cg = ct / CPK, n = (ct % CPK) * WD + w;
+    *word = (uint32_t)(((block * (D / (16 * CPK)) + cg) * 64 + 16 * qd + j) * 4 + n);
     *bit  = 16 * (e % 2) + b * (e / 2);
+}
+/* The V layout above exists for quantised experts only when it tiles evenly. */
+static int layout_ok(const moqae_ref_cfg *c)
+{
+    for (int j = 0; j < c->n_experts; j++)
+        if (c->expert_bits[j] < 16 && (c->head_dim % 64 || c->chunk % 64)) return 0;
+    return 1;
 }
 
 static void put_code(uint8_t *area, uint32_t word, int bit, uint32_t code)
@@ -410,7 +426,7 @@ int moqae_quantize_pack_ref(const moqae_ref_cfg *cfg,
                             uint64_t *chunk_off, int64_t off_stride_bh,
                             int32_t *status)
 {
-    if (!cfg_ok(cfg) || !K || !V || !expert || !arena || !arena_used || !chunk_off || !status) return REF_E_INVAL;
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !K || !V || !expert || !arena || !arena_used || !chunk_off || !status) return REF_E_INVAL;
     if (chunk_begin < 0 || chunk_end < chunk_begin) return REF_E_INVAL;
     if (expert_stride_bh < chunk_end || off_stride_bh < chunk_end) return REF_E_INVAL;
     if (*status != 0) return REF_OK;
@@ -462,7 +478,7 @@ int moqae_decode_attn_ref(const moqae_ref_cfg *cfg,
                           double softmax_scale,
                           double *out)
 {
-    if (!cfg_ok(cfg) || !q || !out) return REF_E_INVAL;
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !q || !out) return REF_E_INVAL;
     if (n_chunks < 0 || n_tail < 0 || n_tail >= cfg->chunk) return REF_E_INVAL;
     if (n_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride_bh < n_chunks)) return REF_E_INVAL;
     if (n_tail > 0 && (!K_tail || !V_tail)) return REF_E_INVAL;

@@ -27,6 +27,14 @@ bool cfg_ok(const moqae_cfg *c) {
     return true;
 }
 
+// The packed layout (pack and decode calls): V tiles span 64 tokens, and the decode kernel's
+// matrix-core path for grouped queries holds (query head, group) pairs in the 16 rows of a tile.
+bool layout_ok(const moqae_cfg *c) {
+    if (c->chunk % 64) return false;
+    const int rep = c->n_q_heads / c->n_kv_heads;
+    return rep == 1 || rep * (kD / c->group) <= 16;
+}
+
 int first_16bit(const moqae_cfg *c) {
     for (int j = 0; j < c->n_experts; j++) if (c->expert_bits[j] == 16) return j;
     return -1;
@@ -107,7 +115,7 @@ uint64_t moqae_arena_upper_bound(const moqae_cfg *cfg, int64_t n_chunks_total) {
 }
 
 uint64_t moqae_decode_workspace_bytes(const moqae_cfg *cfg, int32_t n_chunks) {
-    if (!cfg_ok(cfg) || n_chunks < 0) return 0;
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || n_chunks < 0) return 0;
     return workspace_bytes(cfg, n_chunks);
 }
 
@@ -149,7 +157,7 @@ int moqae_quantize_pack(const moqae_cfg *cfg,
                         uint64_t *chunk_off, int64_t off_stride,
                         int32_t *status,
                         void *stream) {
-    if (!cfg_ok(cfg) || !K || !V || !expert || !arena || !arena_used || !chunk_off || !status) return MOQAE_E_INVAL;
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !K || !V || !expert || !arena || !arena_used || !chunk_off || !status) return MOQAE_E_INVAL;
     if (chunk_begin < 0 || chunk_end < chunk_begin) return MOQAE_E_INVAL;
     if (expert_stride < chunk_end || off_stride < chunk_end) return MOQAE_E_INVAL;
     if (!strides_ok(cfg, stride_b, stride_h, stride_s) || !aligned(K, 16) || !aligned(V, 16)) return MOQAE_E_INVAL;
@@ -179,7 +187,7 @@ int moqae_decode_attn(const moqae_cfg *cfg,
                       float *out,
                       void *workspace, uint64_t workspace_bytes,
                       void *stream) {
-    if (!cfg_ok(cfg) || !q || !out || !workspace) return MOQAE_E_INVAL;
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !q || !out || !workspace) return MOQAE_E_INVAL;
     if (n_chunks < 0 || n_tail < 0 || n_tail >= cfg->chunk || n_chunks + n_tail <= 0) return MOQAE_E_INVAL;
     if (n_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride < n_chunks)) return MOQAE_E_INVAL;
     if (n_tail > 0 && (!K_tail || !V_tail)) return MOQAE_E_INVAL;

@@ -62,7 +62,9 @@ __device__ __forceinline__ void wave_sync() {
 }
 
 template <int REP> struct WaveState {
-    float m[REP], lsum[REP], z[REP], acc[REP][2];        // acc: dims (2l, 2l+1), in units of 2^-24
+    float m[REP], lsum[REP], z[REP];
+    float acc[REP][2];                                   // raw fp16 rows: dims (2l, 2l+1), in units of 2^-24
+    float accq[REP][8];                                  // quantised V: dims 16*ct + l%16, this lane's token slices only
 };
 
 // scale of the k-th pair of a word after masking: 2^(BITS*k') with k' counted from the shift
@@ -106,6 +108,8 @@ __device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_ma
     const float alpha = fast_exp2(st.m[r] - m_new);       // first unit: exp2(-inf) = 0
     st.m[r] = m_new;
     st.lsum[r] *= alpha; st.z[r] *= alpha; st.acc[r][0] *= alpha; st.acc[r][1] *= alpha;
+#pragma unroll
+    for (int ct = 0; ct < 8; ct++) st.accq[r][ct] *= alpha;
 }
 
 // A unit: up to 4 KiB of K codes (nsub KiB) with the matching V codes.  All fields are
@@ -264,25 +268,37 @@ __device__ __forceinline__ void quant_values(const VRegs<G> &v, int lane, int wa
     }
 
     wave_sync();
-    // ---- weighted value sum: lane owns dims (2*lane, 2*lane+1)
-    const int gl = (2 * lane) / G;
-    // steps (tile j, head r, tile half hw); the weight pairs of the next step are requested from
-    // LDS before the current step's dot products
+    // ---- weighted value sum.  V layout: KiB j of the unit, slot l = 16*qd + jj, word nw: a slice of
+    //      TQ = max(TW, 8) tokens (TW = 32/BITS per word, WD = TQ/TW words) of dim 16*ct + jj, for
+    //      CPK = 4/WD column tiles ct per KiB.  The weights of a slice are shared by the words of a
+    //      "key group" (same group of dims, same word of the slice); the next key group's weight
+    //      pairs are requested from LDS before the current one's dot products.
+    constexpr int TW = 32 / BITS, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, TB = 4 * TQ, KPB = 8 / CPK;
+    constexpr int KG = (WD == 2 || G == 32) ? 2 : 1;     // key groups per KiB
+    constexpr int NSTEP = 4 * KG * REP;
+    const int qd = lane >> 4;
+    auto ct_of = [](int j, int nw) { return (j % KPB) * CPK + nw / WD; };
+    auto word_of = [](int kg, int i) { return KG == 1 ? i : (WD == 2 ? kg + 2 * i : 2 * kg + i); };   // i-th word of key group kg
+    auto wl_addr = [&](int s_) -> const uint16_t * {
+        const int j = s_ / (KG * REP), kg = (s_ / REP) % KG, r = s_ % REP;
+        const int g = (16 * ct_of(j, word_of(kg, 0))) / G;
+        const int tb = (j / KPB) * TB + (WD == 2 ? kg * TW : 0);
+        return &L.wl[wave][r][g][tb + qd * TQ];
+    };
     {
         uint32_t wbuf[2][B::PPW];
-        lds_load_words<B::PPW>(&L.wl[wave][0][gl][0], wbuf[0]);
+        lds_load_words<B::PPW>(wl_addr(0), wbuf[0]);
 #pragma unroll
-        for (int s = 0; s < 4 * REP * 2; s++) {
-            const int j = s / (REP * 2), r = (s / 2) % REP, hw = s % 2;
-            if (s + 1 < 4 * REP * 2) {
-                const int jn = (s + 1) / (REP * 2), rn = ((s + 1) / 2) % REP, hn = (s + 1) % 2;
-                lds_load_words<B::PPW>(&L.wl[wave][rn][gl][jn * B::TT + hn * 2 * B::PPW], wbuf[(s + 1) & 1]);
-            }
+        for (int s = 0; s < NSTEP; s++) {
+            const int j = s / (KG * REP), kg = (s / REP) % KG, r = s % REP;
+            if (s + 1 < NSTEP) lds_load_words<B::PPW>(wl_addr(s + 1), wbuf[(s + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
-            const uint32_t w0 = hw == 0 ? v.c[j].x : v.c[j].y;         // dim 2l,   this half of the tile's tokens
-            const uint32_t w1 = hw == 0 ? v.c[j].z : v.c[j].w;         // dim 2l+1
-            st.acc[r][0] = word_dot<BITS>(w0, wbuf[s & 1], st.acc[r][0]);
-            st.acc[r][1] = word_dot<BITS>(w1, wbuf[s & 1], st.acc[r][1]);
+            const uint32_t wv[4] = {v.c[j].x, v.c[j].y, v.c[j].z, v.c[j].w};
+#pragma unroll
+            for (int i = 0; i < 4 / KG; i++) {
+                const int nw = word_of(kg, i), ct = ct_of(j, nw);
+                st.accq[r][ct] = word_dot<BITS>(wv[nw], wbuf[s & 1], st.accq[r][ct]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -503,6 +519,8 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
 #pragma unroll
         for (int r = 0; r < REP; r++) {
             st.m[r] = -INFINITY; st.lsum[r] = 0.0f; st.z[r] = 0.0f; st.acc[r][0] = 0.0f; st.acc[r][1] = 0.0f;
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) st.accq[r][ct] = 0.0f;
         }
 
         // ---- (b) the segment in passes of at most kDescCap chunks whose descriptors
@@ -626,6 +644,14 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             dst[2 * lane] = fmaf(st.acc[r][0], kTwo24, zg);
             dst[2 * lane + 1] = fmaf(st.acc[r][1], kTwo24, zg);
             if (lane == 0) { dst[kD] = st.m[r]; dst[kD + 1] = lt; }
+            wave_sync();
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) {              // fold the four token slices of every column tile
+                float t = st.accq[r][ct];
+                t += __shfl_xor(t, 16);
+                t += __shfl_xor(t, 32);
+                if (lane < 16) dst[16 * ct + lane] = fmaf(t, kTwo24, dst[16 * ct + lane]);
+            }
         }
         __syncthreads();
         const int slot = w - wg_first_of_row(u, NW, a.BH);

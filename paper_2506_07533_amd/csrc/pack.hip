@@ -7,7 +7,7 @@
 //   pack_kernel  one workgroup per (chunk, K or V).  16 lanes own one token row (8 dims each),
 //                group min/max by DPP, codes in registers.  K words are assembled in registers
 //                (row-major layout); V codes go through LDS as bytes and are gathered
-//                token-wise into the tile-transposed layout.  HBM-bound: reads 2*N*D*2 bytes,
+//                token-wise into the dimension-major tile layout.  HBM-bound: reads 2*N*D*2 bytes,
 //                writes the block.
 #include "moqae_dev.hpp"
 #include "moqae_kernels.hpp"
@@ -175,13 +175,17 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     if (!isV) return;
 
     __syncthreads();
-    // V: tiles of TT = 64/bits tokens, 2*D words per tile; dim d owns words 2d, 2d+1 of its tile.
-    const int n = 32 / bits, TT = 64 / bits;
+    // V: dimension-major 1-KiB tiles of 64 slots x 4 words.  A slot holds TQ = max(TW, 8) consecutive
+    // tokens (TW = 32/bits per word, WD = TQ/TW words) of CPK = 4/WD dimensions that lie 16 apart;
+    // slot 16*qd + j of tile cg of a block of 4*TQ tokens: dims 16*(cg*CPK + n/WD) + j, token slice qd.
+    const int TW = 32 / bits, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, NCG = kD / (16 * CPK);
     const int n_words = N * kD * bits / 32;
     for (int wv = tid; wv < n_words; wv += kPackThreads) {
-        const int tile = wv >> 8, r = wv & 255, d = r >> 1, t0 = tile * TT + (r & 1) * n;
+        const int n = wv & 3, l = (wv >> 2) & 63, kib = wv >> 8;
+        const int cg = kib % NCG, block = kib / NCG, qd = l >> 4, j = l & 15;
+        const int d = 16 * (cg * CPK + n / WD) + j, t0 = block * 4 * TQ + qd * TQ + (n % WD) * TW;
         uint32_t w = 0;
-        for (int e = 0; e < n; e++) w |= (uint32_t)vcodes[(t0 + e) * kD + d] << code_shift(e, bits);
+        for (int e = 0; e < TW; e++) w |= (uint32_t)vcodes[(t0 + e) * kD + d] << code_shift(e, bits);
         codes_w[wv] = w;
     }
 }

@@ -123,8 +123,8 @@ def _pack_both(mq, ref, cfg, rcfg, K, V, c0, c1, expert, start=0, slack=0):
     return (arena, used, off, status), (arena_ref, used_ref, off_ref, st_ref)
 
 
-@pytest.mark.parametrize("B,Hkv,N,G,C", [(1, 8, 64, 32, 32), (2, 2, 128, 64, 9), (1, 3, 32, 32, 6),
-                                         (1, 2, 256, 64, 5), (1, 1, 96, 32, 8), (1, 2, 32, 64, 7)])
+@pytest.mark.parametrize("B,Hkv,N,G,C", [(1, 8, 64, 32, 32), (2, 2, 128, 64, 9), (1, 3, 64, 32, 6),
+                                         (1, 2, 256, 64, 5), (1, 1, 192, 32, 8), (1, 2, 64, 64, 7)])
 def test_pack_bit_exact(mq, ref, B, Hkv, N, G, C):
     rng = np.random.default_rng(N + G + C)
     cfg, rcfg = _cfgs(mq, ref, B, Hkv, Hkv, N, G, (2, 4, 8, 16), 1)
@@ -225,9 +225,10 @@ def _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, bits, seed, scale=None, expert=N
     (2, 4, 4, 128, 64, 20, 1),
     (1, 8, 2, 128, 64, 33, 127),     # GQA x4, long tail
     (1, 4, 2, 256, 64, 7, 200),      # GQA x2
-    (1, 8, 1, 32, 32, 40, 31),       # GQA x8, smallest chunk
-    (2, 2, 2, 32, 64, 3, 0),
-    (1, 2, 2, 96, 64, 11, 50),
+    (1, 8, 1, 64, 64, 40, 31),       # GQA x8, smallest chunk
+    (1, 2, 2, 192, 32, 5, 100),      # three 64-token blocks per chunk
+    (2, 2, 2, 64, 64, 3, 0),
+    (1, 2, 2, 192, 64, 11, 50),
     (1, 1, 1, 128, 64, 600, 5),      # more chunks than splits*64: several descriptor batches
 ])
 def test_attention_mixed_bits(mq, ref, B, Hq, Hkv, N, G, C, T):
@@ -236,7 +237,7 @@ def test_attention_mixed_bits(mq, ref, B, Hq, Hkv, N, G, C, T):
 
 
 @pytest.mark.parametrize("bits", [(2,), (4,), (8,), (16,)])
-@pytest.mark.parametrize("N,G,rep", [(128, 64, 1), (64, 32, 4), (32, 32, 1), (256, 64, 2)])
+@pytest.mark.parametrize("N,G,rep", [(128, 64, 1), (64, 32, 4), (192, 32, 1), (256, 64, 2)])
 def test_attention_single_bit_width(mq, ref, bits, N, G, rep):
     err = _attn_case(mq, ref, 1, 2 * rep, 2, N, G, 12, 17, bits, seed=bits[0] + N, freeze=0)
     assert err <= ATTN_TOL, err
@@ -247,7 +248,7 @@ def test_attention_degenerate_cases(mq, ref):
     assert _attn_case(mq, ref, 1, 4, 2, 64, 32, 0, 1, (2, 16), seed=1) <= ATTN_TOL
     assert _attn_case(mq, ref, 2, 2, 2, 128, 64, 0, 97, (2, 16), seed=2) <= ATTN_TOL
     # one chunk, no residual
-    assert _attn_case(mq, ref, 1, 2, 2, 32, 32, 1, 0, (4, 16), seed=3) <= ATTN_TOL
+    assert _attn_case(mq, ref, 1, 2, 2, 64, 32, 1, 0, (4, 16), seed=3) <= ATTN_TOL
     # a sharp softmax (one key dominates) and a flat one
     assert _attn_case(mq, ref, 1, 2, 2, 64, 64, 8, 3, (2, 4, 8, 16), seed=4, scale=3.0) <= ATTN_TOL
     assert _attn_case(mq, ref, 1, 2, 2, 64, 64, 8, 3, (2, 4, 8, 16), seed=5, scale=0.0) <= ATTN_TOL
@@ -262,6 +263,16 @@ def test_argument_errors(mq):
     with pytest.raises(mq.MoqaeError) as e:
         mq.decode_attn(cfg, q, None, None, None, 0, Kt, Kt, 5, 0.1, out, ws)
     assert e.value.code == mq.E_WORKSPACE
+    # the packed layout tiles 64 tokens at a time: routing accepts a 32- or 96-token chunk, pack and decode do not
+    c96 = mq.Cfg(1, 2, 2, 128, 96, 32, (2, 4, 8, 16), 1)
+    assert mq.decode_workspace_bytes(c96, 4) == 0
+    with pytest.raises(mq.MoqaeError) as e:
+        Kt96 = torch.zeros((1, 2, 96, 128), dtype=torch.float16, device="cuda")
+        mq.decode_attn(c96, q, None, None, None, 0, Kt96, Kt96, 5, 0.1, out, torch.zeros(1 << 20, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == mq.E_INVAL
+    # grouped queries: (query heads per KV head) x (groups per row) must fit the 16 rows of a matrix-core tile
+    g8 = mq.Cfg(1, 8, 1, 128, 64, 32, (2, 4, 8, 16), 1)
+    assert mq.decode_workspace_bytes(g8, 4) == 0
     bad = mq.Cfg(1, 3, 2, 128, 64, 32, (2, 4, 8, 16), 1)                 # Hq not a multiple of Hkv
     assert mq.decode_workspace_bytes(bad, 4) == 0 and mq.chunk_block_bytes(bad, 2) == 0
     nofp16 = mq.Cfg(1, 2, 2, 128, 64, 32, (2, 4, 8), 1)                  # freezing needs a 16-bit expert

@@ -257,7 +257,7 @@ _GEN = {
 
 def test_pack_words_golden(ref):
     """A wrong bit position, word order, tile stride or area order moves these words."""
-    N = D = G = 32
+    N = D = G = 64
     t, d = np.meshgrid(np.arange(N), np.arange(D), indexing="ij")
     for (name, bits), probes in _read_words().items():
         cfg = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0)
@@ -386,7 +386,7 @@ def _packed(ref, cfg, K, V, expert, C):
     return arena, off
 
 
-@pytest.mark.parametrize("B,Hq,Hkv,S,N", [(1, 4, 4, 256, 64), (2, 8, 2, 64 * 3 + 17, 64), (1, 2, 1, 5, 32)])
+@pytest.mark.parametrize("B,Hq,Hkv,S,N", [(1, 4, 4, 256, 64), (2, 8, 2, 64 * 3 + 17, 64), (1, 2, 1, 5, 64)])
 def test_attention_all_16bit_equals_unquantised(ref, B, Hq, Hkv, S, N):
     """With only the FP16 expert the path must reproduce plain attention
     (residual rows included, GQA head mapping included)."""
@@ -435,7 +435,7 @@ def test_attention_quantised_is_attention_over_decoded_cache(ref):
 
 def test_attention_special_cases(ref):
     rng = np.random.default_rng(12)
-    N, D = 32, 128
+    N, D = 64, 128
     cfg = ref.RefCfg(1, 2, 1, D, N, 64, (4, 16), 0)
     q = rng.standard_normal((1, 2, D)).astype(np.float16)
     # S = 1 (a single residual row): the output is that row of V
