@@ -19,6 +19,7 @@
 //                       sum p v^ = sum_t (p_t scale_tg) code_td  +  sum_t p_t zero_tg.
 //                     Every workgroup writes one partial (m, l, o[D]) per row it touched.
 // attn_merge_kernel   log-sum-exp merge of the partials of one query head, normalisation.
+#include <type_traits>
 #include "moqae_dev.hpp"
 #include "moqae_kernels.hpp"
 
@@ -46,7 +47,10 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     uint32_t qtab[4][REP][64];                           // q as fp16 pairs, ordered and pre-scaled per bit-width
     float qpart[4][REP][16][2];                          // sum of q over a lane's dims (per group inside the slot)
     float sc[NWV][REP][128];                             // scores (log2 domain) / fp16-path weights of a unit
-    uint16_t wl[NWV][REP][NG][128];                      // fp16 softmax weight * V scale, pre-scaled per pair
+    static constexpr int WLS = 136;                      // weight row stride in halfs: rows fall on different banks
+    uint16_t wl[NWV][REP][NG][WLS];                      // fp16 softmax weight * V scale, pre-scaled per pair
+    uint16_t zrow[WLS];                                  // zeros: the weight row of the unused tile rows
+    float qsumg[REP][NG];                                // sum of q over a group, times 2^-24
     float comb[NWV][REP][kD + 2];                        // per-wavefront (o, m, l) at the end of a row segment
     uint32_t qraw[REP * 64];                             // the row's queries as loaded (fp16 pairs)
     unsigned long long desc[kDescCap];                   // chunk descriptors of the current pass: offset | expert
@@ -61,10 +65,15 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
 template <int REP> struct WaveState {
     float m[REP], lsum[REP], z[REP];
     float acc[REP][2];                                   // raw fp16 rows: dims (2l, 2l+1), in units of 2^-24
-    float accq[REP][8];                                  // quantised V: dims 16*ct + l%16, this lane's token slices only
+    float accq[REP][8];                                  // quantised V, one head per KV head: dims 16*ct + l%16, this lane's token slices only
+    v4f accA[8];                                         // quantised V, grouped queries: matrix-core tile ct, rows 4*(l/16)..+3
 };
 
 // scale of the k-th pair of a word after masking: 2^(BITS*k') with k' counted from the shift
@@ -102,14 +111,28 @@ __device__ __forceinline__ void lds_load_words(const void *src, uint32_t (&dst)[
     }
 }
 
-template <int REP>
-__device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_max) {
+// New running maximum of head r: every accumulator of the head is scaled by 2^(old - new).
+template <int G, int REP>
+__device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_max, int lane) {
     const float m_new = fmaxf(st.m[r], unit_max);
     const float alpha = fast_exp2(st.m[r] - m_new);       // first unit: exp2(-inf) = 0
     st.m[r] = m_new;
     st.lsum[r] *= alpha; st.z[r] *= alpha; st.acc[r][0] *= alpha; st.acc[r][1] *= alpha;
+    if constexpr (REP == 1) {
 #pragma unroll
-    for (int ct = 0; ct < 8; ct++) st.accq[r][ct] *= alpha;
+        for (int ct = 0; ct < 8; ct++) st.accq[r][ct] *= alpha;
+    } else {
+        if (alpha != 1.0f) {                              // wave-uniform; rare once the maximum has settled
+            constexpr int NG = kD / G;
+            const int qd = lane >> 4;
+#pragma unroll
+            for (int n = 0; n < 4; n++) {
+                const float f = ((4 * qd + n) / NG == r) ? alpha : 1.0f;         // tile rows >= REP*NG hold zeros
+#pragma unroll
+                for (int ct = 0; ct < 8; ct++) st.accA[ct][n] *= f;
+            }
+        }
+    }
 }
 
 // A unit: up to 4 KiB of K codes (nsub KiB) with the matching V codes.  All fields are
@@ -233,7 +256,7 @@ __device__ __forceinline__ void quant_scores(const Unit &u, const KRegs<G> &k,
             s4[j] = (j < nsub) ? ps * scale24 : -INFINITY;            // KiB past a short unit: ignored
             lmax = fmaxf(lmax, s4[j]);
         }
-        rescale(st, r, wave_max(lmax));
+        rescale<G, REP>(st, r, wave_max(lmax), lane);
         if (part == 0) {
 #pragma unroll
             for (int j = 0; j < 4; j++) L.sc[wave][r][j * B::TT + tok_l] = s4[j];
@@ -242,9 +265,10 @@ __device__ __forceinline__ void quant_scores(const Unit &u, const KRegs<G> &k,
     wave_sync();
 }
 
+// Softmax weights of a quantised unit: fp16(p * V scale / pair scale) per (head, group, token) into LDS.
 template <int BITS, int G, int REP, int NWV>
-__device__ __forceinline__ void quant_values(const VRegs<G> &v, int lane, int wave,
-                                             AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
+__device__ __forceinline__ void value_weights(const VRegs<G> &v, int lane, int wave,
+                                              AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
     using B = BW<BITS>;
     constexpr int NG = kD / G;
     constexpr int MAXVM = (4 * B::TT * NG / 64) > 0 ? (4 * B::TT * NG / 64) : 1;
@@ -268,7 +292,14 @@ __device__ __forceinline__ void quant_values(const VRegs<G> &v, int lane, int wa
     }
 
     wave_sync();
-    // ---- weighted value sum.  V layout: KiB j of the unit, slot l = 16*qd + jj, word nw: a slice of
+}
+
+// Weighted value sum of a quantised unit on the vector ALU (one query head per KV head).
+template <int BITS, int G, int REP, int NWV>
+__device__ __forceinline__ void value_dots(const VRegs<G> &v, int lane, int wave,
+                                           AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
+    using B = BW<BITS>;
+    // V layout: KiB j of the unit, slot l = 16*qd + jj, word nw: a slice of
     //      TQ = max(TW, 8) tokens (TW = 32/BITS per word, WD = TQ/TW words) of dim 16*ct + jj, for
     //      CPK = 4/WD column tiles ct per KiB.  The weights of a slice are shared by the words of a
     //      "key group" (same group of dims, same word of the slice); the next key group's weight
@@ -309,8 +340,8 @@ __device__ __forceinline__ void quant_values(const VRegs<G> &v, int lane, int wa
 // 16 rows: lane l holds dims 8*(l%16)..+7 of row 4*j + l/16, for K and for V alike.  Every lane of
 // a row ends up with the row's score, so the weights need no trip through LDS: the score phase
 // leaves p[r][j] in registers for the value phase.
-template <int G, int REP, int NWV>
-__device__ __forceinline__ void fp16_scores(const Unit &u, const KRegs<G> &k, int lane, float scale_log2,
+template <int G, int REP, int NWV, typename KR>
+__device__ __forceinline__ void fp16_scores(const Unit &u, const KR &k, int lane, float scale_log2,
                                             AttnLds<G, REP, NWV> &L, WaveState<REP> &st, float (&p4)[REP][4]) {
     const int part = lane & 15, tok_l = lane >> 4;
     const int nvalid = u.nvalid;                          // an fp16 unit always spans 16 rows
@@ -328,7 +359,7 @@ __device__ __forceinline__ void fp16_scores(const Unit &u, const KRegs<G> &k, in
             s4[j] = (4 * j + tok_l < nvalid) ? ps * scale_log2 : -INFINITY;
             lmax = fmaxf(lmax, s4[j]);
         }
-        rescale(st, r, wave_max(lmax));
+        rescale<G, REP>(st, r, wave_max(lmax), lane);
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             p4[r][j] = fast_exp2(s4[j] - st.m[r]);                    // masked rows: exp2(-inf) = 0
@@ -379,6 +410,245 @@ __device__ __forceinline__ void fp16_values(const Unit &u, const VRegs<G> &v, in
     }
 }
 
+// ---- matrix-core path for grouped queries (REP > 1), quantised units -------------------------
+// v_mfma_f32_16x16x32_f16 computes C[i][x] += sum_k A[i][k] B[k][x]; lane l = 16*qd + x holds
+// A[x][8qd..8qd+7], B[8qd..8qd+7][x] and C[4qd..4qd+3][x].  Masked code words are valid B operands
+// as they are (fp16 subnormals, which the matrix core keeps); the per-pair power of two and the
+// 2^-24 are folded into A.  Tile rows carry (query head, group) pairs: row = head * NG + group.
+//   scores: x = token of a 16-token tile, k = 32 dims (lane quarter qd holds dims 32qd + 8mi + 0..7 of
+//           its token in pass mi = 0..3); A = q, zero outside the row's group.  The R = REP*NG rows in
+//           use repeat 16/R times, so that many tiles are computed back to back and every lane keeps the
+//           tile in which its own token lies: no lane is idle in the per-token arithmetic.
+//   values: x = dim of a 16-dim column tile, k = 32 tokens (quarter qd holds its slice of the token
+//           block); A = the softmax weights from LDS, rows >= R read zeros.
+template <int G, int REP> struct MC {
+    static constexpr int NG = kD / G;
+    static constexpr int R = REP * NG;                   // tile rows in use
+    static constexpr int F = 16 / (R < 16 ? R : 16);     // score tiles per pass
+    static constexpr int HPL = 4 / NG;                   // query heads per lane (C register n: head n / NG)
+    static constexpr int NSMAX = 8 / F;                  // passes of the largest unit (128 tokens, 8 tiles)
+    __device__ static __forceinline__ int sel(int qd) { return F == 4 ? qd : (F == 2 ? (qd >> 1) : 0); }
+    __device__ static __forceinline__ int slot0(int qd) { return (4 * qd) % R; }   // (head, group) slot of C register 0
+};
+
+template <int G, int REP> struct KRegsMC {
+    uint4 c[4];
+    uint32_t m[MC<G, REP>::NSMAX * (kD / G)];            // K meta words of the lane's own tokens
+};
+
+__device__ __forceinline__ v4f mfma16(v4u a, v4u b, v4f c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ uint2 ld8(const uint8_t *sbase, uint32_t voff) {
+    return *reinterpret_cast<const uint2 *>(sbase + voff);
+}
+// the k-th fp16 pair of a code word, left where it lies (scaled by 2^pair_exp(k))
+template <int BITS> __device__ __forceinline__ uint32_t pair_reg(uint32_t w, int k) {
+    using B = BW<BITS>;
+    return k < B::KD ? (w & (B::MASK << (BITS * k))) : ((w >> B::SH) & (B::MASK << (BITS * (k - B::KD))));
+}
+template <int G, int REP>
+__device__ __forceinline__ uint32_t kword(const KRegsMC<G, REP> &k, int i) {
+    const uint4 &c = k.c[i >> 2];
+    return (i & 3) == 0 ? c.x : ((i & 3) == 1 ? c.y : ((i & 3) == 2 ? c.z : c.w));
+}
+// pair index (inside its word) that feeds pair register pr of pass mi
+template <int BITS> __device__ __forceinline__ constexpr int mc_pair(int mi, int pr) {
+    return BITS == 2 ? 4 * (mi % 2) + pr : (BITS == 4 ? pr : pr % 2);
+}
+// B operand of score pass mi for token tile `tile`: the codes of dims 32qd + 8mi + 0..7
+template <int BITS, int G, int REP>
+__device__ __forceinline__ v4u mc_kcodes(const KRegsMC<G, REP> &k, int tile, int mi) {
+    v4u b;
+    if constexpr (BITS == 2) {
+        const uint32_t w = kword(k, 2 * tile + mi / 2);
+#pragma unroll
+        for (int pr = 0; pr < 4; pr++) b[pr] = pair_reg<2>(w, mc_pair<2>(mi, pr));
+    } else if constexpr (BITS == 4) {
+        const uint32_t w = kword(k, 4 * tile + mi);
+#pragma unroll
+        for (int pr = 0; pr < 4; pr++) b[pr] = pair_reg<4>(w, pr);
+    } else {
+        const uint32_t w0 = kword(k, 8 * tile + 2 * mi), w1 = kword(k, 8 * tile + 2 * mi + 1);
+        b[0] = pair_reg<8>(w0, 0); b[1] = pair_reg<8>(w0, 1); b[2] = pair_reg<8>(w1, 0); b[3] = pair_reg<8>(w1, 1);
+    }
+    return b;
+}
+
+// A operands of the score passes for the three quantised bit-widths, from the raw fp16 queries in LDS.
+template <int G, int REP>
+__device__ __forceinline__ void mc_build_q(const uint32_t *qraw32, int lane, v4u (&ak)[3][4]) {
+    using M = MC<G, REP>;
+    const int i = lane & 15, qd = lane >> 4;
+    const int slot = i % M::R, r = slot / M::NG, g = slot % M::NG;
+    const bool own = g == (32 * qd) / G;                 // the quarter's dims lie in the row's group
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++) {
+#pragma unroll
+        for (int pr = 0; pr < 4; pr++) {
+            const uint32_t qq = qraw32[r * 64 + 16 * qd + 4 * mi + pr];          // dims 32qd + 8mi + 2pr, +1
+            const float q0 = half_bits_to_float(qq & 0xffffu), q1 = half_bits_to_float(qq >> 16);
+#pragma unroll
+            for (int bi = 0; bi < 3; bi++) {
+                const int kp = bi == 0 ? pair_exp<2>(mc_pair<2>(mi, pr)) : (bi == 1 ? pair_exp<4>(mc_pair<4>(mi, pr)) : 0);
+                const float f = __builtin_bit_cast(float, (uint32_t)(127 - kp) << 23);
+                const uint32_t v = float_to_half_bits(q0 * f) | (float_to_half_bits(q1 * f) << 16);
+                ak[bi][mi][pr] = own ? v : 0u;
+            }
+        }
+    }
+}
+
+// K side of a unit for grouped queries.  Quantised units: lane (x, qd) takes quarter qd of the code row
+// of token 16*tile + x for every tile, and the meta words of its own tokens; raw fp16 units keep the
+// slot order of load_k.  Eight 8-byte loads whatever the bit-width, branch-free like load_k.
+template <int G, int REP>
+__device__ __forceinline__ void load_k_mc(const Unit &u, int lane, KRegsMC<G, REP> &k) {
+    using M = MC<G, REP>;
+    const int x = lane & 15, qd = lane >> 4;
+    const bool raw = u.lgb == 4;
+    const int rbsh = 4 + u.lgb;                           // log2(bytes of a code row)
+    const uint32_t lane_off = raw ? (uint32_t)lane * 16u : (((uint32_t)x << rbsh) + ((uint32_t)qd << (rbsh - 2)));
+    const int iptsh = raw ? 1 : u.lgb - 1;                // log2(loads per tile); raw: per KiB
+    const int tbsh = raw ? 10 : rbsh + 4;                 // log2(bytes per tile); raw: a KiB
+    const int imax = 2 * u.nsub - 1;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const int ic = min(i, imax);
+        const uint2 t = ld8(u.kc + (((size_t)(ic >> iptsh) << tbsh) + (size_t)(ic & ((1 << iptsh) - 1)) * 8), lane_off);
+        if (i & 1) { k.c[i >> 1].z = t.x; k.c[i >> 1].w = t.y; } else { k.c[i >> 1].x = t.x; k.c[i >> 1].y = t.y; }
+    }
+    const int TU = raw ? 16 : (u.nsub << (6 - u.lgb));    // tokens of the unit
+#pragma unroll
+    for (int s = 0; s < M::NSMAX; s++) {
+        const int t = min(16 * (s * M::F + M::sel(qd)) + x, TU - 1);
+        if constexpr (M::NG == 2) {
+            const uint2 mm = ld8(u.km, (uint32_t)t * 8u);
+            k.m[2 * s] = mm.x; k.m[2 * s + 1] = mm.y;
+        } else {
+            const uint4 mm = ld16(u.km, (uint32_t)t * 16u);
+            k.m[4 * s] = mm.x; k.m[4 * s + 1] = mm.y; k.m[4 * s + 2] = mm.z; k.m[4 * s + 3] = mm.w;
+        }
+    }
+}
+
+// Scores of a quantised unit -> L.sc (log2 domain), running maxima updated.
+template <int BITS, int G, int REP, int NWV>
+__device__ __forceinline__ void mc_scores(const Unit &u, const KRegsMC<G, REP> &k, const v4u (&ak)[3][4],
+                                          const float (&qp)[4], int lane, int wave, float scale24,
+                                          AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
+    using M = MC<G, REP>;
+    using B = BW<BITS>;
+    constexpr int NG = M::NG, HPL = M::HPL, F = M::F;
+    constexpr int TL = 16 / BITS;                         // tiles of a full unit: 8, 4, 2
+    constexpr int NS = (TL + F - 1) / F;
+    const int x = lane & 15, qd = lane >> 4, sel = M::sel(qd);
+    const int TU = u.nsub << (6 - u.lgb);
+    float sv[NS][HPL], hmax[HPL];
+#pragma unroll
+    for (int h = 0; h < HPL; h++) hmax[h] = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < NS; s++) {
+        v4f own = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int f = 0; f < F; f++) {
+            const int tile = s * F + f;
+            if (tile < TL) {
+                v4f c = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int mi = 0; mi < 4; mi++) c = mfma16(ak[B::BI][mi], mc_kcodes<BITS, G, REP>(k, tile, mi), c);
+                if (F == 1) own = c;
+                else {
+#pragma unroll
+                    for (int n = 0; n < 4; n++) own[n] = (sel == f) ? c[n] : own[n];
+                }
+            }
+        }
+        const int t = 16 * (s * F + sel) + x;
+        const bool valid = t < TU;
+#pragma unroll
+        for (int h = 0; h < HPL; h++) {
+            float ps = 0.0f;
+#pragma unroll
+            for (int g = 0; g < NG; g++) {
+                const uint32_t mw = k.m[s * NG + g];
+                ps = fmaf(half_bits_to_float(mw & 0xffffu), own[h * NG + g], ps);
+                ps = fmaf(half_bits_to_float(mw >> 16), qp[h * NG + g], ps);
+            }
+            sv[s][h] = valid ? ps * scale24 : -INFINITY;
+            hmax[h] = fmaxf(hmax[h], sv[s][h]);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < HPL; h++) hmax[h] = group_max<16>(hmax[h]);
+#pragma unroll
+    for (int r = 0; r < REP; r++) {                       // the quarters whose rows hold head r
+        float um = -INFINITY;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+            const int r0q = ((4 * q4) % M::R) / NG;
+            if (r0q <= r && r < r0q + HPL)
+                um = fmaxf(um, __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, hmax[r - r0q]), 16 * q4)));
+        }
+        rescale<G, REP>(st, r, um, lane);
+    }
+    const int r0 = M::slot0(qd) / NG;
+#pragma unroll
+    for (int s = 0; s < NS; s++) {
+        const int t = 16 * (s * F + sel) + x;
+#pragma unroll
+        for (int h = 0; h < HPL; h++) L.sc[wave][r0 + h][t] = sv[s][h];
+    }
+    wave_sync();
+}
+
+// Weighted value sum of a quantised unit on the matrix cores.
+template <int BITS, int G, int REP, int NWV>
+__device__ __forceinline__ void mc_value_dots(const VRegs<G> &v, int lane, int wave,
+                                              AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
+    using M = MC<G, REP>;
+    constexpr int TW = 32 / BITS, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, TB = 4 * TQ, KPB = 8 / CPK;
+    constexpr int WLS = AttnLds<G, REP, NWV>::WLS;
+    const int i = lane & 15, qd = lane >> 4;
+    const uint16_t *arow = (i < M::R) ? &L.wl[wave][0][0][0] + i * WLS : &L.zrow[0];   // row = head * NG + group
+    arow += qd * TQ;
+    v4u a0 = {0, 0, 0, 0}, a1 = {0, 0, 0, 0};
+#pragma unroll
+    for (int jk = 0; jk < 4; jk++) {
+        const int bu = jk / KPB, cg = jk % KPB;
+        if (cg == 0) {                                    // the weights of this token block
+            a0 = *reinterpret_cast<const v4u *>(arow + bu * TB);
+            if constexpr (BITS == 2) a1 = *reinterpret_cast<const v4u *>(arow + bu * TB + 8);
+        }
+        const uint32_t wv[4] = {v.c[jk].x, v.c[jk].y, v.c[jk].z, v.c[jk].w};
+        if constexpr (BITS == 8) {
+#pragma unroll
+            for (int nc = 0; nc < 2; nc++) {
+                const int ct = cg * CPK + nc;
+                v4u b;
+                b[0] = pair_reg<8>(wv[2 * nc], 0); b[1] = pair_reg<8>(wv[2 * nc], 1);
+                b[2] = pair_reg<8>(wv[2 * nc + 1], 0); b[3] = pair_reg<8>(wv[2 * nc + 1], 1);
+                st.accA[ct] = mfma16(a0, b, st.accA[ct]);
+            }
+        } else {
+#pragma unroll
+            for (int nw = 0; nw < 4; nw++) {
+                const int ct = cg * CPK + nw;
+                v4u b;
+#pragma unroll
+                for (int pr = 0; pr < 4; pr++) b[pr] = pair_reg<BITS>(wv[nw], pr);
+                st.accA[ct] = mfma16(a0, b, st.accA[ct]);
+                if constexpr (BITS == 2) {
+#pragma unroll
+                    for (int pr = 0; pr < 4; pr++) b[pr] = pair_reg<2>(wv[nw], 4 + pr);
+                    st.accA[ct] = mfma16(a1, b, st.accA[ct]);
+                }
+            }
+        }
+    }
+    wave_sync();
+}
+
 // ---- work distribution ----------------------------------------------------------------------
 // One persistent workgroup per CU slot.  Workgroup w of NW owns the interval
 // [w*BH/NW, (w+1)*BH/NW) of the row axis, where a fraction of a row means that fraction of the
@@ -410,6 +680,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     __shared__ AttnLds<G, REP, NWV> L;
     constexpr int NG = kD / G;
     constexpr int NT = NWV * 64;
+    using KR = std::conditional_t<REP == 1, KRegs<G>, KRegsMC<G, REP>>;
     const int tid = (int)threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // wave-uniform, kept scalar
     const int w = (int)blockIdx.x, NW = (int)gridDim.x;
@@ -511,6 +782,14 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 }
                 L.qpart[bi][r][part][gi] = bi == 3 ? sq : sq * kTwoM24;   // quantised paths work in units of 2^-24
             }
+            if constexpr (REP > 1) {
+                for (int i = tid; i < REP * NG; i += NT) {
+                    float sq = 0.0f;
+                    for (int d = 0; d < G; d++) sq += half_bits_to_float(qraw[(i / NG) * kD + (i % NG) * G + d]);
+                    L.qsumg[i / NG][i % NG] = sq * kTwoM24;
+                }
+                for (int i = tid; i < AttnLds<G, REP, NWV>::WLS; i += NT) L.zrow[i] = 0;
+            }
             __syncthreads();
         }
         const int c0 = __builtin_amdgcn_readfirstlane(L.range[0]), c1 = __builtin_amdgcn_readfirstlane(L.range[1]);
@@ -521,6 +800,16 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             st.m[r] = -INFINITY; st.lsum[r] = 0.0f; st.z[r] = 0.0f; st.acc[r][0] = 0.0f; st.acc[r][1] = 0.0f;
 #pragma unroll
             for (int ct = 0; ct < 8; ct++) st.accq[r][ct] = 0.0f;
+        }
+#pragma unroll
+        for (int ct = 0; ct < 8; ct++) st.accA[ct] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+        v4u ak[3][4];                                    // grouped queries: q as matrix-core operands
+        float qp[4];
+        if constexpr (REP > 1) {
+            mc_build_q<G, REP>(L.qraw, lane, ak);
+            const int slot0 = MC<G, REP>::slot0(lane >> 4);
+#pragma unroll
+            for (int n = 0; n < 4; n++) qp[n] = L.qsumg[(slot0 + n) / NG][(slot0 + n) % NG];
         }
 
         // ---- (b) the segment in passes of at most kDescCap chunks whose descriptors
@@ -601,10 +890,13 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             // K is requested half a unit ahead (right after the scores of the current unit), V a
             // whole unit ahead into the buffer the current unit does not use.
             Unit cur, nxt;
-            KRegs<G> kr;
+            KR kr;
             VRegs<G> va, vb;
             bool have = next_unit(cur);
-            if (have) { load_k<G>(cur, lane, kr); load_v<G>(cur, lane, va); }
+            auto load_keys = [&](const Unit &un) {
+                if constexpr (REP == 1) load_k<G>(un, lane, kr); else load_k_mc<G, REP>(un, lane, kr);
+            };
+            if (have) { load_keys(cur); load_v<G>(cur, lane, va); }
             const float scale24 = a.scale_log2 * kTwo24;
             auto step = [&](const VRegs<G> &vc, VRegs<G> &vn) {
                 const bool have_next = next_unit(nxt);
@@ -612,15 +904,32 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 const int lgb = cur.lgb;
                 float p4[REP][4];                         // fp16 units: weights handed from scores to values
                 load_v<G>(pf, lane, vn);                  // a whole unit ahead
-                if (lgb == 1)      quant_scores<2, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
-                else if (lgb == 2) quant_scores<4, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
-                else if (lgb == 3) quant_scores<8, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
-                else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
-                load_k<G>(pf, lane, kr);                  // half a unit ahead
-                if (lgb == 1)      quant_values<2, G, REP, NWV>(vc, lane, wave, L, st);
-                else if (lgb == 2) quant_values<4, G, REP, NWV>(vc, lane, wave, L, st);
-                else if (lgb == 3) quant_values<8, G, REP, NWV>(vc, lane, wave, L, st);
-                else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
+                if constexpr (REP == 1) {
+                    if (lgb == 1)      quant_scores<2, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                    else if (lgb == 2) quant_scores<4, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                    else if (lgb == 3) quant_scores<8, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
+                } else {
+                    if (lgb == 1)      mc_scores<2, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
+                    else if (lgb == 2) mc_scores<4, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
+                    else if (lgb == 3) mc_scores<8, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
+                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
+                }
+                load_keys(pf);                            // half a unit ahead
+                if (lgb == 1)      value_weights<2, G, REP, NWV>(vc, lane, wave, L, st);
+                else if (lgb == 2) value_weights<4, G, REP, NWV>(vc, lane, wave, L, st);
+                else if (lgb == 3) value_weights<8, G, REP, NWV>(vc, lane, wave, L, st);
+                if constexpr (REP == 1) {
+                    if (lgb == 1)      value_dots<2, G, REP, NWV>(vc, lane, wave, L, st);
+                    else if (lgb == 2) value_dots<4, G, REP, NWV>(vc, lane, wave, L, st);
+                    else if (lgb == 3) value_dots<8, G, REP, NWV>(vc, lane, wave, L, st);
+                    else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
+                } else {
+                    if (lgb == 1)      mc_value_dots<2, G, REP, NWV>(vc, lane, wave, L, st);
+                    else if (lgb == 2) mc_value_dots<4, G, REP, NWV>(vc, lane, wave, L, st);
+                    else if (lgb == 3) mc_value_dots<8, G, REP, NWV>(vc, lane, wave, L, st);
+                    else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
+                }
                 cur = nxt; have = have_next;
             };
             while (have) {
@@ -644,13 +953,30 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             dst[2 * lane] = fmaf(st.acc[r][0], kTwo24, zg);
             dst[2 * lane + 1] = fmaf(st.acc[r][1], kTwo24, zg);
             if (lane == 0) { dst[kD] = st.m[r]; dst[kD + 1] = lt; }
-            wave_sync();
+            if constexpr (REP == 1) {
+                wave_sync();
 #pragma unroll
-            for (int ct = 0; ct < 8; ct++) {              // fold the four token slices of every column tile
-                float t = st.accq[r][ct];
-                t += __shfl_xor(t, 16);
-                t += __shfl_xor(t, 32);
-                if (lane < 16) dst[16 * ct + lane] = fmaf(t, kTwo24, dst[16 * ct + lane]);
+                for (int ct = 0; ct < 8; ct++) {          // fold the four token slices of every column tile
+                    float t = st.accq[r][ct];
+                    t += __shfl_xor(t, 16);
+                    t += __shfl_xor(t, 32);
+                    if (lane < 16) dst[16 * ct + lane] = fmaf(t, kTwo24, dst[16 * ct + lane]);
+                }
+            }
+        }
+        if constexpr (REP > 1) {                          // matrix-core tiles: row = head * NG + group, column = dim
+            wave_sync();
+            const int x = lane & 15, qd = lane >> 4;
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) {
+#pragma unroll
+                for (int n = 0; n < 4; n++) {
+                    const int slot = 4 * qd + n;
+                    if (slot < REP * NG && slot % NG == (16 * ct) / G) {
+                        float *dst = &L.comb[wave][slot / NG][16 * ct + x];
+                        *dst = fmaf(st.accA[ct][n], kTwo24, *dst);
+                    }
+                }
             }
         }
         __syncthreads();
@@ -732,7 +1058,7 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-#define MOQAE_FOR_EACH_VARIANT(X) X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(32, 1) X(32, 2) X(32, 4) X(32, 8)
+#define MOQAE_FOR_EACH_VARIANT(X) X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(32, 1) X(32, 2) X(32, 4)
 
 int attn_resident_wgs_per_cu(int G, int rep) {
 #define MOQAE_CASE(GV, RV) if (G == GV && rep == RV) return resident_wgs_per_cu<GV, RV>();
