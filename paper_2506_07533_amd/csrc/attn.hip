@@ -40,6 +40,10 @@ template <int BITS> struct BW {
     static constexpr int BI = BITS == 2 ? 0 : (BITS == 4 ? 1 : (BITS == 8 ? 2 : 3));
 };
 
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
 constexpr int kDescCap = 1024;                            // chunk descriptors held in LDS at a time
 
 template <int G, int REP, int NWV> struct alignas(16) AttnLds {
@@ -51,6 +55,7 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     uint16_t wl[NWV][REP][NG][WLS];                      // fp16 softmax weight * V scale, pre-scaled per pair
     uint16_t zrow[WLS];                                  // zeros: the weight row of the unused tile rows
     float qsumg[REP][NG];                                // sum of q over a group, times 2^-24
+    v4u qmc[REP > 1 ? 3 : 1][4][REP > 1 ? 64 : 1];       // grouped queries: score operands A per (bit-width, pass, lane)
     float comb[NWV][REP][kD + 2];                        // per-wavefront (o, m, l) at the end of a row segment
     uint32_t qraw[REP * 64];                             // the row's queries as loaded (fp16 pairs)
     unsigned long long desc[kDescCap];                   // chunk descriptors of the current pass: offset | expert
@@ -64,10 +69,6 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 }
-
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 template <int REP> struct WaveState {
     float m[REP], lsum[REP], z[REP];
@@ -476,14 +477,15 @@ __device__ __forceinline__ v4u mc_kcodes(const KRegsMC<G, REP> &k, int tile, int
 }
 
 // A operands of the score passes for the three quantised bit-widths, from the raw fp16 queries in LDS.
-template <int G, int REP>
-__device__ __forceinline__ void mc_build_q(const uint32_t *qraw32, int lane, v4u (&ak)[3][4]) {
+template <int G, int REP, typename LDS>
+__device__ __forceinline__ void mc_build_q(const uint32_t *qraw32, int lane, LDS &L) {
     using M = MC<G, REP>;
     const int i = lane & 15, qd = lane >> 4;
     const int slot = i % M::R, r = slot / M::NG, g = slot % M::NG;
     const bool own = g == (32 * qd) / G;                 // the quarter's dims lie in the row's group
 #pragma unroll
     for (int mi = 0; mi < 4; mi++) {
+        v4u ak[3];
 #pragma unroll
         for (int pr = 0; pr < 4; pr++) {
             const uint32_t qq = qraw32[r * 64 + 16 * qd + 4 * mi + pr];          // dims 32qd + 8mi + 2pr, +1
@@ -493,9 +495,11 @@ __device__ __forceinline__ void mc_build_q(const uint32_t *qraw32, int lane, v4u
                 const int kp = bi == 0 ? pair_exp<2>(mc_pair<2>(mi, pr)) : (bi == 1 ? pair_exp<4>(mc_pair<4>(mi, pr)) : 0);
                 const float f = __builtin_bit_cast(float, (uint32_t)(127 - kp) << 23);
                 const uint32_t v = float_to_half_bits(q0 * f) | (float_to_half_bits(q1 * f) << 16);
-                ak[bi][mi][pr] = own ? v : 0u;
+                ak[bi][pr] = own ? v : 0u;
             }
         }
+#pragma unroll
+        for (int bi = 0; bi < 3; bi++) L.qmc[bi][mi][lane] = ak[bi];
     }
 }
 
@@ -534,7 +538,7 @@ __device__ __forceinline__ void load_k_mc(const Unit &u, int lane, KRegsMC<G, RE
 
 // Scores of a quantised unit -> L.sc (log2 domain), running maxima updated.
 template <int BITS, int G, int REP, int NWV>
-__device__ __forceinline__ void mc_scores(const Unit &u, const KRegsMC<G, REP> &k, const v4u (&ak)[3][4],
+__device__ __forceinline__ void mc_scores(const Unit &u, const KRegsMC<G, REP> &k, const v4u (&ak)[4],
                                           const float (&qp)[4], int lane, int wave, float scale24,
                                           AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
     using M = MC<G, REP>;
@@ -556,7 +560,7 @@ __device__ __forceinline__ void mc_scores(const Unit &u, const KRegsMC<G, REP> &
             if (tile < TL) {
                 v4f c = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                for (int mi = 0; mi < 4; mi++) c = mfma16(ak[B::BI][mi], mc_kcodes<BITS, G, REP>(k, tile, mi), c);
+                for (int mi = 0; mi < 4; mi++) c = mfma16(ak[mi], mc_kcodes<BITS, G, REP>(k, tile, mi), c);
                 if (F == 1) own = c;
                 else {
 #pragma unroll
@@ -671,8 +675,10 @@ int attn_max_partials(int NW, int BH) { return NW / BH + 2; }
 
 // Relative cost of one chunk at a bit-width: kernel time per chunk measured on caches of one
 // bit-width (2-bit chunks are bound by instruction issue, 16-bit ones by bytes).
+template <int REP>
 __device__ __forceinline__ uint32_t chunk_cost(int bits) {
-    return bits == 2 ? 215u : (bits == 4 ? 330u : (bits == 8 ? 600u : 1090u));
+    if constexpr (REP == 1) return bits == 2 ? 215u : (bits == 4 ? 330u : (bits == 8 ? 600u : 1090u));
+    else                    return bits == 2 ? 215u : (bits == 4 ? 333u : (bits == 8 ? 587u : 1391u));
 }
 
 template <int G, int REP, int NWV>
@@ -718,7 +724,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 uint32_t sum = 0;
                 for (int tile = 0; tile < n_tiles; tile++) {
                     const int c = tile * NT + tid;
-                    if (c < C) sum += chunk_cost(bits_of(erow[c]));
+                    if (c < C) sum += chunk_cost<REP>(bits_of(erow[c]));
                 }
 #pragma unroll
                 for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
@@ -731,7 +737,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             int g0 = C, g1 = C;
             for (int tile = 0; tile < n_tiles; tile++) {
                 const int c = tile * NT + tid;
-                const uint32_t cst = c < C ? chunk_cost(bits_of(erow[c])) : 0u;
+                const uint32_t cst = c < C ? chunk_cost<REP>(bits_of(erow[c])) : 0u;
                 uint32_t incl = cst;                                  // inclusive scan inside the wavefront
 #pragma unroll
                 for (int o = 1; o < 64; o <<= 1) {
@@ -789,6 +795,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     L.qsumg[i / NG][i % NG] = sq * kTwoM24;
                 }
                 for (int i = tid; i < AttnLds<G, REP, NWV>::WLS; i += NT) L.zrow[i] = 0;
+                if (wave == 0) mc_build_q<G, REP>(L.qraw, lane, L);
             }
             __syncthreads();
         }
@@ -803,10 +810,8 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int ct = 0; ct < 8; ct++) st.accA[ct] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-        v4u ak[3][4];                                    // grouped queries: q as matrix-core operands
         float qp[4];
         if constexpr (REP > 1) {
-            mc_build_q<G, REP>(L.qraw, lane, ak);
             const int slot0 = MC<G, REP>::slot0(lane >> 4);
 #pragma unroll
             for (int n = 0; n < 4; n++) qp[n] = L.qsumg[(slot0 + n) / NG][(slot0 + n) % NG];
@@ -903,6 +908,12 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 const Unit &pf = have_next ? nxt : cur;  // nothing left: re-read the current unit (ignored)
                 const int lgb = cur.lgb;
                 float p4[REP][4];                         // fp16 units: weights handed from scores to values
+                v4u ak[4];                                // grouped queries: the score operands of this bit-width
+                if constexpr (REP > 1) {
+                    const int bi = min(lgb, 3) - 1;
+#pragma unroll
+                    for (int mi = 0; mi < 4; mi++) ak[mi] = L.qmc[bi][mi][lane];
+                }
                 load_v<G>(pf, lane, vn);                  // a whole unit ahead
                 if constexpr (REP == 1) {
                     if (lgb == 1)      quant_scores<2, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
