@@ -27,6 +27,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 
+# HBM bytes per decode call (attn_split_kernel + attn_merge_kernel, fetched + written) from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_<workload>.md; counters cannot be read
+# from inside this process, so a workload without such a run reports null.
+MEASURED_TRAFFIC = {"llama13b_128k": 693789415}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -162,6 +167,8 @@ def main() -> int:
         "roofline": dict(roof(attn_bytes, t_attn), kernel="attn_split_kernel (+ attn_merge_kernel, timed as one call)"),
         "pct_of_hbm_peak": None,
     }
+    if not args.force_bits:
+        res["roofline"]["traffic"] = MEASURED_TRAFFIC.get(w.name)
     res["value"] = res["roofline"]["achieved"]
     res["pct_of_hbm_peak"] = round(100 * res["roofline"]["frac"], 2)
     if not args.decode_only:

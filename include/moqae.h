@@ -33,9 +33,15 @@
  *            16*(e%2) + b*(e/2);
  *            K codes: token-major rows of D*b/32 words, dim d -> word d/(32/b),
  *                     in-word index d%(32/b);
- *            V codes: tiles of 64/b tokens, 2*D words per tile; dim d owns
- *                     words 2d, 2d+1 of its tile, token tau of the tile ->
- *                     word tau/(32/b), in-word index tau%(32/b);
+ *            V codes: dimension-major 1-KiB tiles of 64 slots x 4 words.  With
+ *                     TW = 32/b tokens per word, a slot holds a slice of
+ *                     TQ = max(TW, 8) consecutive tokens of one dim (WD = TQ/TW
+ *                     words) for CPK = 4/WD dims that lie 16 apart.  Token t:
+ *                     block t/(4*TQ), slice qd = (t % (4*TQ))/TQ, word
+ *                     w = (t % TQ)/TW, in-word index t % TW.  Dim d = 16*ct + j:
+ *                     tile cg = ct/CPK of the block, slot 16*qd + j, word
+ *                     n = (ct % CPK)*WD + w; word index in the area =
+ *                     ((block*D/(16*CPK) + cg)*64 + 16*qd + j)*4 + n;
  *            meta area = one 32-bit word per (token, group), token-major:
  *                     fp16 scale | fp16 zero << 16;  x^ = code*scale + zero.
  *   b = 16 : [K rows | V rows], raw fp16, token-major.
@@ -66,11 +72,12 @@ enum {
 
 typedef struct {
     int32_t batch;          /* B                                                               */
-    int32_t n_q_heads;      /* Hq;  Hq / Hkv must be 1, 2, 4 or 8; query head hq reads KV head
-                               hq / (Hq/Hkv)                                                   */
+    int32_t n_q_heads;      /* Hq;  Hq / Hkv must be 1, 2, 4 or 8 and, if > 1, (Hq/Hkv)*(D/G) <= 16;
+                               query head hq reads KV head hq / (Hq/Hkv)                       */
     int32_t n_kv_heads;     /* Hkv                                                             */
     int32_t head_dim;       /* D, must be 128                                                  */
-    int32_t chunk;          /* N tokens per chunk: a multiple of 32, 32..1024                  */
+    int32_t chunk;          /* N tokens per chunk, 32..256: a multiple of 32 for routing, of 64
+                               for pack and decode (a V tile spans 64 tokens)                  */
     int32_t group;          /* G elements per quantisation group along D: 32 or 64             */
     int32_t n_experts;      /* M, 1..8                                                         */
     int32_t expert_bits[MOQAE_MAX_EXPERTS]; /* B_j in {2,4,8,16}; index order = tie-break order */
@@ -139,7 +146,8 @@ int moqae_quantize_pack(const moqae_cfg *cfg,
  * [B, Hkv, N, D] of which rows [0, n_tail) are valid, 0 <= n_tail < N (may be
  * NULL when n_tail == 0); n_chunks + n_tail must be > 0.
  * out: fp32 [B, Hq, D].  workspace: at least moqae_decode_workspace_bytes()
- * bytes, 256-byte aligned, contents irrelevant on entry (split partials).
+ * bytes, 256-byte aligned, contents irrelevant on entry (one partial softmax
+ * state per workgroup and row, merged by a second kernel of the same call).
  */
 int moqae_decode_attn(const moqae_cfg *cfg,
                       const void *q,
