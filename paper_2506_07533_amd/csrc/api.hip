@@ -78,13 +78,17 @@ int choose_wgs(const moqae_cfg *c, int n_chunks, int n_tail) {
     return (int)n;
 }
 
-// Workspace: one partial (o[D], m, l) per query head and per workgroup that can touch its row.
-// Sized for the largest residual (n_tail = chunk - 1) so that it does not depend on n_tail.
+// Workspace: the ticket counters of the rows, then one partial (o[D], m, l) per query head and per
+// workgroup that can touch its row.  Sized for the largest residual (n_tail = chunk - 1) so that it
+// does not depend on n_tail.
+uint64_t counters_bytes(const moqae_cfg *c, int n_chunks) {
+    return ((uint64_t)attn_counter_bytes(c->batch * c->n_kv_heads, n_chunks, c->chunk) + 255u) & ~255ull;
+}
 uint64_t workspace_bytes(const moqae_cfg *c, int n_chunks) {
     const int BH = c->batch * c->n_kv_heads;
     const int n_wg = choose_wgs(c, n_chunks, c->chunk - 1);
     const uint64_t rows = (uint64_t)c->batch * c->n_q_heads;
-    return rows * (uint64_t)attn_max_partials(n_wg, BH) * (kD + 2) * sizeof(float);
+    return counters_bytes(c, n_chunks) + rows * (uint64_t)attn_max_partials(n_wg, BH) * (kD + 2) * sizeof(float);
 }
 
 }  // namespace
@@ -200,7 +204,8 @@ int moqae_decode_attn(const moqae_cfg *cfg,
     a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
-    a.part = static_cast<float *>(workspace); a.out = out;
+    a.counters = static_cast<unsigned int *>(workspace);
+    a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, n_chunks)); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;
     a.n_chunks = n_chunks; a.n_tail = n_tail;
     a.n_wg = choose_wgs(cfg, n_chunks, n_tail);

@@ -44,7 +44,10 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
-constexpr int kDescCap = 1024;                            // chunk descriptors held in LDS at a time
+constexpr int kDescCap = 1024;                            // chunks of a row segment (descriptors held in LDS)
+constexpr int kUnitCap = 8192;                            // units of a row segment
+constexpr int kCounterStride = 64;                        // uint32 slots between two ticket counters (256 bytes)
+constexpr int kMaxBatches = 64;                           // ticket batches a workgroup can be granted per row segment
 
 template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     static constexpr int NG = kD / G;
@@ -59,9 +62,13 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     float comb[NWV][REP][kD + 2];                        // per-wavefront (o, m, l) at the end of a row segment
     uint32_t qraw[REP * 64];                             // the row's queries as loaded (fp16 pairs)
     unsigned long long desc[kDescCap];                   // chunk descriptors of the current pass: offset | expert
-    uint32_t wsum[NWV], wscan[NWV];
-    int range[2];
-    int ticket;
+    // ticket queue of the workgroup: local tickets [0, limit) are granted; batch i maps local
+    // tickets from bl[i] on to the row's tickets from bg[i] on
+    uint16_t ustart[kDescCap];                           // first unit of every chunk of the segment
+    uint16_t inv[kUnitCap];                              // unit -> chunk of the segment
+    uint32_t wscan[NWV];
+    uint32_t next, limit, done, fetching, g_seen, nb;
+    uint32_t bl[kMaxBatches], bg[kMaxBatches];
 };
 
 // Orders this wavefront's LDS traffic between phases that exchange data across lanes.
@@ -675,6 +682,9 @@ int attn_max_partials(int NW, int BH) { return NW / BH + 2; }
 
 // Relative cost of one chunk at a bit-width: kernel time per chunk measured on caches of one
 // bit-width (2-bit chunks are bound by instruction issue, 16-bit ones by bytes).
+// Chunks per row segment: at most kDescCap, and at most kUnitCap units if all of them were FP16.
+__host__ __device__ inline int attn_segment_chunks(int N) { return min(kDescCap, kUnitCap / (N / 16)); }
+
 template <int REP>
 __device__ __forceinline__ uint32_t chunk_cost(int bits) {
     if constexpr (REP == 1) return bits == 2 ? 215u : (bits == 4 ? 330u : (bits == 8 ? 600u : 1090u));
@@ -691,8 +701,6 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // wave-uniform, kept scalar
     const int w = (int)blockIdx.x, NW = (int)gridDim.x;
     const int N = a.N, C = a.n_chunks;
-    const int LGPC = N >= 256 ? 1 : 0, PC = 1 << LGPC;   // tickets per chunk (N <= 256)
-    const int TKN = N >> LGPC;                           // tokens per ticket
 
     auto bits_of = [&](int e) {
         int b = 0;
@@ -703,64 +711,25 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
 
     int r0, f0, r1, f1;
     wg_interval(w, NW, a.BH, r0, f0, r1, f1);
+    const int seg_chunks = attn_segment_chunks(N);
+    const int n_seg = max(1, (C + seg_chunks - 1) / seg_chunks);
     for (int u = r0; u <= r1 && u < a.BH; u++) {
         if (u == r1 && f1 == 0) break;
-        const uint32_t lo_num = (u == r0) ? (uint32_t)f0 : 0u, hi_num = (u == r1) ? (uint32_t)f1 : (uint32_t)NW;
         const uint8_t *erow = a.expert + (int64_t)u * a.desc_stride;
         const uint64_t *orow = a.chunk_off + (int64_t)u * a.desc_stride;
+        // workgroups that share this row's tickets, and the share of the row inside this workgroup's
+        // interval: a workgroup whose interval covers only part of the row takes at most that part of
+        // the tickets (it owes the rest of its time to the neighbouring row)
+        const uint32_t P = (uint32_t)(wg_last_of_row(u, NW, a.BH) - wg_first_of_row(u, NW, a.BH) + 1);
+        const long long ov = min((long long)(w + 1) * a.BH, (long long)(u + 1) * NW) - max((long long)w * a.BH, (long long)u * NW);
 
-        // ---- (a) row set-up: raw q, cost scan -> chunk range [c0, c1) of this segment, q tables.
-        //      All global loads are issued before the first barrier.
-        const int n_tiles = (C + NT - 1) / NT;
+        // ---- (a) row set-up: raw q and the descriptors of the first segment in one round trip, q tables
         {
             const int bq = u / a.Hkv, hq0 = (u % a.Hkv) * REP;
             const uint32_t *qrow32 = reinterpret_cast<const uint32_t *>(a.q + ((int64_t)bq * a.Hkv * REP + hq0) * kD);
-            __syncthreads();                             // LDS of the previous segment is free
+            __syncthreads();                             // LDS of the previous row is free
             for (int i = tid; i < REP * 64; i += NT) L.qraw[i] = qrow32[i];
-            if (tid == 0) { L.range[0] = C; L.range[1] = C; }
-            // pass 1 (only when the row has more chunks than threads): the row total
-            unsigned long long total = 0;
-            if (n_tiles > 1) {
-                uint32_t sum = 0;
-                for (int tile = 0; tile < n_tiles; tile++) {
-                    const int c = tile * NT + tid;
-                    if (c < C) sum += chunk_cost<REP>(bits_of(erow[c]));
-                }
-#pragma unroll
-                for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
-                if (lane == 0) L.wsum[wave] = sum;
-                __syncthreads();
-#pragma unroll
-                for (int wv = 0; wv < NWV; wv++) total += L.wsum[wv];
-            }
-            unsigned long long base = 0;
-            int g0 = C, g1 = C;
-            for (int tile = 0; tile < n_tiles; tile++) {
-                const int c = tile * NT + tid;
-                const uint32_t cst = c < C ? chunk_cost<REP>(bits_of(erow[c])) : 0u;
-                uint32_t incl = cst;                                  // inclusive scan inside the wavefront
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const uint32_t v = __shfl_up(incl, o);
-                    if (lane >= o) incl += v;
-                }
-                if (tile > 0) __syncthreads();
-                if (lane == 63) L.wscan[wave] = incl;
-                __syncthreads();
-                unsigned long long pos = base + incl - cst, tile_total = 0;
-#pragma unroll
-                for (int wv = 0; wv < NWV; wv++) { if (wv < wave) pos += L.wscan[wv]; tile_total += L.wscan[wv]; }
-                if (n_tiles == 1) total = tile_total;
-                // chunk c belongs to the segment iff lo_num/NW <= pos_c/total < hi_num/NW
-                if (c < C) {
-                    if (pos * (unsigned)NW >= total * lo_num) g0 = min(g0, c);
-                    if (hi_num < (uint32_t)NW && pos * (unsigned)NW >= total * hi_num) g1 = min(g1, c);
-                }
-                base += tile_total;
-            }
-            if (g0 < C) atomicMin(&L.range[0], g0);
-            if (g1 < C) atomicMin(&L.range[1], g1);
-            if (n_tiles == 0) __syncthreads();           // no chunk at all: the scan's barrier did not run (qraw)
+            __syncthreads();
 
             const uint16_t *qraw = reinterpret_cast<const uint16_t *>(L.qraw);
             for (int i = tid; i < 4 * REP * 64; i += NT) {
@@ -797,9 +766,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 for (int i = tid; i < AttnLds<G, REP, NWV>::WLS; i += NT) L.zrow[i] = 0;
                 if (wave == 0) mc_build_q<G, REP>(L.qraw, lane, L);
             }
-            __syncthreads();
         }
-        const int c0 = __builtin_amdgcn_readfirstlane(L.range[0]), c1 = __builtin_amdgcn_readfirstlane(L.range[1]);
 
         WaveState<REP> st;
 #pragma unroll
@@ -811,86 +778,159 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
 #pragma unroll
         for (int ct = 0; ct < 8; ct++) st.accA[ct] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
         float qp[4];
-        if constexpr (REP > 1) {
-            const int slot0 = MC<G, REP>::slot0(lane >> 4);
+
+        // ---- (b) the row in segments whose chunk descriptors (block offset | log2 bits) sit in LDS.
+        //      A ticket is one unit (<= 4 KiB of K codes + 4 KiB of V codes: 128/64/32/16 tokens at
+        //      2/4/8/16 bits, or 16 rows of the FP16 residual), so every ticket costs about the same.
+        //      The tickets of a segment are shared by all workgroups of the row through a counter in
+        //      global memory: a workgroup is granted batches of consecutive tickets (guided sizes: a
+        //      share of what is left, so the last batches are small and everybody finishes together)
+        //      and its wavefronts draw from the granted range through a counter in LDS.
+        for (int seg = 0; seg < n_seg; seg++) {
+            const int cs = seg * seg_chunks, ce = min(C, cs + seg_chunks);
+            if (seg > 0) __syncthreads();                // previous segment's tables consumed
+            // chunks [cs + tid*KPT, +KPT) per thread: descriptor, units per chunk, exclusive scan
+            const int KPT = (seg_chunks + NT - 1) / NT;  // <= 2
+            uint32_t ucnt[2] = {0u, 0u}, mine = 0u;
 #pragma unroll
-            for (int n = 0; n < 4; n++) qp[n] = L.qsumg[(slot0 + n) / NG][(slot0 + n) % NG];
-        }
-
-        // ---- (b) the segment in passes of at most kDescCap chunks whose descriptors
-        //      (block offset | expert index) sit in LDS; wavefronts draw tickets from LDS
-        for (int cs = c0; cs < c1 || (cs == c0 && c0 >= c1); cs += kDescCap) {
-            const int ce = min(c1, cs + kDescCap);
-            const bool last_pass = ce >= c1;
-            if (cs > c0) __syncthreads();                // previous pass's descriptors consumed
-            for (int c = cs + tid; c < ce; c += NT) {
-                const int bits = bits_of(erow[c]);
-                const unsigned long long lgb = bits == 2 ? 1 : (bits == 4 ? 2 : (bits == 8 ? 3 : 4));
-                L.desc[c - cs] = orow[c] | lgb;          // block offsets are multiples of 256
+            for (int k = 0; k < 2; k++) {
+                const int c = cs + tid * KPT + k;
+                if (k < KPT && c < ce) {
+                    const int bits = bits_of(erow[c]);
+                    const int lgb = bits == 2 ? 1 : (bits == 4 ? 2 : (bits == 8 ? 3 : 4));
+                    L.desc[c - cs] = orow[c] | (unsigned long long)lgb;      // block offsets are multiples of 256
+                    ucnt[k] = (uint32_t)((N + (256 >> lgb) - 1) >> (8 - lgb));
+                    mine += ucnt[k];
+                }
             }
-            if (tid == 0) L.ticket = 0;
+            uint32_t incl = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t v = __shfl_up(incl, o);
+                if (lane >= o) incl += v;
+            }
+            if (lane == 63) L.wscan[wave] = incl;
+            if (tid == 0) { L.next = 0; L.limit = 0; L.done = 0; L.fetching = 0; L.g_seen = 0; L.nb = 0; }
             __syncthreads();
-            const int n_chunk_tickets = max(0, ce - cs) << LGPC;
-            const int TK = n_chunk_tickets + ((last_pass && hi_num == (uint32_t)NW) ? (a.n_tail + 127) / 128 : 0);
+            uint32_t pos = incl - mine, n_chunk_units = 0;
+#pragma unroll
+            for (int wv = 0; wv < NWV; wv++) { if (wv < wave) pos += L.wscan[wv]; n_chunk_units += L.wscan[wv]; }
+#pragma unroll
+            for (int k = 0; k < 2; k++) {
+                const int c = cs + tid * KPT + k;
+                if (k < KPT && c < ce) {
+                    L.ustart[c - cs] = (uint16_t)pos;
+                    for (uint32_t i = 0; i < ucnt[k]; i++) L.inv[pos + i] = (uint16_t)(c - cs);
+                    pos += ucnt[k];
+                }
+            }
+            __syncthreads();
+            if constexpr (REP > 1) {
+                if (seg == 0) {
+                    const int slot0 = MC<G, REP>::slot0(lane >> 4);
+#pragma unroll
+                    for (int n = 0; n < 4; n++) qp[n] = L.qsumg[(slot0 + n) / NG][(slot0 + n) % NG];
+                }
+            }
+            const uint32_t T = n_chunk_units + (uint32_t)(seg == n_seg - 1 ? (a.n_tail + 15) / 16 : 0);
+            unsigned int *counter = a.counters + ((size_t)u * n_seg + seg) * kCounterStride;
+            // no cap for a workgroup whose whole interval lies in this row, or that covers the whole row
+            const uint32_t quota = ov >= min(NW, a.BH) ? 0xffffffffu : (uint32_t)(((unsigned long long)T * (unsigned long long)ov + NW - 1) / NW);
 
-            // tickets: the draw for the next ticket is issued when the current one starts
-            int pend = 0;
-            auto issue_draw = [&]() { if (lane == 0) pend = atomicAdd(&L.ticket, 1); };
-            int c_lgb = 0, c_t0 = 0, c_tend = 0, s_next = 0, c_nu = 0, c_tail0 = -1;
-            const uint8_t *c_blk = nullptr;
-            bool have_ticket = false;
-            auto begin_ticket = [&]() {                  // the pending draw becomes the current ticket
-                const int tk = __builtin_amdgcn_readfirstlane(pend);
-                have_ticket = tk < TK;
-                if (!have_ticket) return;
+            // One wavefront at a time asks the row's counter for the next batch.
+            auto fetch = [&]() {
+                if (lane == 0) {
+                    const uint32_t limit = __atomic_load_n(&L.limit, __ATOMIC_RELAXED);
+                    if (!__atomic_load_n(&L.done, __ATOMIC_RELAXED)) {
+                        const uint32_t seen = L.g_seen, nb = L.nb;
+                        // guided batch size from the counter value seen at the previous grant (none yet:
+                        // the smallest batch), so that nobody sits on a large batch when the row runs dry
+                        uint32_t want = (uint32_t)NWV;
+                        if (nb > 0 && T > seen) want = max(want, (T - seen) / (4u * P));
+                        if (nb >= (uint32_t)kMaxBatches - 1) want = T;                 // table full: all that is left
+                        want = min(want, quota - limit);                               // limit < quota here
+                        const uint32_t g0 = atomicAdd(counter, want);
+                        L.g_seen = g0 + want;
+                        uint32_t granted = 0;
+                        if (g0 < T) {
+                            granted = min(want, T - g0);
+                            L.bl[nb] = limit; L.bg[nb] = g0; L.nb = nb + 1;
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                            __atomic_store_n(&L.limit, limit + granted, __ATOMIC_RELAXED);
+                        }
+                        if (g0 + want >= T || limit + granted >= quota) {
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                            __atomic_store_n(&L.done, 1u, __ATOMIC_RELAXED);
+                        }
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    __atomic_store_n(&L.fetching, 0u, __ATOMIC_RELAXED);
+                }
+            };
+            auto try_fetch = [&]() -> bool {             // true if this wavefront held the lock (and fetched)
+                uint32_t won = 0;
+                if (lane == 0) won = atomicCAS(&L.fetching, 0u, 1u) == 0u ? 1u : 0u;
+                won = (uint32_t)__builtin_amdgcn_readfirstlane((int)won);
+                if (won) fetch();
+                return won != 0;
+            };
+
+            // tickets: the draw for the next unit is issued when the current one is taken
+            uint32_t pend = 0;
+            int bcur = 0;                                // batch of this wavefront's latest ticket
+            auto issue_draw = [&]() { if (lane == 0) pend = atomicAdd(&L.next, 1u); };
+            auto next_unit = [&](Unit &un) -> bool {     // the pending draw becomes the next unit
+                const uint32_t t = (uint32_t)__builtin_amdgcn_readfirstlane((int)pend);
+                uint32_t limit;
+                for (;;) {                               // wait until local ticket t is granted, or nothing is left
+                    limit = (uint32_t)__builtin_amdgcn_readfirstlane((int)__atomic_load_n(&L.limit, __ATOMIC_RELAXED));
+                    if (t < limit) break;
+                    if (__builtin_amdgcn_readfirstlane((int)__atomic_load_n(&L.done, __ATOMIC_RELAXED))) {
+                        limit = (uint32_t)__builtin_amdgcn_readfirstlane((int)__atomic_load_n(&L.limit, __ATOMIC_RELAXED));
+                        if (t < limit) break;            // done is written after the last limit
+                        return false;
+                    }
+                    if (!try_fetch()) __builtin_amdgcn_s_sleep(2);
+                }
+                if (t + (uint32_t)NWV >= limit && !__builtin_amdgcn_readfirstlane((int)__atomic_load_n(&L.done, __ATOMIC_RELAXED)))
+                    try_fetch();                         // top up ahead of need; whoever gets the lock does it
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                while (bcur + 1 < __builtin_amdgcn_readfirstlane((int)__atomic_load_n(&L.nb, __ATOMIC_RELAXED)) &&
+                       t >= (uint32_t)__builtin_amdgcn_readfirstlane((int)L.bl[bcur + 1])) bcur++;
+                const uint32_t tk = (uint32_t)__builtin_amdgcn_readfirstlane((int)(L.bg[bcur] + (t - L.bl[bcur])));
                 issue_draw();
-                if (tk < n_chunk_tickets) {
-                    const unsigned long long dsc = L.desc[tk >> LGPC];
+                if (tk < n_chunk_units) {
+                    const int cl = __builtin_amdgcn_readfirstlane((int)L.inv[tk]);
+                    const unsigned long long dsc = L.desc[cl];
                     const uint32_t dlo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dsc);
                     const uint32_t dhi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dsc >> 32));
-                    c_lgb = (int)(dlo & 7u);
-                    c_blk = a.arena + (((unsigned long long)dhi << 32) | (dlo & ~0xffu));
-                    c_t0 = (tk & (PC - 1)) * TKN; c_tend = c_t0 + TKN; c_tail0 = -1;
-                    c_nu = (TKN + (256 >> c_lgb) - 1) >> (8 - c_lgb);    // units of 4 KiB of codes
-                } else {                                 // FP16 residual rows [c_tail0, c_tend)
-                    c_lgb = 4; c_tail0 = (tk - n_chunk_tickets) * 128; c_tend = min(a.n_tail, c_tail0 + 128);
-                    c_nu = (c_tend - c_tail0 + 15) >> 4;
+                    const int sidx = (int)tk - __builtin_amdgcn_readfirstlane((int)L.ustart[cl]);
+                    const int lgb = (int)(dlo & 7u);
+                    const uint8_t *blk = a.arena + (((unsigned long long)dhi << 32) | (dlo & ~0xffu));
+                    const int t0 = sidx << (8 - lgb);
+                    un.lgb = lgb;
+                    un.nsub = min(4, (N - t0) >> (6 - lgb)); un.nvalid = un.nsub << (6 - lgb);
+                    if (lgb == 4) {
+                        un.kc = blk + ((size_t)t0 << 8); un.vc = un.kc + ((size_t)N << 8);
+                        un.km = un.kc; un.vm = un.kc;    // no meta: see load_k
+                    } else {
+                        const size_t cb = (size_t)N << (4 + lgb), mb = (size_t)N * NG * 4;
+                        un.kc = blk + ((size_t)t0 << (4 + lgb));
+                        un.km = blk + cb + (size_t)t0 * NG * 4;
+                        un.vc = un.kc + cb + mb;
+                        un.vm = un.km + cb + mb;
+                    }
+                } else {                                 // 16 rows of the FP16 residual
+                    const int row0 = (int)(tk - n_chunk_units) * 16;
+                    const size_t rowb = ((size_t)u * N + (size_t)row0) * 256;
+                    un.lgb = 4; un.nsub = 4; un.nvalid = min(16, a.n_tail - row0);
+                    un.kc = reinterpret_cast<const uint8_t *>(a.K_tail) + rowb;
+                    un.vc = reinterpret_cast<const uint8_t *>(a.V_tail) + rowb;
+                    un.km = un.kc; un.vm = un.kc;
                 }
-                s_next = 0;
+                return true;
             };
             issue_draw();
-            begin_ticket();
-            auto next_unit = [&](Unit &un) -> bool {
-                for (;;) {
-                    if (!have_ticket) return false;
-                    if (s_next < c_nu) {
-                        const int s = s_next++;
-                        un.lgb = c_lgb;
-                        if (c_tail0 >= 0) {
-                            const size_t rowb = ((size_t)u * N + (size_t)(c_tail0 + 16 * s)) * 256;
-                            un.nsub = 4; un.nvalid = min(16, c_tend - c_tail0 - 16 * s);
-                            un.kc = reinterpret_cast<const uint8_t *>(a.K_tail) + rowb;
-                            un.vc = reinterpret_cast<const uint8_t *>(a.V_tail) + rowb;
-                            un.km = un.kc; un.vm = un.kc;            // no meta: see load_k
-                        } else {
-                            const int t0 = c_t0 + (s << (8 - c_lgb));
-                            un.nsub = min(4, (c_tend - t0) >> (6 - c_lgb)); un.nvalid = un.nsub << (6 - c_lgb);
-                            if (c_lgb == 4) {
-                                un.kc = c_blk + ((size_t)t0 << 8); un.vc = un.kc + ((size_t)N << 8);
-                                un.km = un.kc; un.vm = un.kc;
-                            } else {
-                                const size_t cb = (size_t)N << (4 + c_lgb), mb = (size_t)N * NG * 4;
-                                un.kc = c_blk + ((size_t)t0 << (4 + c_lgb));
-                                un.km = c_blk + cb + (size_t)t0 * NG * 4;
-                                un.vc = un.kc + cb + mb;
-                                un.vm = un.km + cb + mb;
-                            }
-                        }
-                        return true;
-                    }
-                    begin_ticket();                      // ticket finished: take the next one
-                }
-            };
 
             // K is requested half a unit ahead (right after the scores of the current unit), V a
             // whole unit ahead into the buffer the current unit does not use.
@@ -948,7 +988,6 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 if (!have) break;
                 step(vb, va);
             }
-            if (c0 >= c1) break;                         // empty chunk range: the single pass is done
         }
 
         // ---- (c) fold the wavefronts' states: o[d] = acc[d] * 2^24 + sum_t p_t zero_{t,g(d)}
@@ -1011,6 +1050,20 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     }
 }
 
+// Zeroes the ticket counters of a decode call (a kernel rather than a memset node, so that the call
+// can be captured into a graph).
+__global__ void attn_clear_kernel(unsigned int *counters, int n) {
+    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i < n) counters[(size_t)i * kCounterStride] = 0u;
+}
+int attn_row_segments(int n_chunks, int N) {
+    const int sc = attn_segment_chunks(N);
+    return n_chunks > sc ? (n_chunks + sc - 1) / sc : 1;
+}
+size_t attn_counter_bytes(int BH, int n_chunks, int N) {
+    return (size_t)BH * attn_row_segments(n_chunks, N) * kCounterStride * sizeof(unsigned int);
+}
+
 // out[b, hq, :] = sum_p o_p 2^(m_p - M) / sum_p l_p 2^(m_p - M) over the partials of the row
 // (one per workgroup that touched the row's KV head).
 constexpr int kMergeGroups = 2;
@@ -1061,6 +1114,10 @@ static int resident_wgs_per_cu() {
 template <int G, int REP>
 static hipError_t launch_gr(const AttnArgs &a, hipStream_t s) {
     constexpr int NWV = waves_per_wg<REP>();
+    const int n_counters = a.BH * attn_row_segments(a.n_chunks, a.N);
+    hipLaunchKernelGGL(attn_clear_kernel, dim3((unsigned)((n_counters + 255) / 256)), dim3(256), 0, s, a.counters, n_counters);
+    hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return e0;
     hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -1,5 +1,6 @@
 // Host-visible launch interface of the three kernels (internal to libmoqae).
 #pragma once
+#include <cstddef>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,6 +29,7 @@ struct AttnArgs {
     int64_t desc_stride;
     const uint16_t *K_tail, *V_tail;
     float *part; float *out;
+    unsigned int *counters;     // ticket counters, one per (row, row segment), attn_counter_bytes() in all
     float scale_log2;           // softmax_scale * log2(e)
     int n_chunks, n_tail, n_wg, max_partials, N, G, Hkv, rep, BH;
     int bits_of[8];
@@ -36,6 +38,7 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
 int attn_resident_wgs_per_cu(int G, int rep);   // occupancy of the split kernel (host query, cached)
 int attn_waves_per_wg(int rep);
 int attn_max_partials(int n_wg, int BH);        // partial slots per row
+size_t attn_counter_bytes(int BH, int n_chunks, int N); // bytes of the ticket counters at the start of the workspace
 
 
 }  // namespace moqae
