@@ -2,8 +2,8 @@
 // at its routed bit-width (Sec. 3.1-3.2 of the paper say only that a chunk is quantised with
 // the configuration its router chose; the quantiser and the layout are defined in moqae.h).
 //
-//   plan_kernel  one workgroup: block sizes -> exclusive scan in (b, h, c) order -> offsets,
-//                capacity check, new arena end.
+//   plan_rows_kernel / plan_kernel  block sizes -> exclusive scan in (b, h, c) order -> offsets and
+//                capacity check: one workgroup per row when the table allows, else one workgroup.
 //   pack_kernel  one workgroup per (chunk, K or V).  16 lanes own one token row (8 dims each),
 //                group min/max by DPP, codes in registers.  K words are assembled in registers
 //                (row-major layout); V codes go through LDS as bytes and are gathered
@@ -16,8 +16,32 @@ namespace moqae {
 
 constexpr int kPlanThreads = 1024;
 
+constexpr int kPlanRun = 8;                          // entries per thread and pass
+constexpr int kPlanPass = kPlanThreads * kPlanRun;
+
+// Sum over the workgroup (every thread gets it) and exclusive prefix of x over the threads.
+__device__ __forceinline__ unsigned long long plan_block_scan(unsigned long long x, unsigned long long *wsum,
+                                                              unsigned long long &total) {
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    unsigned long long incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+    __syncthreads();                                  // wsum free
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    unsigned long long before = 0; total = 0;
+#pragma unroll
+    for (int wv = 0; wv < kPlanThreads / 64; wv++) { const unsigned long long v = wsum[wv]; if (wv < wave) before += v; total += v; }
+    return before + incl - x;
+}
+
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PackArgs a) {
-    __shared__ unsigned long long scan[kPlanThreads];
+    __shared__ uint8_t ebuf[kPlanPass];               // a pass's expert indices, in (b, h, c) order
+    __shared__ uint32_t obuf[kPlanPass];              // their block offsets relative to the pass, in units of 256 bytes
+    __shared__ unsigned long long wsum[kPlanThreads / 64];
     __shared__ int bad;
     const int tid = (int)threadIdx.x;
     if (*a.status != 0) return;                       // sticky error: the call is a no-op
@@ -25,61 +49,160 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PackArgs a) {
     __syncthreads();
 
     const int64_t total = (int64_t)a.BH * a.n_chunks;
-    const int64_t per = (total + kPlanThreads - 1) / kPlanThreads;
-    const int64_t i0 = min(total, per * tid), i1 = min(total, i0 + per);
-    const int64_t u0 = i0 / a.n_chunks; const int cc0 = (int)(i0 % a.n_chunks);
-    unsigned long long size_of[8];                    // rounded block size per expert
+    uint32_t size_of[8];                              // rounded block size per expert, in units of 256 bytes
 #pragma unroll
-    for (int e = 0; e < 8; e++) size_of[e] = (block_bytes(a.N, a.G, a.bits_of[e]) + 255u) & ~255ull;
+    for (int e = 0; e < 8; e++) size_of[e] = (uint32_t)((block_bytes(a.N, a.G, a.bits_of[e]) + 255u) >> 8);
     auto size_at = [&](int e) {
-        unsigned long long v = 0;
+        uint32_t v = 0;
 #pragma unroll
         for (int k = 0; k < 8; k++) v = (e == k) ? size_of[k] : v;
         return v;
     };
-    unsigned long long local = 0;
-    {
-        int64_t u = u0; int cc = cc0;
-        for (int64_t i = i0; i < i1; i += 8) {            // eight independent loads in flight
-            int e[8];
-#pragma unroll
-            for (int k = 0; k < 8; k++) {
-                e[k] = (i + k < i1) ? a.expert[u * a.expert_stride + a.chunk_begin + cc] : 0;
-                if (++cc == a.n_chunks) { cc = 0; u++; }
-            }
-#pragma unroll
-            for (int k = 0; k < 8; k++) if (i + k < i1) { if (e[k] >= a.M) bad = 1; else local += size_at(e[k]); }
-        }
-    }
-    scan[tid] = local;
-    __syncthreads();
-    for (int off = 1; off < kPlanThreads; off <<= 1) {          // Hillis-Steele inclusive scan
-        unsigned long long v = tid >= off ? scan[tid - off] : 0;
-        __syncthreads();
-        scan[tid] += v;
-        __syncthreads();
-    }
     const unsigned long long start = (*a.arena_used + 255u) & ~255ull;
-    const unsigned long long sum = scan[kPlanThreads - 1];
-    if (bad) { if (tid == 0) *a.status = -1; return; }
-    if (start + sum > a.capacity) { if (tid == 0) *a.status = -3; return; }
-    unsigned long long pos = start + scan[tid] - local;
+    // Entry j of the pass that begins at p0 is (row u, chunk cc) with u*n_chunks + cc = p0 + j; thread t
+    // handles entries t, t + 1024, ... (coalesced), stepping (u, cc) without a division.
+    const int step_u = kPlanThreads / a.n_chunks, step_c = kPlanThreads % a.n_chunks;
+
+    // Sweep 1: the total size (capacity and expert check) -- nothing is written when the call fails.
+    unsigned long long mine = 0, all = 0;
     {
-        int64_t u = u0; int cc = cc0;
-        for (int64_t i = i0; i < i1; i += 8) {
-            int e[8]; int64_t at[8];
+        int64_t u = tid / a.n_chunks; int cc = tid - (int)u * a.n_chunks;
+        for (int64_t i = tid; i < total; i += (int64_t)kPlanThreads * 16) {
+            int e[16];
 #pragma unroll
-            for (int k = 0; k < 8; k++) {
-                at[k] = u * a.off_stride + a.chunk_begin + cc;
-                e[k] = (i + k < i1) ? a.expert[u * a.expert_stride + a.chunk_begin + cc] : 0;
-                if (++cc == a.n_chunks) { cc = 0; u++; }
+            for (int k = 0; k < 16; k++) {
+                e[k] = (i + (int64_t)k * kPlanThreads < total) ? a.expert[u * a.expert_stride + a.chunk_begin + cc] : 0;
+                u += step_u; cc += step_c;
+                if (cc >= a.n_chunks) { cc -= a.n_chunks; u++; }
             }
 #pragma unroll
-            for (int k = 0; k < 8; k++) if (i + k < i1) { a.chunk_off[at[k]] = pos; pos += size_at(e[k]); }
+            for (int k = 0; k < 16; k++)
+                if (i + (int64_t)k * kPlanThreads < total) { if (e[k] >= a.M) bad = 1; else mine += size_at(e[k]); }
         }
     }
-    __syncthreads();                                  // every thread has read *arena_used
-    if (tid == 0) *a.arena_used = start + sum;
+    plan_block_scan(mine, wsum, all);
+    if (bad) { if (tid == 0) *a.status = -1; return; }
+    if (start + (all << 8) > a.capacity) { if (tid == 0) *a.status = -3; return; }
+
+    // Sweep 2: offsets, a pass of kPlanPass entries at a time: staged into LDS with coalesced loads,
+    // thread t scans the run of kPlanRun entries from t*kPlanRun, offsets go back through LDS so
+    // that the stores are coalesced too.
+    unsigned long long carry = start;
+    for (int64_t p0 = 0; p0 < total; p0 += kPlanPass) {
+        const int n_pass = (int)min((int64_t)kPlanPass, total - p0);
+        int64_t u = (p0 + tid) / a.n_chunks; int cc = (int)((p0 + tid) - u * a.n_chunks);
+        int64_t at[kPlanRun];
+#pragma unroll
+        for (int k = 0; k < kPlanRun; k++) {
+            const int j = k * kPlanThreads + tid;
+            at[k] = u * a.off_stride + a.chunk_begin + cc;
+            if (j < n_pass) ebuf[j] = a.expert[u * a.expert_stride + a.chunk_begin + cc];
+            u += step_u; cc += step_c;
+            if (cc >= a.n_chunks) { cc -= a.n_chunks; u++; }
+        }
+        __syncthreads();
+        const int j0 = min(n_pass, tid * kPlanRun), j1 = min(n_pass, j0 + kPlanRun);
+        uint32_t sz[kPlanRun], local = 0;
+#pragma unroll
+        for (int k = 0; k < kPlanRun; k++) { sz[k] = j0 + k < j1 ? size_at(ebuf[j0 + k]) : 0u; local += sz[k]; }
+        unsigned long long pass_total;
+        uint32_t pos = (uint32_t)plan_block_scan(local, wsum, pass_total);
+#pragma unroll
+        for (int k = 0; k < kPlanRun; k++) { if (j0 + k < j1) obuf[j0 + k] = pos; pos += sz[k]; }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kPlanRun; k++) {
+            const int j = k * kPlanThreads + tid;
+            if (j < n_pass) a.chunk_off[at[k]] = carry + ((unsigned long long)obuf[j] << 8);
+        }
+        carry += pass_total << 8;
+        __syncthreads();                              // ebuf, obuf free
+    }
+}
+
+// The same plan with one workgroup per (sequence, KV head) row, for tables of at most kPlanRowsMax rows
+// whose rows can be read 16 bytes at a time.  Every workgroup reads the whole expert table (it is
+// small and stays in L2), so that each knows the sizes of all rows -- the base of its own row and
+// the total for the capacity check -- without any exchange between workgroups; it then writes the
+// offsets of its own row.
+constexpr int kPlanRowsMax = 1024;
+__global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(PackArgs a) {
+    __shared__ uint32_t rowtot[kPlanRowsMax];         // block bytes of every row, in units of 256 bytes
+    __shared__ unsigned long long wsum[kPlanThreads / 64];
+    __shared__ int bad;
+    const int tid = (int)threadIdx.x, u_own = (int)blockIdx.x;
+    if (*a.status != 0) return;                       // sticky error: the call is a no-op
+    for (int i = tid; i < a.BH; i += kPlanThreads) rowtot[i] = 0;
+    if (tid == 0) bad = 0;
+    __syncthreads();
+
+    uint32_t size_of[8];
+    unsigned long long lut = 0;                       // size_of[e] in 16-bit field e (a block is < 2^16 * 256 bytes)
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        size_of[e] = (uint32_t)((block_bytes(a.N, a.G, a.bits_of[e]) + 255u) >> 8);
+        if (e < 4) lut |= (unsigned long long)size_of[e] << (16 * e);
+    }
+    unsigned long long lut_hi = 0;
+#pragma unroll
+    for (int e = 4; e < 8; e++) lut_hi |= (unsigned long long)size_of[e] << (16 * (e - 4));
+    auto size_at = [&](uint32_t e) { return (uint32_t)(((e & 4u) ? lut_hi : lut) >> (16u * (e & 3u))) & 0xffffu; };
+    const unsigned long long start = (*a.arena_used + 255u) & ~255ull;
+
+    // (1) sizes of all rows: 16-byte pieces of the table, all requested before any is used
+    const int C = a.n_chunks, C16 = C & ~15, ppr = C16 / 16;             // whole pieces per row
+    const int n_pieces = a.BH * ppr;
+    for (int p0 = 0; p0 < n_pieces; p0 += kPlanThreads * 8) {
+        uint4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const int p = min(p0 + k * kPlanThreads + tid, n_pieces - 1);
+            const int row = p / ppr, c = (p - row * ppr) * 16;
+            v[k] = *reinterpret_cast<const uint4 *>(a.expert + (int64_t)row * a.expert_stride + a.chunk_begin + c);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const int p = p0 + k * kPlanThreads + tid;
+            if (p < n_pieces) {
+                const uint32_t wv[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+                uint32_t sum = 0;
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const uint32_t e = (wv[i >> 2] >> (8 * (i & 3))) & 0xffu;
+                    if (e >= (uint32_t)a.M) bad = 1;
+                    sum += size_at(e);
+                }
+                atomicAdd(&rowtot[p / ppr], sum);
+            }
+        }
+    }
+    for (int i = tid; i < a.BH * (C - C16); i += kPlanThreads) {         // the last < 16 chunks of every row
+        const int row = i / (C - C16), c = C16 + i % (C - C16);
+        const uint32_t e = a.expert[(int64_t)row * a.expert_stride + a.chunk_begin + c];
+        if (e >= (uint32_t)a.M) bad = 1;
+        atomicAdd(&rowtot[row], size_at(e));
+    }
+    __syncthreads();
+
+    // (2) base of every row and the total; the verdict is the same in every workgroup
+    unsigned long long all = 0;
+    const unsigned long long before = plan_block_scan(tid < a.BH ? (unsigned long long)rowtot[tid] : 0ull, wsum, all);
+    __shared__ unsigned long long own_base;
+    if (tid == u_own) own_base = before;
+    if (bad) { if (tid == 0 && u_own == 0) *a.status = -1; return; }
+    if (start + (all << 8) > a.capacity) { if (tid == 0 && u_own == 0) *a.status = -3; return; }
+    __syncthreads();
+
+    // (3) the offsets of this workgroup's row
+    unsigned long long carry = start + (own_base << 8);
+    for (int c0 = 0; c0 < C; c0 += kPlanThreads) {
+        const int c = c0 + tid;
+        const uint32_t sz = c < C ? size_at(a.expert[(int64_t)u_own * a.expert_stride + a.chunk_begin + c]) : 0u;
+        unsigned long long pass_total;
+        const unsigned long long pos = plan_block_scan(sz, wsum, pass_total);
+        if (c < C) a.chunk_off[(int64_t)u_own * a.off_stride + a.chunk_begin + c] = carry + (pos << 8);
+        carry += pass_total << 8;
+    }
 }
 
 constexpr int kPackThreads = 256;
@@ -97,6 +220,13 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     const int isV = (int)blockIdx.z;
     const int tid = (int)threadIdx.x;
     const int N = a.N;
+    if (blockIdx.x == 0 && u == 0 && isV == 0 && tid == 0) {
+        // the new end of the arena = the end of the last block in (b, h, c) order (the plan kernels
+        // leave the counter alone: their workgroups read it at different times)
+        const int64_t lu = a.BH - 1, lc = a.chunk_begin + a.n_chunks - 1;
+        const unsigned long long sz = (block_bytes(N, a.G, a.bits_of[a.expert[lu * a.expert_stride + lc]]) + 255u) & ~255ull;
+        *a.arena_used = a.chunk_off[lu * a.off_stride + lc] + sz;
+    }
     const int bits = a.bits_of[a.expert[(int64_t)u * a.expert_stride + c]];
     uint8_t *blk = a.arena + a.chunk_off[(int64_t)u * a.off_stride + c];
     const int b = u / a.Hkv, h = u % a.Hkv;
@@ -192,7 +322,10 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
 
 hipError_t launch_pack(const PackArgs &a, hipStream_t s) {
     if (a.n_chunks <= 0 || a.BH <= 0) return hipSuccess;
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
+    const bool rows_ok = a.BH <= kPlanRowsMax &&
+                         ((reinterpret_cast<uintptr_t>(a.expert + a.chunk_begin) | (uintptr_t)a.expert_stride) & 15u) == 0;
+    if (rows_ok) hipLaunchKernelGGL(plan_rows_kernel, dim3((unsigned)a.BH), dim3(kPlanThreads), 0, s, a);
+    else         hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)a.n_chunks, (unsigned)a.BH, 2u);
