@@ -485,13 +485,12 @@ __device__ __forceinline__ v4u mc_kcodes(const KRegsMC<G, REP> &k, int tile, int
 
 // A operands of the score passes for the three quantised bit-widths, from the raw fp16 queries in LDS.
 template <int G, int REP, typename LDS>
-__device__ __forceinline__ void mc_build_q(const uint32_t *qraw32, int lane, LDS &L) {
+__device__ __forceinline__ void mc_build_q(const uint32_t *qraw32, int lane, int mi, LDS &L) {
     using M = MC<G, REP>;
     const int i = lane & 15, qd = lane >> 4;
     const int slot = i % M::R, r = slot / M::NG, g = slot % M::NG;
     const bool own = g == (32 * qd) / G;                 // the quarter's dims lie in the row's group
-#pragma unroll
-    for (int mi = 0; mi < 4; mi++) {
+    {                                                    // pass mi: one wavefront per pass
         v4u ak[3];
 #pragma unroll
         for (int pr = 0; pr < 4; pr++) {
@@ -499,7 +498,7 @@ __device__ __forceinline__ void mc_build_q(const uint32_t *qraw32, int lane, LDS
             const float q0 = half_bits_to_float(qq & 0xffffu), q1 = half_bits_to_float(qq >> 16);
 #pragma unroll
             for (int bi = 0; bi < 3; bi++) {
-                const int kp = bi == 0 ? pair_exp<2>(mc_pair<2>(mi, pr)) : (bi == 1 ? pair_exp<4>(mc_pair<4>(mi, pr)) : 0);
+                const int kp = bi == 0 ? pair_exp<2>(mc_pair<2>(mi, pr)) : (bi == 1 ? pair_exp<4>(mc_pair<4>(mi, pr)) : 0);   // mi & 1 decides
                 const float f = __builtin_bit_cast(float, (uint32_t)(127 - kp) << 23);
                 const uint32_t v = float_to_half_bits(q0 * f) | (float_to_half_bits(q1 * f) << 16);
                 ak[bi][pr] = own ? v : 0u;
@@ -764,7 +763,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     L.qsumg[i / NG][i % NG] = sq * kTwoM24;
                 }
                 for (int i = tid; i < AttnLds<G, REP, NWV>::WLS; i += NT) L.zrow[i] = 0;
-                if (wave == 0) mc_build_q<G, REP>(L.qraw, lane, L);
+                if (wave < 4) mc_build_q<G, REP>(L.qraw, lane, wave, L);
             }
         }
 
