@@ -389,11 +389,12 @@ __device__ __forceinline__ void fp16_values(const Unit &u, const VRegs<G> &v, in
         for (int j = 0; j < 4; j++) {
             const float p24 = p4[r][j] * kTwoM24;                     // accumulators carry a factor 2^-24
             const bool ok = 4 * j + tok_l < nvalid;                   // rows past nvalid may hold NaN / Inf
-            const uint32_t w[4] = {v.c[j].x, v.c[j].y, v.c[j].z, v.c[j].w};
+            // the packed halves feed the multiply-add directly (mixed-precision FMA), nothing is unpacked
+            const uint32_t w[4] = {ok ? v.c[j].x : 0u, ok ? v.c[j].y : 0u, ok ? v.c[j].z : 0u, ok ? v.c[j].w : 0u};
 #pragma unroll
             for (int e = 0; e < 8; e++) {
-                const float x = ok ? half_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xffffu) : 0.0f;
-                acc8[e] = fmaf(p24, x, acc8[e]);
+                const half2_t h = as_half2(w[e >> 1]);
+                acc8[e] = fmaf(p24, (float)((e & 1) ? h.y : h.x), acc8[e]);
             }
         }
         // fold the four row groups, then hand every dim to the lane that owns it (2l, 2l+1)
