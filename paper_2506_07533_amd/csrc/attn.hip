@@ -1096,7 +1096,7 @@ __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const floa
     }
 }
 
-template <int REP> constexpr int waves_per_wg() { return REP == 1 ? 12 : 8; }
+template <int REP> constexpr int waves_per_wg() { return 8; }
 
 template <int G, int REP>
 static int resident_wgs_per_cu() {
@@ -1134,7 +1134,7 @@ int attn_resident_wgs_per_cu(int G, int rep) {
 #undef MOQAE_CASE
     return 1;
 }
-int attn_waves_per_wg(int rep) { return rep == 1 ? 12 : 8; }
+int attn_waves_per_wg(int rep) { (void)rep; return 8; }
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
 #define MOQAE_CASE(GV, RV) if (a.G == GV && a.rep == RV) return launch_gr<GV, RV>(a, s);
