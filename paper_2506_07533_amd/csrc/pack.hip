@@ -206,13 +206,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(PackArgs a) {
 }
 
 constexpr int kPackThreads = 256;
+constexpr int kVRow = kD + 4;                        // bytes per token row of the V staging buffer
 
 // Position of the code with in-word index e (b bits): even e in the low half-word, odd e high.
 __device__ __forceinline__ int code_shift(int e, int b) { return 16 * (e & 1) + b * (e >> 1); }
 
 template <int G>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
-    extern __shared__ uint8_t vcodes[];               // [N][128] code bytes (V only)
+    extern __shared__ uint8_t vcodes[];               // [N][kVRow] code bytes (V only); odd dword stride: rows fall on different banks
     if (*a.status != 0) return;
 
     const int c = a.chunk_begin + (int)blockIdx.x;
@@ -220,13 +221,6 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     const int isV = (int)blockIdx.z;
     const int tid = (int)threadIdx.x;
     const int N = a.N;
-    if (blockIdx.x == 0 && u == 0 && isV == 0 && tid == 0) {
-        // the new end of the arena = the end of the last block in (b, h, c) order (the plan kernels
-        // leave the counter alone: their workgroups read it at different times)
-        const int64_t lu = a.BH - 1, lc = a.chunk_begin + a.n_chunks - 1;
-        const unsigned long long sz = (block_bytes(N, a.G, a.bits_of[a.expert[lu * a.expert_stride + lc]]) + 255u) & ~255ull;
-        *a.arena_used = a.chunk_off[lu * a.off_stride + lc] + sz;
-    }
     const int bits = a.bits_of[a.expert[(int64_t)u * a.expert_stride + c]];
     uint8_t *blk = a.arena + a.chunk_off[(int64_t)u * a.off_stride + c];
     const int b = u / a.Hkv, h = u % a.Hkv;
@@ -279,10 +273,9 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
         if ((lane16 % LPG) == 0) meta_w[row * NG + lane16 / LPG] = s16 | (float_to_half_bits(mn) << 16);
 
         if (isV) {
-            uint2 pk;
-            pk.x = code[0] | code[1] << 8 | code[2] << 16 | code[3] << 24;
-            pk.y = code[4] | code[5] << 8 | code[6] << 16 | code[7] << 24;
-            *reinterpret_cast<uint2 *>(vcodes + row * kD + lane16 * 8) = pk;
+            uint32_t *dstv = reinterpret_cast<uint32_t *>(vcodes + row * kVRow + lane16 * 8);
+            dstv[0] = code[0] | code[1] << 8 | code[2] << 16 | code[3] << 24;
+            dstv[1] = code[4] | code[5] << 8 | code[6] << 16 | code[7] << 24;
         } else if (bits == 2) {                       // 16 dims per word: two lanes per word
             uint32_t w = 0;
 #pragma unroll
@@ -309,15 +302,30 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     // tokens (TW = 32/bits per word, WD = TQ/TW words) of CPK = 4/WD dimensions that lie 16 apart;
     // slot 16*qd + j of tile cg of a block of 4*TQ tokens: dims 16*(cg*CPK + n/WD) + j, token slice qd.
     const int TW = 32 / bits, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, NCG = kD / (16 * CPK);
-    const int n_words = N * kD * bits / 32;
-    for (int wv = tid; wv < n_words; wv += kPackThreads) {
-        const int n = wv & 3, l = (wv >> 2) & 63, kib = wv >> 8;
-        const int cg = kib % NCG, block = kib / NCG, qd = l >> 4, j = l & 15;
-        const int d = 16 * (cg * CPK + n / WD) + j, t0 = block * 4 * TQ + qd * TQ + (n % WD) * TW;
-        uint32_t w = 0;
-        for (int e = 0; e < TW; e++) w |= (uint32_t)vcodes[(t0 + e) * kD + d] << code_shift(e, bits);
-        codes_w[wv] = w;
+    const int n_groups = N * kD * bits / 128;         // a thread builds the words of four adjacent dims at a time
+    for (int g = tid; g < n_groups; g += kPackThreads) {
+        const int n = g & 3, jq = (g >> 2) & 3, qd = (g >> 4) & 3, kib = g >> 6;
+        const int cg = kib % NCG, block = kib / NCG;
+        const int d0 = 16 * (cg * CPK + n / WD) + 4 * jq, t0 = block * 4 * TQ + qd * TQ + (n % WD) * TW;
+        uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+        for (int e = 0; e < TW; e++) {
+            const uint32_t v4 = *reinterpret_cast<const uint32_t *>(vcodes + (t0 + e) * kVRow + d0);   // codes of dims d0..d0+3
+            const int sh = code_shift(e, bits);
+            w0 |= (v4 & 0xffu) << sh; w1 |= ((v4 >> 8) & 0xffu) << sh; w2 |= ((v4 >> 16) & 0xffu) << sh; w3 |= (v4 >> 24) << sh;
+        }
+        uint32_t *dst = codes_w + (kib * 64 + 16 * qd + 4 * jq) * 4 + n;     // slot 16*qd + 4*jq + k, word n
+        dst[0] = w0; dst[4] = w1; dst[8] = w2; dst[12] = w3;
     }
+}
+
+// The new end of the arena = the end of the last block in (b, h, c) order.  A kernel of its own, after
+// the plan: the workgroups of the plan read the counter at different times, so none of them may move
+// it, and the few registers this takes would cost the pack kernel occupancy.
+__global__ void arena_end_kernel(PackArgs a) {
+    if (*a.status != 0) return;
+    const int64_t lu = a.BH - 1, lc = a.chunk_begin + a.n_chunks - 1;
+    const unsigned long long sz = (block_bytes(a.N, a.G, a.bits_of[a.expert[lu * a.expert_stride + lc]]) + 255u) & ~255ull;
+    *a.arena_used = a.chunk_off[lu * a.off_stride + lc] + sz;
 }
 
 hipError_t launch_pack(const PackArgs &a, hipStream_t s) {
@@ -329,9 +337,12 @@ hipError_t launch_pack(const PackArgs &a, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)a.n_chunks, (unsigned)a.BH, 2u);
-    const size_t lds = (size_t)a.N * kD;
+    const size_t lds = (size_t)a.N * kVRow;
     if (a.G == 32) hipLaunchKernelGGL(pack_kernel<32>, grid, dim3(kPackThreads), lds, s, a);
     else           hipLaunchKernelGGL(pack_kernel<64>, grid, dim3(kPackThreads), lds, s, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(arena_end_kernel, dim3(1), dim3(1), 0, s, a);
     return hipGetLastError();
 }
 
