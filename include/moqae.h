@@ -166,6 +166,14 @@ uint64_t moqae_decode_workspace_bytes(const moqae_cfg *cfg, int32_t n_chunks);  
 const char *moqae_strerror(int code);
 uint32_t moqae_abi_version(void);
 
+/*
+ * Measurement aid, not part of the method: the decode calls this host thread makes from now on record
+ * the two given events (hipEvent_t passed as void*, owned by the caller, created with timing enabled)
+ * on the call's stream right before and right after the main kernel of moqae_decode_attn, so that a
+ * benchmark can time that kernel alone, as a profiler does.  Pass NULL, NULL to stop.  Returns MOQAE_OK.
+ */
+int moqae_debug_time_decode_kernel(void *event_begin, void *event_end);
+
 #ifdef __cplusplus
 }
 #endif

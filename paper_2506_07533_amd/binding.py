@@ -50,7 +50,8 @@ class Cfg:
 
 _lib = None
 EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "moqae_chunk_block_bytes",
-           "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version"]
+           "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version",
+           "moqae_debug_time_decode_kernel"]
 
 
 def lib():

@@ -91,9 +91,16 @@ uint64_t workspace_bytes(const moqae_cfg *c, int n_chunks) {
     return counters_bytes(c, n_chunks) + rows * (uint64_t)attn_max_partials(n_wg, BH) * (kD + 2) * sizeof(float);
 }
 
+thread_local hipEvent_t g_time_begin = nullptr, g_time_end = nullptr;   // measurement aid, see moqae.h
+
 }  // namespace
 
 extern "C" {
+
+int moqae_debug_time_decode_kernel(void *event_begin, void *event_end) {
+    g_time_begin = static_cast<hipEvent_t>(event_begin); g_time_end = static_cast<hipEvent_t>(event_end);
+    return MOQAE_OK;
+}
 
 uint32_t moqae_abi_version(void) { return MOQAE_ABI_VERSION; }
 
@@ -213,7 +220,7 @@ int moqae_decode_attn(const moqae_cfg *cfg,
     a.N = cfg->chunk; a.G = cfg->group; a.Hkv = cfg->n_kv_heads; a.rep = cfg->n_q_heads / cfg->n_kv_heads;
     a.BH = cfg->batch * cfg->n_kv_heads;
     for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;
-    hipError_t e = launch_attn(a, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_attn(a, static_cast<hipStream_t>(stream), g_time_begin, g_time_end);
     return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
 }
 

@@ -1112,15 +1112,17 @@ static int resident_wgs_per_cu() {
 }
 
 template <int G, int REP>
-static hipError_t launch_gr(const AttnArgs &a, hipStream_t s) {
+static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     constexpr int NWV = waves_per_wg<REP>();
     const int n_counters = a.BH * attn_row_segments(a.n_chunks, a.N);
     hipLaunchKernelGGL(attn_clear_kernel, dim3((unsigned)((n_counters + 255) / 256)), dim3(256), 0, s, a.counters, n_counters);
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
+    if (ev_begin && hipEventRecord(ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (ev_end && hipEventRecord(ev_end, s) != hipSuccess) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)(a.BH * a.rep)), dim3(kD * kMergeGroups), 0, s,
                        (const float *)a.part, a.out, a.rep, a.n_wg, a.BH, a.max_partials);
     return hipGetLastError();
@@ -1136,8 +1138,8 @@ int attn_resident_wgs_per_cu(int G, int rep) {
 }
 int attn_waves_per_wg(int rep) { (void)rep; return 8; }
 
-hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
-#define MOQAE_CASE(GV, RV) if (a.G == GV && a.rep == RV) return launch_gr<GV, RV>(a, s);
+hipError_t launch_attn(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
+#define MOQAE_CASE(GV, RV) if (a.G == GV && a.rep == RV) return launch_gr<GV, RV>(a, s, ev_begin, ev_end);
     MOQAE_FOR_EACH_VARIANT(MOQAE_CASE)
 #undef MOQAE_CASE
     return hipErrorInvalidValue;

@@ -34,7 +34,7 @@ struct AttnArgs {
     int n_chunks, n_tail, n_wg, max_partials, N, G, Hkv, rep, BH;
     int bits_of[8];
 };
-hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 int attn_resident_wgs_per_cu(int G, int rep);   // occupancy of the split kernel (host query, cached)
 int attn_waves_per_wg(int rep);
 int attn_max_partials(int n_wg, int BH);        // partial slots per row
