@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # HBM bytes per decode call (attn_split_kernel + attn_merge_kernel, fetched + written) from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_<workload>.md; counters cannot be read
 # from inside this process, so a workload without such a run reports null.
-MEASURED_TRAFFIC = {"llama13b_128k": 693514240}
+MEASURED_TRAFFIC = {"llama13b_128k": 693527135}
 
 
 def log(*a):
@@ -96,6 +96,8 @@ def main() -> int:
     from paper_2506_07533_amd import binding as mq, synth
 
     w = synth.WORKLOADS[args.workload]
+    if w.n_layers > 1:
+        return bench_stack(args, w)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     BH, C, T, M = w.batch * w.n_kv_heads, w.n_chunks, w.n_tail, len(w.expert_bits)
@@ -146,10 +148,10 @@ def main() -> int:
         if not args.decode_only:
             mq.quantize_pack(cfg, K, V, 0, C, expert, arenas[a], useds[a], offs[a], status)
         if ev: ev[2].record()
-        if k is not None: L.moqae_debug_time_decode_kernel(*hev.pair(k))
+        if k is not None and (k & 1): L.moqae_debug_time_decode_kernel(*hev.pair(k))   # odd steps: the main kernel alone
         mq.decode_attn(cfg, q, arenas[a ^ 1], offs[a ^ 1], expert, C, Kt if T else None, Vt if T else None, T,
                        scale, out, ws)
-        if k is not None: L.moqae_debug_time_decode_kernel(None, None)
+        if k is not None and (k & 1): L.moqae_debug_time_decode_kernel(None, None)
         if ev: ev[3].record()
 
     for a in range(2):                                   # both arenas packed before anything is timed
@@ -170,8 +172,10 @@ def main() -> int:
     assert int(status.item()) == 0, "arena overflow"
     t_route = np.array([e[0].elapsed_time(e[1]) for e in evs])
     t_pack = np.array([e[1].elapsed_time(e[2]) for e in evs])
-    t_attn = np.array([e[2].elapsed_time(e[3]) for e in evs])         # the whole decode call (three kernels)
-    t_split = np.array([hev.elapsed_ms(i) for i in range(args.steps)])  # its main kernel alone
+    # the whole decode call (three kernels) on the even steps, where nothing else is recorded inside it;
+    # its main kernel alone on the odd steps
+    t_attn = np.array([e[2].elapsed_time(e[3]) for i, e in enumerate(evs) if not (i & 1)])
+    t_split = np.array([hev.elapsed_ms(i) for i in range(args.steps) if i & 1]) if args.steps > 1 else t_attn
     ms_per_step = wall_ms / args.steps
 
     n_units = BH * C
@@ -214,6 +218,101 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, scale)
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+def bench_stack(args, w):
+    """The multi-layer workload: prefill compression of every layer with routing sharing (one routed
+    layer per group), then decode steps that append one token to every layer and attend over it.
+    A step here = one decode step over all layers (append + decode call per layer)."""
+    import math
+    import torch
+    from paper_2506_07533_amd import binding as mq, cache, synth
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    N, D, B, H = w.chunk, w.head_dim, w.batch, w.n_kv_heads
+    C0 = w.seq // N
+    cfg = mq.Cfg(B, w.n_q_heads, H, D, N, w.group, w.expert_bits, w.freeze_chunks)
+    blk = [mq.chunk_block_bytes(cfg, b) for b in w.expert_bits]
+    mean_blk = sum(sz * p for sz, p in zip(blk, w.mix))
+    arena_bytes = int(B * H * (C0 + 2) * mean_blk * 1.08)
+    stack = cache.KVStack(cfg, w.n_layers, w.share_group, C0 + 1, arena_bytes=[arena_bytes] * w.n_layers)
+    routers = {}
+    t_route = t_pack = 0.0
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for l in range(w.n_layers):
+        d = synth.make_layer_device(w, l, dev)
+        routers[l] = (d["W1"], d["W2"], d["W3"], None)
+        lc = stack.layers[l]
+        # one untimed pass first (the first kernel to touch freshly written tensors of this size pays several
+        # milliseconds of address-translation warm-up that has nothing to do with the method)
+        if stack.is_leader(l):
+            lc.route(d["K"], 0, C0, routers[l])
+        lc.pack(d["K"], d["V"], 0, C0)
+        lc.arena_used.zero_()
+        torch.cuda.synchronize()
+        ev[0].record()
+        if stack.is_leader(l):
+            lc.route(d["K"], 0, C0, routers[l])
+        else:
+            lc.share_decisions_from(stack.layers[stack.leader_of(l)], 0, C0)
+        ev[1].record()
+        lc.pack(d["K"], d["V"], 0, C0)
+        ev[2].record()
+        torch.cuda.synchronize()
+        lc.n_chunks, lc.n_tail = C0, 0
+        t_route += ev[0].elapsed_time(ev[1]); t_pack += ev[1].elapsed_time(ev[2])
+        lc.check_status()
+        del d
+        log(f"[bench] layer {l} compressed")
+    packed = sum(int(lc.arena_used.item()) for lc in stack.layers)
+    n_units = B * H * C0 * w.n_layers
+
+    scale = 1.0 / math.sqrt(D)
+    g = torch.Generator(device=dev); g.manual_seed(99)
+    kn = torch.randn((B, H, D), generator=g, device=dev, dtype=torch.float16)
+    vn = torch.randn((B, H, D), generator=g, device=dev, dtype=torch.float16)
+    q = torch.randn((B, w.n_q_heads, D), generator=g, device=dev, dtype=torch.float16)
+    out = torch.zeros((B, w.n_q_heads, D), dtype=torch.float32, device=dev)
+
+    def step():
+        for l in range(w.n_layers):
+            stack.append(l, kn, vn, routers)
+            stack.layers[l].decode(q, out, scale)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    n_tail = stack.layers[0].n_tail
+    step_bytes = packed + w.n_layers * (B * H * C0 * 9 + 2 * B * H * n_tail * D * 2 + q.numel() * 2 + out.numel() * 4)
+    gbps = step_bytes / (gpu_ms / args.steps * 1e-3) / 1e9
+    res = {
+        "metric": "decode_attn_hbm_GBps", "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": B, "q_heads": w.n_q_heads, "kv_heads": H, "head_dim": D,
+                   "cached_tokens": w.seq, "chunk": N, "group": w.group, "layers": w.n_layers,
+                   "routing_sharing_group": w.share_group, "chunks": n_units, "packed_bytes": packed,
+                   "step": "one decode step over all layers: append one token and one decode call per layer"},
+        "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None, "bytes_per_launch": int(step_bytes // w.n_layers),
+                     "avg_ms": round(gpu_ms / args.steps / w.n_layers, 4),
+                     "kernel": "decode calls of a step, appends included (GPU time of the step / layers)"},
+        "pct_of_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
+        "prefill_route_ms": round(t_route, 3), "prefill_pack_ms": round(t_pack, 3),
+        "route_pack_chunks_per_s": round(n_units / ((t_route + t_pack) * 1e-3), 1),
+        "routed_layers": w.n_layers // max(1, w.share_group),
+    }
     print(json.dumps(res), flush=True)
     return 0
 
