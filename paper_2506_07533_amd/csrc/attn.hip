@@ -3,20 +3,23 @@
 // paper: the quantised keys are de-quantised before they meet the query; softmax needs high
 // precision).
 //
-// attn_split_kernel   one persistent workgroup per CU (16 wavefronts; 8 for grouped queries).  A
-//                     workgroup owns a cost-balanced interval of the (sequence, KV head) rows;
-//                     inside a row its wavefronts draw tickets of 128 tokens from an LDS
-//                     counter and stream them "unit" by unit.  A unit is up to 4 KiB of K
-//                     codes plus the matching 4 KiB of V codes (128 / 64 / 32 / 16 tokens at
-//                     2 / 4 / 8 / 16 bits), loaded with one 16-byte load per lane per KiB.
-//                     K: a lane holds 128/b consecutive codes of one token; V: a lane holds the
-//                     codes of dims (2l, 2l+1) for the 64/b tokens of a tile.  Codes are never
-//                     converted: masking a word leaves two codes in the mantissa fields of an
-//                     fp16 pair (subnormal values code * 4^k * 2^-24, which v_dot2_f32_f16
-//                     keeps), the power of four is folded into pre-scaled copies of q (K) or
-//                     of the softmax weight (V), and the zero-points are factored out:
+// attn_split_kernel   one persistent workgroup per CU (8 wavefronts).  A workgroup owns an interval
+//                     of the (sequence, KV head) rows; inside a row its wavefronts draw tickets
+//                     (one "unit" each) from counters shared by the workgroups of the row.  A unit is
+//                     up to 4 KiB of K codes plus the matching 4 KiB of V codes (128 / 64 / 32 / 16
+//                     tokens at 2 / 4 / 8 / 16 bits), loaded with one 16-byte load per lane per KiB.
+//                     Codes are never converted one by one.  The zero-points are factored out,
 //                       q.k^   = sum_g scale_g * (sum_d code_d q_d) + zero_g * (sum_{d in g} q_d)
-//                       sum p v^ = sum_t (p_t scale_tg) code_td  +  sum_t p_t zero_tg.
+//                       sum p v^ = sum_t (p_t scale_tg) code_td  +  sum_t p_t zero_tg,
+//                     and the code sums run on the matrix cores:
+//                     - one query head per KV head: byte-wise masks leave one code per byte and
+//                       v_mfma_i32_16x16x64_i8 multiplies them with the base-128 digits of a
+//                       fixed-point copy of q (scores) or of the softmax weights (values);
+//                     - grouped queries: masking a word leaves two codes in the mantissa fields of an
+//                       fp16 pair (subnormal values code * 4^k * 2^-24, which the matrix core keeps)
+//                       and v_mfma_f32_16x16x32_f16 multiplies them with pre-scaled copies of q / of
+//                       the weights, all heads of the group in one product;
+//                     - raw fp16 rows (16-bit chunks, FP16 residual): v_dot2_f32_f16 / mixed FMAs.
 //                     Every workgroup writes one partial (m, l, o[D]) per row it touched.
 // attn_merge_kernel   log-sum-exp merge of the partials of one query head, normalisation.
 #include <type_traits>
@@ -43,6 +46,7 @@ template <int BITS> struct BW {
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kDescCap = 1024;                            // chunks of a row segment (descriptors held in LDS)
 constexpr int kUnitCap = 8192;                            // units of a row segment
@@ -51,8 +55,15 @@ constexpr int kMaxBatches = 64;                           // ticket batches a wo
 
 template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     static constexpr int NG = kD / G;
-    uint32_t qtab[4][REP][64];                           // q as fp16 pairs, ordered and pre-scaled per bit-width
-    float qpart[4][REP][16][2];                          // sum of q over a lane's dims (per group inside the slot)
+    uint32_t qtab[REP][64];                              // q as fp16 pairs in the order of the raw fp16 rows
+    // one query head per KV head: operands and constants of the integer matrix-core path (see iq_build_q)
+    v4i qa[REP == 1 ? 8 : 1][64];
+    v4i wa[REP == 1 ? NWV : 1][2][64];                   // per wavefront: weight digits of up to two token blocks
+    uint32_t wpos[REP == 1 ? 3 : 1][8][64];
+    uint4 kx[REP == 1 ? NWV : 1][4 * 72];                // per wavefront: the K codes of a unit on their way to the lanes that use them
+    int iq[kD];
+    float iqpart[3][8][2];
+    float iqscale[4];
     float sc[NWV][REP][128];                             // scores (log2 domain) / fp16-path weights of a unit
     static constexpr int WLS = 136;                      // weight row stride in halfs: rows fall on different banks
     uint16_t wl[NWV][REP][NG][WLS];                      // fp16 softmax weight * V scale, pre-scaled per pair
@@ -89,36 +100,6 @@ template <int BITS> __device__ __forceinline__ int pair_exp(int k) {
     return BITS * (k < BW<BITS>::KD ? k : k - BW<BITS>::KD);
 }
 
-// one 32-bit word of codes against PPW pre-scaled pairs
-template <int BITS>
-__device__ __forceinline__ float word_dot(uint32_t w, const uint32_t *pairs, float acc) {
-    using B = BW<BITS>;
-#pragma unroll
-    for (int k = 0; k < B::KD; k++) acc = dot2(w & (B::MASK << (BITS * k)), pairs[k], acc);
-    if constexpr (B::PPW > B::KD) {
-        const uint32_t w2 = w >> B::SH;
-#pragma unroll
-        for (int k = B::KD; k < B::PPW; k++) acc = dot2(w2 & (B::MASK << (BITS * (k - B::KD))), pairs[k], acc);
-    }
-    return acc;
-}
-
-// N consecutive 32-bit words from LDS with the widest reads
-template <int N>
-__device__ __forceinline__ void lds_load_words(const void *src, uint32_t (&dst)[N]) {
-    if constexpr (N == 8) {
-        const uint4 t0 = *reinterpret_cast<const uint4 *>(src), t1 = *(reinterpret_cast<const uint4 *>(src) + 1);
-        dst[0] = t0.x; dst[1] = t0.y; dst[2] = t0.z; dst[3] = t0.w; dst[4] = t1.x; dst[5] = t1.y; dst[6] = t1.z; dst[7] = t1.w;
-    } else if constexpr (N == 4) {
-        const uint4 t0 = *reinterpret_cast<const uint4 *>(src);
-        dst[0] = t0.x; dst[1] = t0.y; dst[2] = t0.z; dst[3] = t0.w;
-    } else {
-        static_assert(N == 2, "2, 4 or 8 words");
-        const uint2 t0 = *reinterpret_cast<const uint2 *>(src);
-        dst[0] = t0.x; dst[1] = t0.y;
-    }
-}
-
 // New running maximum of head r: every accumulator of the head is scaled by 2^(old - new).
 template <int G, int REP>
 __device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_max, int lane) {
@@ -147,8 +128,8 @@ __device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_ma
 // wave-uniform and live in scalar registers; lgb = log2(bit-width) (1, 2, 3; 4 = raw fp16).
 struct Unit {
     int lgb, nsub, nvalid;                               // nvalid: valid rows of an fp16 unit
-    const uint8_t *kc, *vc;
-    const uint8_t *km, *vm;
+    const uint8_t *kb, *vb;                              // bases: the chunk block (both), or the residual K and V rows of the row
+    uint32_t kc, km, vc, vm;                             // byte offsets of the unit's K codes / K meta (from kb), V codes / V meta (from vb)
 };
 
 template <int G> struct KRegs {
@@ -171,106 +152,22 @@ __device__ __forceinline__ uint32_t ld4(const uint8_t *sbase, uint32_t voff) {
     return *reinterpret_cast<const uint32_t *>(sbase + voff);
 }
 
-// Loads the K side of a unit whatever its bit-width: lane l takes the 16-byte slot 64*j + l of
-// each KiB and the meta word(s) of the (token, group) that slot belongs to.  Branch-free: a
-// short unit (nsub < 4) re-reads its last KiB and an fp16 unit reads words of its own rows in
-// place of the meta words it does not have; both are ignored by the consumer.
-template <int G>
-__device__ __forceinline__ void load_k(const Unit &u, int lane, KRegs<G> &k) {
-    constexpr int NG = kD / G;
-    constexpr int LGG = G == 64 ? 6 : 5;
-    const int lg = min(u.lgb, 3);                         // log2(lanes per token row) of the quantised layouts
-    const uint32_t tok_l = (uint32_t)lane >> lg, part = (uint32_t)lane & ((1u << lg) - 1u);
-    const uint32_t voffm = (tok_l * NG + ((part << (7 - lg)) >> LGG)) * 4u;
-    const uint32_t tile_meta = (uint32_t)((64 >> lg) * NG * 4);          // meta bytes per KiB of codes
-    const bool two = (7 - lg) > LGG;                      // slot wider than a group (2 bits, G = 32)
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-        const int jc = min(j, u.nsub - 1);
-        k.c[j] = ld16(u.kc + jc * 1024, (uint32_t)lane * 16u);
-        const uint8_t *mb = u.km + jc * tile_meta;
-        k.m[j][0] = ld4(mb, voffm);
-        if constexpr (KRegs<G>::GSMAX == 2) k.m[j][1] = ld4(mb, voffm + (two ? 4u : 0u));
-    }
-}
 // The V side: the 16-byte slots 64*j + l of the unit's V KiBs and its (token, group) meta
 // words 64*jj + l, same conventions.
 template <int G>
 __device__ __forceinline__ void load_v(const Unit &u, int lane, VRegs<G> &v) {
     constexpr int NG = kD / G;
-#pragma unroll
-    for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vc + min(j, u.nsub - 1) * 1024, (uint32_t)lane * 16u);
+    const uint32_t vv = u.vc + (uint32_t)lane * 16u, vmo = u.vm + (uint32_t)lane * 4u;
     const int nvm = u.lgb == 4 ? 1 : (u.nsub * NG) >> u.lgb;              // >= 1
+    if (u.nsub == 4) {
 #pragma unroll
-    for (int jj = 0; jj < VRegs<G>::MV; jj++) v.m[jj] = ld4(u.vm + min(jj, nvm - 1) * 256, (uint32_t)lane * 4u);
-}
-
-// ---- one unit of a quantised chunk -----------------------------------------------------------
-// Two phases so that the caller can issue its memory requests between them, in code common to all
-// bit-widths (the compiler's wait-count bookkeeping stays exact that way).
-template <int BITS, int G, int REP, int NWV>
-__device__ __forceinline__ void quant_scores(const Unit &u, const KRegs<G> &k,
-                                             int lane, int wave, float scale24,
-                                             AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
-    using B = BW<BITS>;
-    constexpr int GS = (B::E > G) ? B::E / G : 1;        // groups inside one slot
-    const int part = lane % B::SPR, tok_l = lane / B::SPR;
-    const int nsub = u.nsub;
-
-    // ---- scores, word by word (one word's worth of q pairs at a time); the q pairs of the next
-    //      word are requested from LDS before the current word is consumed, so that the LDS latency
-    //      hides behind the dot products instead of stalling the wavefront four times per unit
-    float isum[REP][4][GS];
+        for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vb + j * 1024, vv);
+    } else {
 #pragma unroll
-    for (int r = 0; r < REP; r++)
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-#pragma unroll
-            for (int gi = 0; gi < GS; gi++) isum[r][j][gi] = 0.0f;
-    {
-        uint32_t qbuf[2][B::PPW];
-        lds_load_words<B::PPW>(&L.qtab[B::BI][0][part * B::PS], qbuf[0]);
-#pragma unroll
-        for (int s = 0; s < REP * 4; s++) {
-            const int r = s / 4, wd = s % 4;
-            if (s + 1 < REP * 4)
-                lds_load_words<B::PPW>(&L.qtab[B::BI][(s + 1) / 4][part * B::PS + ((s + 1) % 4) * B::PPW], qbuf[(s + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const uint32_t w = wd == 0 ? k.c[j].x : (wd == 1 ? k.c[j].y : (wd == 2 ? k.c[j].z : k.c[j].w));
-                isum[r][j][wd / (4 / GS)] = word_dot<BITS>(w, qbuf[s & 1], isum[r][j][wd / (4 / GS)]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vb, vv + (uint32_t)min(j, u.nsub - 1) * 1024u);
     }
 #pragma unroll
-    for (int r = 0; r < REP; r++) {
-        float qp[GS];
-#pragma unroll
-        for (int gi = 0; gi < GS; gi++) qp[gi] = L.qpart[B::BI][r][part][gi];     // already times 2^-24
-        float s4[4], lmax = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            float ps = 0.0f;
-#pragma unroll
-            for (int gi = 0; gi < GS; gi++) {
-                const float sK = half_bits_to_float(k.m[j][gi] & 0xffffu);
-                const float zK = half_bits_to_float(k.m[j][gi] >> 16);
-                ps = fmaf(sK, isum[r][j][gi], ps);
-                ps = fmaf(zK, qp[gi], ps);
-            }
-            ps = group_sum<B::SPR>(ps);
-            s4[j] = (j < nsub) ? ps * scale24 : -INFINITY;            // KiB past a short unit: ignored
-            lmax = fmaxf(lmax, s4[j]);
-        }
-        rescale<G, REP>(st, r, wave_max(lmax), lane);
-        if (part == 0) {
-#pragma unroll
-            for (int j = 0; j < 4; j++) L.sc[wave][r][j * B::TT + tok_l] = s4[j];
-        }
-    }
-    wave_sync();
+    for (int jj = 0; jj < VRegs<G>::MV; jj++) v.m[jj] = ld4(u.vb, vmo + (uint32_t)min(jj, nvm - 1) * 256u);
 }
 
 // Softmax weights of a quantised unit: fp16(p * V scale / pair scale) per (head, group, token) into LDS.
@@ -302,48 +199,6 @@ __device__ __forceinline__ void value_weights(const VRegs<G> &v, int lane, int w
     wave_sync();
 }
 
-// Weighted value sum of a quantised unit on the vector ALU (one query head per KV head).
-template <int BITS, int G, int REP, int NWV>
-__device__ __forceinline__ void value_dots(const VRegs<G> &v, int lane, int wave,
-                                           AttnLds<G, REP, NWV> &L, WaveState<REP> &st) {
-    using B = BW<BITS>;
-    // V layout: KiB j of the unit, slot l = 16*qd + jj, word nw: a slice of
-    //      TQ = max(TW, 8) tokens (TW = 32/BITS per word, WD = TQ/TW words) of dim 16*ct + jj, for
-    //      CPK = 4/WD column tiles ct per KiB.  The weights of a slice are shared by the words of a
-    //      "key group" (same group of dims, same word of the slice); the next key group's weight
-    //      pairs are requested from LDS before the current one's dot products.
-    constexpr int TW = 32 / BITS, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, TB = 4 * TQ, KPB = 8 / CPK;
-    constexpr int KG = (WD == 2 || G == 32) ? 2 : 1;     // key groups per KiB
-    constexpr int NSTEP = 4 * KG * REP;
-    const int qd = lane >> 4;
-    auto ct_of = [](int j, int nw) { return (j % KPB) * CPK + nw / WD; };
-    auto word_of = [](int kg, int i) { return KG == 1 ? i : (WD == 2 ? kg + 2 * i : 2 * kg + i); };   // i-th word of key group kg
-    auto wl_addr = [&](int s_) -> const uint16_t * {
-        const int j = s_ / (KG * REP), kg = (s_ / REP) % KG, r = s_ % REP;
-        const int g = (16 * ct_of(j, word_of(kg, 0))) / G;
-        const int tb = (j / KPB) * TB + (WD == 2 ? kg * TW : 0);
-        return &L.wl[wave][r][g][tb + qd * TQ];
-    };
-    {
-        uint32_t wbuf[2][B::PPW];
-        lds_load_words<B::PPW>(wl_addr(0), wbuf[0]);
-#pragma unroll
-        for (int s = 0; s < NSTEP; s++) {
-            const int j = s / (KG * REP), kg = (s / REP) % KG, r = s % REP;
-            if (s + 1 < NSTEP) lds_load_words<B::PPW>(wl_addr(s + 1), wbuf[(s + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-            const uint32_t wv[4] = {v.c[j].x, v.c[j].y, v.c[j].z, v.c[j].w};
-#pragma unroll
-            for (int i = 0; i < 4 / KG; i++) {
-                const int nw = word_of(kg, i), ct = ct_of(j, nw);
-                st.accq[r][ct] = word_dot<BITS>(wv[nw], wbuf[s & 1], st.accq[r][ct]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    wave_sync();
-}
-
 // ---- one unit of raw fp16 rows (16-bit chunks and the FP16 residual) -----------------------
 // 16 rows: lane l holds dims 8*(l%16)..+7 of row 4*j + l/16, for K and for V alike.  Every lane of
 // a row ends up with the row's score, so the weights need no trip through LDS: the score phase
@@ -355,7 +210,7 @@ __device__ __forceinline__ void fp16_scores(const Unit &u, const KR &k, int lane
     const int nvalid = u.nvalid;                          // an fp16 unit always spans 16 rows
 #pragma unroll
     for (int r = 0; r < REP; r++) {
-        const uint4 qv = *reinterpret_cast<const uint4 *>(&L.qtab[3][r][part * 4]);
+        const uint4 qv = *reinterpret_cast<const uint4 *>(&L.qtab[r][part * 4]);
         float s4[4], lmax = -INFINITY;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
@@ -526,7 +381,7 @@ __device__ __forceinline__ void load_k_mc(const Unit &u, int lane, KRegsMC<G, RE
 #pragma unroll
     for (int i = 0; i < 8; i++) {
         const int ic = min(i, imax);
-        const uint2 t = ld8(u.kc + (((size_t)(ic >> iptsh) << tbsh) + (size_t)(ic & ((1 << iptsh) - 1)) * 8), lane_off);
+        const uint2 t = ld8(u.kb, u.kc + lane_off + (((uint32_t)(ic >> iptsh) << tbsh) + (uint32_t)(ic & ((1 << iptsh) - 1)) * 8u));
         if (i & 1) { k.c[i >> 1].z = t.x; k.c[i >> 1].w = t.y; } else { k.c[i >> 1].x = t.x; k.c[i >> 1].y = t.y; }
     }
     const int TU = raw ? 16 : (u.nsub << (6 - u.lgb));    // tokens of the unit
@@ -534,10 +389,10 @@ __device__ __forceinline__ void load_k_mc(const Unit &u, int lane, KRegsMC<G, RE
     for (int s = 0; s < M::NSMAX; s++) {
         const int t = min(16 * (s * M::F + M::sel(qd)) + x, TU - 1);
         if constexpr (M::NG == 2) {
-            const uint2 mm = ld8(u.km, (uint32_t)t * 8u);
+            const uint2 mm = ld8(u.kb, u.km + (uint32_t)t * 8u);
             k.m[2 * s] = mm.x; k.m[2 * s + 1] = mm.y;
         } else {
-            const uint4 mm = ld16(u.km, (uint32_t)t * 16u);
+            const uint4 mm = ld16(u.kb, u.km + (uint32_t)t * 16u);
             k.m[4 * s] = mm.x; k.m[4 * s + 1] = mm.y; k.m[4 * s + 2] = mm.z; k.m[4 * s + 3] = mm.w;
         }
     }
@@ -660,6 +515,359 @@ __device__ __forceinline__ void mc_value_dots(const VRegs<G> &v, int lane, int w
     wave_sync();
 }
 
+// ---- integer matrix-core path (one query head per KV head), quantised units ------------------
+// v_mfma_i32_16x16x64_i8 computes C[i][x] += sum_k A[i][k] B[k][x] on signed bytes; lane l = 16*xq + x
+// holds A[x][16xq..16xq+15], B[16xq..16xq+15][x] and C[4xq..4xq+3][x].  The codes are the B operand:
+// masking a code word byte-wise leaves one code per byte (2 bits: four planes, the code shifted left
+// by 0, 2, 4, 5 bits; 4 bits: the low and the high nibbles; 8 bits: the bytes themselves, minus 128
+// through a sign flip).  The other factor -- q for the scores, softmax weight * V scale for the values --
+// is turned into a fixed-point integer, multiplied by the power of two that undoes its plane's shift,
+// and split into four base-128 digits that sit in four rows of A; the four digit sums come back in the
+// four C registers of a lane and are recombined exactly in integer / fp32 arithmetic.
+//   scores: A is block diagonal (rows 4xq..4xq+3 are nonzero for k in quarter xq only), so that a lane's
+//           C registers hold the dot product of its OWN 16 code bytes with the digits of q: the matrix
+//           core serves as a per-lane 16-term integer dot product.  All lanes of a quarter must then hold
+//           the same dims, which fixes the lane -> slot assignment of load_k_iq.
+//   values: column x = dim of a 16-dim column tile, k = 64 tokens (quarter xq holds its slice of the token
+//           block); rows 4g..4g+3 = digits of the weights of group g, so quarter g of the lanes ends up
+//           with the sums for the column tiles whose dims lie in group g.
+__device__ __forceinline__ v4i mfma_i8(v4i a, v4i b, v4i c) {
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+// sum_n 128^n C[n] as fp32 (the two halves are exact integers below 2^31)
+__device__ __forceinline__ float iq_combine(v4i c) {
+    const int hi = c[3] * 128 + c[2], lo = c[1] * 128 + c[0];
+    return fmaf((float)hi, 16384.0f, (float)lo);
+}
+// The byte planes of a code word.  2 bits: byte y of plane p holds code 8*(y%2) + 2p + y/2 of the word,
+// shifted left by {0, 2, 4, 5}[p]; 4 bits: code 4*(y%2) + 2p + y/2; 8 bits: code 2*(y%2) + y/2, minus 128.
+template <int BITS> struct IQ {
+    static constexpr int NP = 8 / BITS;                  // planes of a word
+    static constexpr int LGM = BITS == 2 ? 6 : 0;        // log2 of the factor every product carries
+    static constexpr int BI = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
+    __device__ static __forceinline__ void planes(uint32_t w, int *m) {
+        if constexpr (BITS == 2) {
+            m[0] = (int)(w & 0x03030303u); m[1] = (int)(w & 0x0c0c0c0cu);
+            m[2] = (int)(w & 0x30303030u); m[3] = (int)((w >> 1) & 0x60606060u);
+        } else if constexpr (BITS == 4) {
+            m[0] = (int)(w & 0x0f0f0f0fu); m[1] = (int)((w >> 4) & 0x0f0f0f0fu);
+        } else {
+            m[0] = (int)(w ^ 0x80808080u);
+        }
+    }
+};
+__device__ __forceinline__ uint32_t word_of(const uint4 &c, int i) {
+    return i == 0 ? c.x : (i == 1 ? c.y : (i == 2 ? c.z : c.w));
+}
+
+// K side of a unit, one query head per KV head.  The codes are read in memory order (lane l takes the
+// 16-byte slot 64j + l of KiB j, fully coalesced); iq_regroup then hands every lane the slot the matrix
+// products want.  The meta words are read for the lane's final (token, group) directly:
+//   2 bits: register j holds token 32j + 16*(xq/2) + c, half row xq%2 (64 dims);
+//   4 bits: token 16j + c, quarter row xq (32 dims);
+//   8 bits: token 16*(j/2) + c, eighth of a row 4*(j%2) + xq (16 dims);
+// raw fp16 units keep the slot order and have no meta.
+template <int G>
+__device__ __forceinline__ void load_k_iq(const Unit &u, int lane, KRegs<G> &k) {
+    constexpr int NG = kD / G;
+    const uint32_t xq = (uint32_t)lane >> 4, c = (uint32_t)lane & 15u;
+    const uint32_t vk = u.kc + (uint32_t)lane * 16u;
+    if (u.nsub == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) k.c[j] = ld16(u.kb + j * 1024, vk);
+    } else {                                              // short unit: the last KiB is read again (ignored)
+#pragma unroll
+        for (int j = 0; j < 4; j++) k.c[j] = ld16(u.kb, vk + (uint32_t)min(j, u.nsub - 1) * 1024u);
+    }
+    if (u.lgb == 1) {
+        const uint32_t tok = 16u * (xq >> 1) + c, part = xq & 1u;
+        const uint32_t vm = u.km + (tok * NG + part * (NG / 2)) * 4u;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const uint32_t jo = (uint32_t)min(j, u.nsub - 1) * (32u * NG * 4u);
+            k.m[j][0] = ld4(u.kb, vm + jo);
+            if constexpr (NG == 4) k.m[j][1] = ld4(u.kb, vm + jo + 4u);
+        }
+    } else if (u.lgb == 2) {
+        const uint32_t vm = u.km + (c * NG + (NG == 2 ? (xq >> 1) : xq)) * 4u;
+#pragma unroll
+        for (int j = 0; j < 4; j++) k.m[j][0] = ld4(u.kb + j * 16 * NG * 4, vm);
+    } else if (u.lgb == 3) {
+        const uint32_t vm = u.km + (c * NG + (NG == 2 ? 0u : (xq >> 1))) * 4u;
+#pragma unroll
+        for (int j = 0; j < 4; j++) k.m[j][0] = ld4(u.kb + (j >> 1) * 16 * NG * 4 + (j & 1) * (NG / 2) * 4, vm);
+    }
+}
+
+// Hands every lane the code slots of its (token, part) through the wavefront's LDS buffer.  The slots
+// are stored XOR-swizzled (and every KiB 128 bytes further than the last), so that both the writes in
+// memory order and the regrouped reads touch every bank once.
+template <int BITS, int G, int NWV>
+__device__ __forceinline__ void iq_regroup(const KRegs<G> &k, int lane, int wave, AttnLds<G, 1, NWV> &L, uint4 (&kc)[4]) {
+    constexpr int KS = 72;                                // slots between two KiBs
+    uint4 *buf = &L.kx[wave][0];
+    const int xq = lane >> 4, c = lane & 15;
+    const int sw = BITS == 2 ? (lane >> 4) & 1 : (BITS == 4 ? (lane >> 4) & 3 : (lane >> 3) & 7);
+#pragma unroll
+    for (int j = 0; j < 4; j++) buf[j * KS + (lane ^ sw)] = k.c[j];
+    wave_sync();
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        int pos;
+        if constexpr (BITS == 2)      pos = j * KS + ((32 * (xq >> 1) + 2 * c + (xq & 1)) ^ (c >> 3));
+        else if constexpr (BITS == 4) pos = j * KS + 4 * c + (xq ^ (c >> 2));
+        else                          pos = (2 * (j >> 1) + (c >> 3)) * KS + 8 * (c & 7) + ((4 * (j & 1) + xq) ^ (c & 7));
+        kc[j] = buf[pos];
+    }
+    wave_sync();
+}
+
+// Scores of a quantised unit -> L.sc (log2 domain), running maximum updated.
+template <int BITS, int G, int NWV>
+__device__ __forceinline__ void iq_scores(const Unit &u, const KRegs<G> &k, int lane, int wave,
+                                          AttnLds<G, 1, NWV> &L, WaveState<1> &st) {
+    constexpr int NG = kD / G;
+    const int xq = lane >> 4, c = lane & 15;
+    const float sc = L.iqscale[IQ<BITS>::BI];
+    const v4i zero = {0, 0, 0, 0};
+    uint4 kc[4];
+    iq_regroup<BITS, G, NWV>(k, lane, wave, L, kc);
+    if constexpr (BITS == 2) {
+        constexpr int GS = NG == 4 ? 2 : 1;              // groups inside a half row
+        const int part = xq & 1;
+        v4i A[4];
+#pragma unroll
+        for (int wd = 0; wd < 4; wd++) A[wd] = L.qa[wd][lane];
+        float qp[GS];
+#pragma unroll
+        for (int gi = 0; gi < GS; gi++) qp[gi] = L.iqpart[0][part][gi];
+        float s4[4], lmax = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            v4i acc[GS];
+#pragma unroll
+            for (int gi = 0; gi < GS; gi++) acc[gi] = zero;
+#pragma unroll
+            for (int wd = 0; wd < 4; wd++) {
+                int m[4];
+                IQ<2>::planes(word_of(kc[j], wd), m);
+                acc[wd / (4 / GS)] = mfma_i8(A[wd], v4i{m[0], m[1], m[2], m[3]}, acc[wd / (4 / GS)]);
+            }
+            float ps = 0.0f;
+#pragma unroll
+            for (int gi = 0; gi < GS; gi++) {
+                ps = fmaf(half_bits_to_float(k.m[j][gi] & 0xffffu), iq_combine(acc[gi]), ps);
+                ps = fmaf(half_bits_to_float(k.m[j][gi] >> 16), qp[gi], ps);
+            }
+            ps += __shfl_xor(ps, 16);
+            s4[j] = (j < u.nsub) ? ps * sc : -INFINITY;   // KiB past a short unit: ignored
+            lmax = fmaxf(lmax, s4[j]);
+        }
+        rescale<G, 1>(st, 0, wave_max(lmax), lane);
+        if (part == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) L.sc[wave][0][32 * j + 16 * (xq >> 1) + c] = s4[j];
+        }
+    } else if constexpr (BITS == 4) {
+        const v4i A0 = L.qa[4][lane], A1 = L.qa[5][lane];
+        const float qp = L.iqpart[1][xq][0];
+        float s4[4], lmax = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            int m0[2], m1[2], m2[2], m3[2];
+            IQ<4>::planes(kc[j].x, m0); IQ<4>::planes(kc[j].y, m1);
+            IQ<4>::planes(kc[j].z, m2); IQ<4>::planes(kc[j].w, m3);
+            v4i acc = mfma_i8(A0, v4i{m0[0], m0[1], m1[0], m1[1]}, zero);
+            acc = mfma_i8(A1, v4i{m2[0], m2[1], m3[0], m3[1]}, acc);
+            float ps = half_bits_to_float(k.m[j][0] >> 16) * qp;
+            ps = fmaf(half_bits_to_float(k.m[j][0] & 0xffffu), iq_combine(acc), ps);
+            ps += __shfl_xor(ps, 16);
+            ps += __shfl_xor(ps, 32);
+            s4[j] = ps * sc;
+            lmax = fmaxf(lmax, s4[j]);
+        }
+        rescale<G, 1>(st, 0, wave_max(lmax), lane);
+        if (xq == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) L.sc[wave][0][16 * j + c] = s4[j];
+        }
+    } else {
+        const v4i A[2] = {L.qa[6][lane], L.qa[7][lane]};
+        const float qp[2] = {L.iqpart[2][xq][0], L.iqpart[2][4 + xq][0]};
+        float s2[2], lmax = -INFINITY;
+#pragma unroll
+        for (int jj = 0; jj < 2; jj++) {
+            float ps = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 2; r++) {
+                const uint4 &w = kc[2 * jj + r];
+                const v4i b = {(int)(w.x ^ 0x80808080u), (int)(w.y ^ 0x80808080u), (int)(w.z ^ 0x80808080u), (int)(w.w ^ 0x80808080u)};
+                const float isum = fmaf(128.0f, qp[r], iq_combine(mfma_i8(A[r], b, zero)));
+                const uint32_t mw = k.m[2 * jj + r][0];
+                ps = fmaf(half_bits_to_float(mw & 0xffffu), isum, ps);
+                ps = fmaf(half_bits_to_float(mw >> 16), qp[r], ps);
+            }
+            ps += __shfl_xor(ps, 16);
+            ps += __shfl_xor(ps, 32);
+            s2[jj] = ps * sc;
+            lmax = fmaxf(lmax, s2[jj]);
+        }
+        rescale<G, 1>(st, 0, wave_max(lmax), lane);
+        if (xq == 0) { L.sc[wave][0][c] = s2[0]; L.sc[wave][0][16 + c] = s2[1]; }
+    }
+    wave_sync();
+}
+
+// Softmax weights of a quantised unit as the A operand of the value products: one lane per V (token,
+// group) meta word computes p * V scale, the wavefront agrees on a common power of two, and the four
+// base-128 digits of the fixed-point weight go to the rows 4g..4g+3 of the operand image in LDS.
+// Returns the factor that turns the recombined digit sums back into weights * codes.
+template <int BITS, int G, int NWV>
+__device__ __forceinline__ float iq_weights(const VRegs<G> &v, int lane, int wave,
+                                            AttnLds<G, 1, NWV> &L, WaveState<1> &st) {
+    constexpr int NG = kD / G;
+    constexpr int MV = (256 / BITS) * NG / 64;           // meta words per lane: tokens of a unit * groups / 64
+    float wv[MV], wmax = 0.0f;
+#pragma unroll
+    for (int jj = 0; jj < MV; jj++) {
+        const int idx = 64 * jj + lane, tv = idx / NG, g = idx % NG;
+        const float sV = half_bits_to_float(v.m[jj] & 0xffffu);
+        const float zV = half_bits_to_float(v.m[jj] >> 16);
+        const float p = fast_exp2(L.sc[wave][0][tv] - st.m[0]);       // tokens past a short unit: score -inf, p = 0
+        if (g == 0) st.lsum[0] += p;
+        st.z[0] = fmaf(p, BITS == 8 ? fmaf(128.0f, sV, zV) : zV, st.z[0]);   // 8 bits: the codes enter minus 128
+        wv[jj] = p * sV;
+        wmax = fmaxf(wmax, wv[jj]);
+    }
+    wmax = wave_max(wmax);
+    // 2^ef <= wmax < 2^(ef+1) (ef >= -100): weight * 2^(20 - ef) < 2^21
+    const int ef = max((int)((__builtin_bit_cast(uint32_t, wmax) >> 23) & 255u) - 127, -100);
+    const float up = __builtin_bit_cast(float, (uint32_t)(127 + 20 - ef) << 23);
+    uint8_t *img = reinterpret_cast<uint8_t *>(&L.wa[wave][0][0]);
+#pragma unroll
+    for (int jj = 0; jj < MV; jj++) {
+        const uint32_t pos = L.wpos[IQ<BITS>::BI][jj][lane];         // byte offset of digit 0 | plane shift << 16
+        const uint32_t W = (uint32_t)(wv[jj] * up + 0.5f) << (pos >> 16);
+        uint8_t *dst = img + (pos & 0xffffu);
+        dst[0] = (uint8_t)(W & 127u); dst[16] = (uint8_t)((W >> 7) & 127u);
+        dst[32] = (uint8_t)((W >> 14) & 127u); dst[48] = (uint8_t)((W >> 21) & 127u);
+    }
+    wave_sync();
+    return __builtin_bit_cast(float, (uint32_t)(127 + ef - 20 - IQ<BITS>::LGM) << 23);
+}
+
+// Weighted value sum of a quantised unit on the integer matrix cores.
+template <int BITS, int G, int NWV>
+__device__ __forceinline__ void iq_values(const VRegs<G> &v, int lane, int wave, float cw,
+                                          AttnLds<G, 1, NWV> &L, WaveState<1> &st) {
+    const v4i zero = {0, 0, 0, 0};
+    const v4i A0 = L.wa[wave][0][lane];
+    if constexpr (BITS == 2) {                           // two blocks of 64 tokens; KiB j: block j/2, column tiles 4*(j%2)..+3
+        const v4i A1 = L.wa[wave][1][lane];
+#pragma unroll
+        for (int ct = 0; ct < 8; ct++) {
+            int m[4];
+            IQ<2>::planes(word_of(v.c[ct / 4], ct % 4), m);
+            v4i acc = mfma_i8(A0, v4i{m[0], m[1], m[2], m[3]}, zero);
+            IQ<2>::planes(word_of(v.c[2 + ct / 4], ct % 4), m);
+            acc = mfma_i8(A1, v4i{m[0], m[1], m[2], m[3]}, acc);
+            st.accq[0][ct] = fmaf(iq_combine(acc), cw, st.accq[0][ct]);
+        }
+    } else if constexpr (BITS == 4) {                    // two blocks of 32 tokens share one product
+#pragma unroll
+        for (int ct = 0; ct < 8; ct++) {
+            int ma[2], mb[2];
+            IQ<4>::planes(word_of(v.c[ct / 4], ct % 4), ma);
+            IQ<4>::planes(word_of(v.c[2 + ct / 4], ct % 4), mb);
+            const v4i acc = mfma_i8(A0, v4i{ma[0], ma[1], mb[0], mb[1]}, zero);
+            st.accq[0][ct] = fmaf(iq_combine(acc), cw, st.accq[0][ct]);
+        }
+    } else {                                             // one block of 32 tokens: half of the k range is unused
+#pragma unroll
+        for (int ct = 0; ct < 8; ct++) {
+            const uint32_t w0 = word_of(v.c[ct / 2], 2 * (ct % 2)), w1 = word_of(v.c[ct / 2], 2 * (ct % 2) + 1);
+            const v4i acc = mfma_i8(A0, v4i{(int)(w0 ^ 0x80808080u), (int)(w1 ^ 0x80808080u), 0, 0}, zero);
+            st.accq[0][ct] = fmaf(iq_combine(acc), cw, st.accq[0][ct]);
+        }
+    }
+    wave_sync();
+}
+
+// Tables of the integer path for the queries of one row (REP == 1), built by the whole workgroup
+// once L.qraw is in place:  iq[d] = q_d as a fixed-point integer below 2^21 in magnitude, qa = the
+// eight A operands of the score products (2 bits: word 0..3 of a slot; 4 bits: word pair 0, 1;
+// 8 bits: register parity 0, 1), iqpart = sum of iq over a lane's dims inside one group (times the
+// common factor of the bit-width), iqscale = softmax scale (log2 domain) / fixed-point factors.
+template <int G, int NWV>
+__device__ __forceinline__ void iq_build_q(AttnLds<G, 1, NWV> &L, int tid, int lane, float scale_log2) {
+    constexpr int NT = NWV * 64;
+    const uint32_t pr = L.qraw[lane];
+    float qm = fmaxf(fabsf(half_bits_to_float(pr & 0xffffu)), fabsf(half_bits_to_float(pr >> 16)));
+    qm = wave_max(qm);
+    const int ef = qm > 0.0f ? (int)((__builtin_bit_cast(uint32_t, qm) >> 23) & 255u) - 127 : 0;   // 2^ef <= max |q| < 2^(ef+1)
+    const float up = __builtin_bit_cast(float, (uint32_t)(127 + 20 - ef) << 23);
+    const uint16_t *qraw = reinterpret_cast<const uint16_t *>(L.qraw);
+    if (tid < kD) L.iq[tid] = (int)rintf(half_bits_to_float(qraw[tid]) * up);
+    if (tid < 3) L.iqscale[tid] = scale_log2 * __builtin_bit_cast(float, (uint32_t)(127 + ef - 20 - (tid == 0 ? 6 : 0)) << 23);
+    __syncthreads();
+    for (int i = tid; i < 8 * 64; i += NT) {
+        const int t = i >> 6, l = i & 63, xq = l >> 4, row = l & 15, n = row & 3;
+        uint32_t wds[4] = {0u, 0u, 0u, 0u};
+        if ((row >> 2) == xq) {
+#pragma unroll
+            for (int b = 0; b < 16; b++) {
+                const int m = b >> 2, y = b & 3;
+                int d, sh = 0;                            // dim of byte b, power of two that undoes the plane's shift
+                if (t < 4)      { d = (xq & 1) * 64 + t * 16 + 8 * (y & 1) + 2 * m + (y >> 1); sh = m == 3 ? 1 : 6 - 2 * m; }
+                else if (t < 6) { d = xq * 32 + (2 * (t - 4) + (m >> 1)) * 8 + 4 * (y & 1) + 2 * (m & 1) + (y >> 1); }
+                else            { d = (4 * (t - 6) + xq) * 16 + m * 4 + 2 * (y & 1) + (y >> 1); }
+                const int Q = L.iq[d];
+                const uint32_t mag = (uint32_t)(Q < 0 ? -Q : Q) << sh;
+                int dg = (int)((mag >> (7 * n)) & 127u);
+                if (Q < 0) dg = -dg;
+                wds[m] |= ((uint32_t)dg & 255u) << (8 * y);
+            }
+        }
+        L.qa[t][l] = v4i{(int)wds[0], (int)wds[1], (int)wds[2], (int)wds[3]};
+    }
+    for (int i = tid; i < 3 * 8 * 2; i += NT) {
+        const int bi = i / 16, part = (i / 2) % 8, gi = i % 2;
+        const int E = 64 >> bi;                           // codes of a slot
+        const int gs = E > G ? E / G : 1;
+        int sq = 0;
+        if (part < (2 << bi) && gi < gs) {
+            const int len = E / gs, d0 = part * E + gi * len;
+            for (int d = 0; d < len; d++) sq += L.iq[d0 + d];
+        }
+        L.iqpart[bi][part][gi] = (float)sq * (bi == 0 ? 64.0f : 1.0f);
+    }
+}
+
+// Positions of the weight digits in the operand image, per bit-width and (meta word, lane): byte
+// offset of digit 0 (digit n follows 16n bytes later) | shift that undoes the plane's << 16.
+template <int G, int NWV>
+__device__ __forceinline__ void iq_build_wpos(AttnLds<G, 1, NWV> &L, int tid) {
+    constexpr int NT = NWV * 64, NG = kD / G;
+    for (int i = tid; i < 3 * 8 * 64; i += NT) {
+        const int bi = i / 512, jj = (i / 64) % 8, l = i % 64;
+        const int idx = 64 * jj + l, tv = idx / NG, g = idx % NG;
+        uint32_t pos = 0;
+        if (tv < (128 >> bi)) {
+            int blk = 0, xq, b, sh = 0;
+            if (bi == 0)      { blk = tv >> 6; const int tb = tv & 63, e = tb & 15, p = (e & 7) >> 1;
+                                xq = tb >> 4; b = 4 * p + (e >> 3) + 2 * (e & 1); sh = p == 3 ? 1 : 6 - 2 * p; }
+            else if (bi == 1) { const int tb = tv & 31, e = tb & 7, p = (e & 3) >> 1;
+                                xq = tb >> 3; b = 8 * (tv >> 5) + 4 * p + (e >> 2) + 2 * (e & 1); }
+            else              { const int e = tv & 3;
+                                xq = tv >> 3; b = 4 * ((tv & 7) >> 2) + (e >> 1) + 2 * (e & 1); }
+            pos = (uint32_t)(blk * 1024 + (16 * xq + 4 * g) * 16 + b) | ((uint32_t)sh << 16);
+        }
+        L.wpos[bi][jj][l] = pos;
+    }
+    // rows of the image that no group writes stay zero
+    for (int i = tid; i < NWV * 2 * 64; i += NT) L.wa[i / 128][(i / 64) % 2][i % 64] = v4i{0, 0, 0, 0};
+}
+
 // ---- work distribution ----------------------------------------------------------------------
 // One persistent workgroup per CU slot.  Workgroup w of NW owns the interval
 // [w*BH/NW, (w+1)*BH/NW) of the row axis, where a fraction of a row means that fraction of the
@@ -680,16 +888,8 @@ __host__ __device__ inline int wg_last_of_row(int r, int NW, int BH) {
 }
 int attn_max_partials(int NW, int BH) { return NW / BH + 2; }
 
-// Relative cost of one chunk at a bit-width: kernel time per chunk measured on caches of one
-// bit-width (2-bit chunks are bound by instruction issue, 16-bit ones by bytes).
 // Chunks per row segment: at most kDescCap, and at most kUnitCap units if all of them were FP16.
 __host__ __device__ inline int attn_segment_chunks(int N) { return min(kDescCap, kUnitCap / (N / 16)); }
-
-template <int REP>
-__device__ __forceinline__ uint32_t chunk_cost(int bits) {
-    if constexpr (REP == 1) return bits == 2 ? 215u : (bits == 4 ? 330u : (bits == 8 ? 600u : 1090u));
-    else                    return bits == 2 ? 215u : (bits == 4 ? 333u : (bits == 8 ? 587u : 1391u));
-}
 
 template <int G, int REP, int NWV>
 __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
@@ -709,6 +909,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
         return b;
     };
 
+    if constexpr (REP == 1) iq_build_wpos<G, NWV>(L, tid);  // made visible by the barriers of the row set-up
     int r0, f0, r1, f1;
     wg_interval(w, NW, a.BH, r0, f0, r1, f1);
     const int seg_chunks = attn_segment_chunks(N);
@@ -732,31 +933,11 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             __syncthreads();
 
             const uint16_t *qraw = reinterpret_cast<const uint16_t *>(L.qraw);
-            for (int i = tid; i < 4 * REP * 64; i += NT) {
-                const int bi = i / (REP * 64), r = (i / 64) % REP, ent = i % 64;
-                const int BITSv = 2 << bi;
-                const int ps = 64 / BITSv, ppw = bi == 3 ? 1 : 16 / BITSv, kd = bi == 0 ? 5 : (bi == 1 ? 2 : 1);
-                const int part = ent / ps, ii = ent % ps, j = ii / ppw, k = ii % ppw;
-                const int d0 = part * (128 / BITSv) + j * 2 * ppw + 2 * k;
-                const int kp = bi == 3 ? 0 : BITSv * (k < kd ? k : k - kd);
-                const float f = __builtin_bit_cast(float, (uint32_t)(127 - kp) << 23);
-                const uint32_t lo16 = float_to_half_bits(half_bits_to_float(qraw[r * kD + d0]) * f);
-                const uint32_t hi16 = float_to_half_bits(half_bits_to_float(qraw[r * kD + d0 + 1]) * f);
-                L.qtab[bi][r][ent] = lo16 | (hi16 << 16);
+            for (int i = tid; i < REP * 64; i += NT) {   // raw fp16 rows: lane part = l%16 holds dims 8*part..+7
+                const int r = i / 64, ent = i % 64;
+                L.qtab[r][ent] = L.qraw[r * 64 + ent];
             }
-            for (int i = tid; i < 4 * REP * 16 * 2; i += NT) {
-                const int bi = i / (REP * 32), r = (i / 32) % REP, part = (i / 2) % 16, gi = i % 2;
-                const int BITSv = 2 << bi, E = 128 / BITSv;
-                float sq = 0.0f;
-                if (part < BITSv) {
-                    const int gs = E > G ? E / G : 1;
-                    if (gi < gs) {
-                        const int len = E / gs, d0 = part * E + gi * len;
-                        for (int d = 0; d < len; d++) sq += half_bits_to_float(qraw[r * kD + d0 + d]);
-                    }
-                }
-                L.qpart[bi][r][part][gi] = bi == 3 ? sq : sq * kTwoM24;   // quantised paths work in units of 2^-24
-            }
+            if constexpr (REP == 1) iq_build_q<G, NWV>(L, tid, lane, a.scale_log2);
             if constexpr (REP > 1) {
                 for (int i = tid; i < REP * NG; i += NT) {
                     float sq = 0.0f;
@@ -910,23 +1091,24 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     const int t0 = sidx << (8 - lgb);
                     un.lgb = lgb;
                     un.nsub = min(4, (N - t0) >> (6 - lgb)); un.nvalid = un.nsub << (6 - lgb);
+                    un.kb = blk; un.vb = blk;
                     if (lgb == 4) {
-                        un.kc = blk + ((size_t)t0 << 8); un.vc = un.kc + ((size_t)N << 8);
+                        un.kc = (uint32_t)t0 << 8; un.vc = un.kc + ((uint32_t)N << 8);
                         un.km = un.kc; un.vm = un.kc;    // no meta: see load_k
                     } else {
-                        const size_t cb = (size_t)N << (4 + lgb), mb = (size_t)N * NG * 4;
-                        un.kc = blk + ((size_t)t0 << (4 + lgb));
-                        un.km = blk + cb + (size_t)t0 * NG * 4;
+                        const uint32_t cb = (uint32_t)N << (4 + lgb), mb = (uint32_t)N * NG * 4;
+                        un.kc = (uint32_t)t0 << (4 + lgb);
+                        un.km = cb + (uint32_t)t0 * NG * 4;
                         un.vc = un.kc + cb + mb;
                         un.vm = un.km + cb + mb;
                     }
                 } else {                                 // 16 rows of the FP16 residual
                     const int row0 = (int)(tk - n_chunk_units) * 16;
-                    const size_t rowb = ((size_t)u * N + (size_t)row0) * 256;
                     un.lgb = 4; un.nsub = 4; un.nvalid = min(16, a.n_tail - row0);
-                    un.kc = reinterpret_cast<const uint8_t *>(a.K_tail) + rowb;
-                    un.vc = reinterpret_cast<const uint8_t *>(a.V_tail) + rowb;
-                    un.km = un.kc; un.vm = un.kc;
+                    un.kb = reinterpret_cast<const uint8_t *>(a.K_tail) + (size_t)u * N * 256;
+                    un.vb = reinterpret_cast<const uint8_t *>(a.V_tail) + (size_t)u * N * 256;
+                    un.kc = un.vc = (uint32_t)row0 * 256u;
+                    un.km = un.kc; un.vm = un.vc;
                 }
                 return true;
             };
@@ -939,7 +1121,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             VRegs<G> va, vb;
             bool have = next_unit(cur);
             auto load_keys = [&](const Unit &un) {
-                if constexpr (REP == 1) load_k<G>(un, lane, kr); else load_k_mc<G, REP>(un, lane, kr);
+                if constexpr (REP == 1) load_k_iq<G>(un, lane, kr); else load_k_mc<G, REP>(un, lane, kr);
             };
             if (have) { load_keys(cur); load_v<G>(cur, lane, va); }
             const float scale24 = a.scale_log2 * kTwo24;
@@ -956,26 +1138,24 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 }
                 load_v<G>(pf, lane, vn);                  // a whole unit ahead
                 if constexpr (REP == 1) {
-                    if (lgb == 1)      quant_scores<2, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
-                    else if (lgb == 2) quant_scores<4, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
-                    else if (lgb == 3) quant_scores<8, G, REP, NWV>(cur, kr, lane, wave, scale24, L, st);
+                    if (lgb == 1)      iq_scores<2, G, NWV>(cur, kr, lane, wave, L, st);
+                    else if (lgb == 2) iq_scores<4, G, NWV>(cur, kr, lane, wave, L, st);
+                    else if (lgb == 3) iq_scores<8, G, NWV>(cur, kr, lane, wave, L, st);
                     else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
+                    load_keys(pf);                        // half a unit ahead
+                    if (lgb == 1)      iq_values<2, G, NWV>(vc, lane, wave, iq_weights<2, G, NWV>(vc, lane, wave, L, st), L, st);
+                    else if (lgb == 2) iq_values<4, G, NWV>(vc, lane, wave, iq_weights<4, G, NWV>(vc, lane, wave, L, st), L, st);
+                    else if (lgb == 3) iq_values<8, G, NWV>(vc, lane, wave, iq_weights<8, G, NWV>(vc, lane, wave, L, st), L, st);
+                    else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
                 } else {
                     if (lgb == 1)      mc_scores<2, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
                     else if (lgb == 2) mc_scores<4, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
                     else if (lgb == 3) mc_scores<8, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
                     else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
-                }
-                load_keys(pf);                            // half a unit ahead
-                if (lgb == 1)      value_weights<2, G, REP, NWV>(vc, lane, wave, L, st);
-                else if (lgb == 2) value_weights<4, G, REP, NWV>(vc, lane, wave, L, st);
-                else if (lgb == 3) value_weights<8, G, REP, NWV>(vc, lane, wave, L, st);
-                if constexpr (REP == 1) {
-                    if (lgb == 1)      value_dots<2, G, REP, NWV>(vc, lane, wave, L, st);
-                    else if (lgb == 2) value_dots<4, G, REP, NWV>(vc, lane, wave, L, st);
-                    else if (lgb == 3) value_dots<8, G, REP, NWV>(vc, lane, wave, L, st);
-                    else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
-                } else {
+                    load_keys(pf);                        // half a unit ahead
+                    if (lgb == 1)      value_weights<2, G, REP, NWV>(vc, lane, wave, L, st);
+                    else if (lgb == 2) value_weights<4, G, REP, NWV>(vc, lane, wave, L, st);
+                    else if (lgb == 3) value_weights<8, G, REP, NWV>(vc, lane, wave, L, st);
                     if (lgb == 1)      mc_value_dots<2, G, REP, NWV>(vc, lane, wave, L, st);
                     else if (lgb == 2) mc_value_dots<4, G, REP, NWV>(vc, lane, wave, L, st);
                     else if (lgb == 3) mc_value_dots<8, G, REP, NWV>(vc, lane, wave, L, st);
@@ -1006,12 +1186,8 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             if constexpr (REP == 1) {
                 wave_sync();
 #pragma unroll
-                for (int ct = 0; ct < 8; ct++) {          // fold the four token slices of every column tile
-                    float t = st.accq[r][ct];
-                    t += __shfl_xor(t, 16);
-                    t += __shfl_xor(t, 32);
-                    if (lane < 16) dst[16 * ct + lane] = fmaf(t, kTwo24, dst[16 * ct + lane]);
-                }
+                for (int ct = 0; ct < 8; ct++)            // column tile ct: the lane quarter of its group holds the sums
+                    if ((lane >> 4) == (16 * ct) / G) dst[16 * ct + (lane & 15)] += st.accq[r][ct];
             }
         }
         if constexpr (REP > 1) {                          // matrix-core tiles: row = head * NG + group, column = dim

@@ -205,6 +205,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(PackArgs a) {
     }
 }
 
+// The packed cache is written once and read much later by another kernel: streaming stores keep it
+// from displacing (and later being written back from under) what the caches hold.
+template <typename T> __device__ __forceinline__ void nt_store(T *p, T v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void nt_store(uint4 *p, uint4 v) {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(u4{v.x, v.y, v.z, v.w}, reinterpret_cast<u4 *>(p));
+}
+__device__ __forceinline__ void nt_store(uint2 *p, uint2 v) {
+    typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+    __builtin_nontemporal_store(u2{v.x, v.y}, reinterpret_cast<u2 *>(p));
+}
+
+__device__ __forceinline__ uint4 nt_load(const uint4 *p) {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    const u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(p));
+    return uint4{v[0], v[1], v[2], v[3]};
+}
+
 constexpr int kPackThreads = 256;
 constexpr int kVRow = kD + 4;                        // bytes per token row of the V staging buffer
 
@@ -232,7 +250,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     if (bits == 16) {                                 // FP16 expert: rows copied verbatim
         uint4 *dst = reinterpret_cast<uint4 *>(blk + (isV ? (size_t)N * kD * 2 : 0));
         for (int row = rsub; row < N; row += kPackThreads / 16)
-            dst[row * 16 + lane16] = *reinterpret_cast<const uint4 *>(src + (int64_t)row * a.stride_s + lane16 * 8);
+            nt_store(&dst[row * 16 + lane16], nt_load(reinterpret_cast<const uint4 *>(src + (int64_t)row * a.stride_s + lane16 * 8)));
         return;
     }
 
@@ -245,7 +263,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     const float qmax = (float)((1 << bits) - 1);
 
     for (int row = rsub; row < N; row += kPackThreads / 16) {
-        const uint4 xv = *reinterpret_cast<const uint4 *>(src + (int64_t)row * a.stride_s + lane16 * 8);
+        const uint4 xv = nt_load(reinterpret_cast<const uint4 *>(src + (int64_t)row * a.stride_s + lane16 * 8));
         const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
         float x[8];
 #pragma unroll
@@ -270,7 +288,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
             t = fminf(fmaxf(t, 0.0f), qmax);
             code[e] = (uint32_t)t;
         }
-        if ((lane16 % LPG) == 0) meta_w[row * NG + lane16 / LPG] = s16 | (float_to_half_bits(mn) << 16);
+        if ((lane16 % LPG) == 0) nt_store(&meta_w[row * NG + lane16 / LPG], s16 | (float_to_half_bits(mn) << 16));
 
         if (isV) {
             uint32_t *dstv = reinterpret_cast<uint32_t *>(vcodes + row * kVRow + lane16 * 8);
@@ -282,17 +300,17 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
             for (int e = 0; e < 8; e++) w |= code[e] << code_shift(e, 2);
             if (lane16 & 1) w <<= 8;                  // in-word indices 8..15
             w |= dpp_u<DPP_XOR1>(w);
-            if (!(lane16 & 1)) codes_w[row * 8 + (lane16 >> 1)] = w;
+            if (!(lane16 & 1)) nt_store(&codes_w[row * 8 + (lane16 >> 1)], w);
         } else if (bits == 4) {                       // 8 dims per word: one lane per word
             uint32_t w = 0;
 #pragma unroll
             for (int e = 0; e < 8; e++) w |= code[e] << code_shift(e, 4);
-            codes_w[row * 16 + lane16] = w;
+            nt_store(&codes_w[row * 16 + lane16], w);
         } else {                                      // 8 bits, 4 dims per word: two words per lane
             uint2 w;
             w.x = code[0] | code[2] << 8 | code[1] << 16 | code[3] << 24;
             w.y = code[4] | code[6] << 8 | code[5] << 16 | code[7] << 24;
-            *reinterpret_cast<uint2 *>(codes_w + row * 32 + lane16 * 2) = w;
+            nt_store(reinterpret_cast<uint2 *>(codes_w + row * 32 + lane16 * 2), w);
         }
     }
     if (!isV) return;
@@ -314,7 +332,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
             w0 |= (v4 & 0xffu) << sh; w1 |= ((v4 >> 8) & 0xffu) << sh; w2 |= ((v4 >> 16) & 0xffu) << sh; w3 |= (v4 >> 24) << sh;
         }
         uint32_t *dst = codes_w + (kib * 64 + 16 * qd + 4 * jq) * 4 + n;     // slot 16*qd + 4*jq + k, word n
-        dst[0] = w0; dst[4] = w1; dst[8] = w2; dst[12] = w3;
+        nt_store(dst, w0); nt_store(dst + 4, w1); nt_store(dst + 8, w2); nt_store(dst + 12, w3);
     }
 }
 
