@@ -62,6 +62,7 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     uint32_t wpos[REP == 1 ? 3 : 1][8][64];
     uint4 kx[REP == 1 ? NWV : 1][4 * 72];                // per wavefront: the K codes of a unit on their way to the lanes that use them
     int iq[kD];
+    int iqs16[8];
     float iqpart[3][8][2];
     float iqscale[4];
     float sc[NWV][REP][128];                             // scores (log2 domain) / fp16-path weights of a unit
@@ -807,37 +808,42 @@ __device__ __forceinline__ void iq_build_q(AttnLds<G, 1, NWV> &L, int tid, int l
     const int ef = qm > 0.0f ? (int)((__builtin_bit_cast(uint32_t, qm) >> 23) & 255u) - 127 : 0;   // 2^ef <= max |q| < 2^(ef+1)
     const float up = __builtin_bit_cast(float, (uint32_t)(127 + 20 - ef) << 23);
     const uint16_t *qraw = reinterpret_cast<const uint16_t *>(L.qraw);
-    if (tid < kD) L.iq[tid] = (int)rintf(half_bits_to_float(qraw[tid]) * up);
     if (tid < 3) L.iqscale[tid] = scale_log2 * __builtin_bit_cast(float, (uint32_t)(127 + ef - 20 - (tid == 0 ? 6 : 0)) << 23);
-    __syncthreads();
-    for (int i = tid; i < 8 * 64; i += NT) {
-        const int t = i >> 6, l = i & 63, xq = l >> 4, row = l & 15, n = row & 3;
-        uint32_t wds[4] = {0u, 0u, 0u, 0u};
-        if ((row >> 2) == xq) {
-#pragma unroll
-            for (int b = 0; b < 16; b++) {
-                const int m = b >> 2, y = b & 3;
-                int d, sh = 0;                            // dim of byte b, power of two that undoes the plane's shift
-                if (t < 4)      { d = (xq & 1) * 64 + t * 16 + 8 * (y & 1) + 2 * m + (y >> 1); sh = m == 3 ? 1 : 6 - 2 * m; }
-                else if (t < 6) { d = xq * 32 + (2 * (t - 4) + (m >> 1)) * 8 + 4 * (y & 1) + 2 * (m & 1) + (y >> 1); }
-                else            { d = (4 * (t - 6) + xq) * 16 + m * 4 + 2 * (y & 1) + (y >> 1); }
-                const int Q = L.iq[d];
-                const uint32_t mag = (uint32_t)(Q < 0 ? -Q : Q) << sh;
-                int dg = (int)((mag >> (7 * n)) & 127u);
-                if (Q < 0) dg = -dg;
-                wds[m] |= ((uint32_t)dg & 255u) << (8 * y);
-            }
-        }
-        L.qa[t][l] = v4i{(int)wds[0], (int)wds[1], (int)wds[2], (int)wds[3]};
+    int s16 = 0;                                          // sums of iq over blocks of 16 dims (wavefronts 0 and 1)
+    if (tid < kD) {
+        s16 = L.iq[tid] = (int)rintf(half_bits_to_float(qraw[tid]) * up);
+        s16 += (int)dpp_u<DPP_XOR1>((uint32_t)s16); s16 += (int)dpp_u<DPP_XOR2>((uint32_t)s16);
+        s16 += (int)dpp_u<DPP_HALF_MIRROR>((uint32_t)s16); s16 += (int)dpp_u<DPP_MIRROR>((uint32_t)s16);
+        if ((tid & 15) == 0) L.iqs16[tid >> 4] = s16;
     }
-    for (int i = tid; i < 3 * 8 * 2; i += NT) {
-        const int bi = i / 16, part = (i / 2) % 8, gi = i % 2;
+    __syncthreads();
+    // the 16 lanes 20*xq + n of every operand are nonzero (the rest was zeroed once): one word per thread
+    static_assert(NT == 512, "one operand word per thread");
+    {
+        const int t = tid >> 6, xq = (tid >> 4) & 3, n = (tid >> 2) & 3, m = tid & 3;
+        uint32_t wd = 0u;
+#pragma unroll
+        for (int y = 0; y < 4; y++) {
+            int d, sh = 0;                                // dim of byte 4m + y, power of two that undoes the plane's shift
+            if (t < 4)      { d = (xq & 1) * 64 + t * 16 + 8 * (y & 1) + 2 * m + (y >> 1); sh = m == 3 ? 1 : 6 - 2 * m; }
+            else if (t < 6) { d = xq * 32 + (2 * (t - 4) + (m >> 1)) * 8 + 4 * (y & 1) + 2 * (m & 1) + (y >> 1); }
+            else            { d = (4 * (t - 6) + xq) * 16 + m * 4 + 2 * (y & 1) + (y >> 1); }
+            const int Q = L.iq[d];
+            const uint32_t mag = (uint32_t)(Q < 0 ? -Q : Q) << sh;
+            int dg = (int)((mag >> (7 * n)) & 127u);
+            if (Q < 0) dg = -dg;
+            wd |= ((uint32_t)dg & 255u) << (8 * y);
+        }
+        reinterpret_cast<uint32_t *>(&L.qa[t][20 * xq + n])[m] = wd;
+    }
+    if (tid < 3 * 8 * 2) {
+        const int bi = tid / 16, part = (tid / 2) % 8, gi = tid % 2;
         const int E = 64 >> bi;                           // codes of a slot
         const int gs = E > G ? E / G : 1;
         int sq = 0;
         if (part < (2 << bi) && gi < gs) {
-            const int len = E / gs, d0 = part * E + gi * len;
-            for (int d = 0; d < len; d++) sq += L.iq[d0 + d];
+            const int nb = E / gs / 16, b0 = (part * E + gi * (E / gs)) / 16;
+            for (int k = 0; k < nb; k++) sq += L.iqs16[b0 + k];
         }
         L.iqpart[bi][part][gi] = (float)sq * (bi == 0 ? 64.0f : 1.0f);
     }
@@ -864,7 +870,8 @@ __device__ __forceinline__ void iq_build_wpos(AttnLds<G, 1, NWV> &L, int tid) {
         }
         L.wpos[bi][jj][l] = pos;
     }
-    // rows of the image that no group writes stay zero
+    // operand lanes / rows of the image that nobody writes stay zero
+    for (int i = tid; i < 8 * 64; i += NT) L.qa[i / 64][i % 64] = v4i{0, 0, 0, 0};
     for (int i = tid; i < NWV * 2 * 64; i += NT) L.wa[i / 128][(i / 64) % 2][i % 64] = v4i{0, 0, 0, 0};
 }
 
@@ -924,19 +931,31 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
         const uint32_t P = (uint32_t)(wg_last_of_row(u, NW, a.BH) - wg_first_of_row(u, NW, a.BH) + 1);
         const long long ov = min((long long)(w + 1) * a.BH, (long long)(u + 1) * NW) - max((long long)w * a.BH, (long long)u * NW);
 
-        // ---- (a) row set-up: raw q and the descriptors of the first segment in one round trip, q tables
+        // ---- (a) row set-up.  One round trip to memory for everything the first units need: the raw
+        //      queries, the chunk descriptors of the first segment and the first batch of tickets.  The
+        //      tables derived from q are built later, while the first units' codes are on their way.
+        const int KPT = (seg_chunks + NT - 1) / NT;      // chunks per thread of a segment (<= 2)
+        uint32_t q_first = 0u, g_first = 0u;
+        uint8_t e_first[2] = {0, 0};
+        uint64_t o_first[2] = {0ull, 0ull};
         {
+            static_assert(REP * 64 <= NT, "one query word per thread");
             const int bq = u / a.Hkv, hq0 = (u % a.Hkv) * REP;
             const uint32_t *qrow32 = reinterpret_cast<const uint32_t *>(a.q + ((int64_t)bq * a.Hkv * REP + hq0) * kD);
-            __syncthreads();                             // LDS of the previous row is free
-            for (int i = tid; i < REP * 64; i += NT) L.qraw[i] = qrow32[i];
-            __syncthreads();
-
-            const uint16_t *qraw = reinterpret_cast<const uint16_t *>(L.qraw);
-            for (int i = tid; i < REP * 64; i += NT) {   // raw fp16 rows: lane part = l%16 holds dims 8*part..+7
-                const int r = i / 64, ent = i % 64;
-                L.qtab[r][ent] = L.qraw[r * 64 + ent];
+            if (tid < REP * 64) q_first = qrow32[tid];
+#pragma unroll
+            for (int k = 0; k < 2; k++) {
+                const int c = tid * KPT + k;
+                if (k < KPT && c < min(C, seg_chunks)) { e_first[k] = erow[c]; o_first[k] = orow[c]; }
             }
+            if (tid == 0) g_first = atomicAdd(a.counters + (size_t)u * n_seg * kCounterStride, (unsigned int)NWV);
+            __syncthreads();                             // LDS of the previous row is free
+            if (tid < REP * 64) L.qraw[tid] = q_first;
+        }
+        constexpr bool kLateTables = REP == 1;           // grouped queries: the builders would not fit beside the loads in flight
+        auto build_q_tables = [&]() {                    // by the whole workgroup; L.qraw is in place
+            const uint16_t *qraw = reinterpret_cast<const uint16_t *>(L.qraw);
+            if (tid < REP * 64) L.qtab[tid / 64][tid % 64] = L.qraw[tid];   // raw fp16 rows: lane part = l%16 holds dims 8*part..+7
             if constexpr (REP == 1) iq_build_q<G, NWV>(L, tid, lane, a.scale_log2);
             if constexpr (REP > 1) {
                 for (int i = tid; i < REP * NG; i += NT) {
@@ -947,7 +966,9 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 for (int i = tid; i < AttnLds<G, REP, NWV>::WLS; i += NT) L.zrow[i] = 0;
                 if (wave < 4) mc_build_q<G, REP>(L.qraw, lane, wave, L);
             }
-        }
+            __syncthreads();
+        };
+        if constexpr (!kLateTables) { __syncthreads(); build_q_tables(); }
 
         WaveState<REP> st;
 #pragma unroll
@@ -971,15 +992,14 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             const int cs = seg * seg_chunks, ce = min(C, cs + seg_chunks);
             if (seg > 0) __syncthreads();                // previous segment's tables consumed
             // chunks [cs + tid*KPT, +KPT) per thread: descriptor, units per chunk, exclusive scan
-            const int KPT = (seg_chunks + NT - 1) / NT;  // <= 2
             uint32_t ucnt[2] = {0u, 0u}, mine = 0u;
 #pragma unroll
             for (int k = 0; k < 2; k++) {
                 const int c = cs + tid * KPT + k;
                 if (k < KPT && c < ce) {
-                    const int bits = bits_of(erow[c]);
+                    const int bits = bits_of(seg == 0 ? e_first[k] : erow[c]);
                     const int lgb = bits == 2 ? 1 : (bits == 4 ? 2 : (bits == 8 ? 3 : 4));
-                    L.desc[c - cs] = orow[c] | (unsigned long long)lgb;      // block offsets are multiples of 256
+                    L.desc[c - cs] = (seg == 0 ? o_first[k] : orow[c]) | (unsigned long long)lgb;   // block offsets are multiples of 256
                     ucnt[k] = (uint32_t)((N + (256 >> lgb) - 1) >> (8 - lgb));
                     mine += ucnt[k];
                 }
@@ -996,6 +1016,16 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             uint32_t pos = incl - mine, n_chunk_units = 0;
 #pragma unroll
             for (int wv = 0; wv < NWV; wv++) { if (wv < wave) pos += L.wscan[wv]; n_chunk_units += L.wscan[wv]; }
+            const uint32_t T = n_chunk_units + (uint32_t)(seg == n_seg - 1 ? (a.n_tail + 15) / 16 : 0);
+            unsigned int *counter = a.counters + ((size_t)u * n_seg + seg) * kCounterStride;
+            // no cap for a workgroup whose whole interval lies in this row, or that covers the whole row
+            const uint32_t quota = ov >= min(NW, a.BH) ? 0xffffffffu : (uint32_t)(((unsigned long long)T * (unsigned long long)ov + NW - 1) / NW);
+            if (seg == 0 && tid == 0) {                  // the batch asked for during the row set-up
+                const uint32_t granted = g_first < T ? min((uint32_t)NWV, T - g_first) : 0u;
+                L.g_seen = g_first + (uint32_t)NWV;
+                if (granted) { L.bl[0] = 0u; L.bg[0] = g_first; L.nb = 1u; L.limit = granted; }
+                if (g_first + (uint32_t)NWV >= T || granted >= quota) L.done = 1u;
+            }
 #pragma unroll
             for (int k = 0; k < 2; k++) {
                 const int c = cs + tid * KPT + k;
@@ -1006,17 +1036,6 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 }
             }
             __syncthreads();
-            if constexpr (REP > 1) {
-                if (seg == 0) {
-                    const int slot0 = MC<G, REP>::slot0(lane >> 4);
-#pragma unroll
-                    for (int n = 0; n < 4; n++) qp[n] = L.qsumg[(slot0 + n) / NG][(slot0 + n) % NG];
-                }
-            }
-            const uint32_t T = n_chunk_units + (uint32_t)(seg == n_seg - 1 ? (a.n_tail + 15) / 16 : 0);
-            unsigned int *counter = a.counters + ((size_t)u * n_seg + seg) * kCounterStride;
-            // no cap for a workgroup whose whole interval lies in this row, or that covers the whole row
-            const uint32_t quota = ov >= min(NW, a.BH) ? 0xffffffffu : (uint32_t)(((unsigned long long)T * (unsigned long long)ov + NW - 1) / NW);
 
             // One wavefront at a time asks the row's counter for the next batch.
             auto fetch = [&]() {
@@ -1124,6 +1143,14 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 if constexpr (REP == 1) load_k_iq<G>(un, lane, kr); else load_k_mc<G, REP>(un, lane, kr);
             };
             if (have) { load_keys(cur); load_v<G>(cur, lane, va); }
+            if (seg == 0) {                              // the q tables, behind the first units' loads
+                if constexpr (kLateTables) build_q_tables();
+                if constexpr (REP > 1) {
+                    const int slot0 = MC<G, REP>::slot0(lane >> 4);
+#pragma unroll
+                    for (int n = 0; n < 4; n++) qp[n] = L.qsumg[(slot0 + n) / NG][(slot0 + n) % NG];
+                }
+            }
             const float scale24 = a.scale_log2 * kTwo24;
             auto step = [&](const VRegs<G> &vc, VRegs<G> &vn) {
                 const bool have_next = next_unit(nxt);
