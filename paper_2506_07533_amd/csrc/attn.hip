@@ -3,8 +3,9 @@
 // paper: the quantised keys are de-quantised before they meet the query; softmax needs high
 // precision).
 //
+// attn_prep_kernel    zeroes the ticket counters and counts the units of every (sequence, KV head) row.
 // attn_split_kernel   one persistent workgroup per CU (8 wavefronts).  A workgroup owns an interval
-//                     of the (sequence, KV head) rows; inside a row its wavefronts draw tickets
+//                     of the rows, balanced by units; inside a row its wavefronts draw tickets
 //                     (one "unit" each) from counters shared by the workgroups of the row.  A unit is
 //                     up to 4 KiB of K codes plus the matching 4 KiB of V codes (128 / 64 / 32 / 16
 //                     tokens at 2 / 4 / 8 / 16 bits), loaded with one 16-byte load per lane per KiB.
@@ -51,6 +52,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kDescCap = 1024;                            // chunks of a row segment (descriptors held in LDS)
 constexpr int kUnitCap = 8192;                            // units of a row segment
 constexpr int kCounterStride = 64;                        // uint32 slots between two ticket counters (256 bytes)
+constexpr int kMaxWeightedRowsLds = 1024;                // == kMaxWeightedRows
 constexpr int kMaxBatches = 64;                           // ticket batches a workgroup can be granted per row segment
 
 template <int G, int REP, int NWV> struct alignas(16) AttnLds {
@@ -79,6 +81,7 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     uint16_t ustart[kDescCap];                           // first unit of every chunk of the segment
     uint16_t inv[kUnitCap];                              // unit -> chunk of the segment
     uint32_t wscan[NWV];
+    uint32_t U[kMaxWeightedRowsLds + 1], r0;            // prefix sums of the rows' units
     uint32_t next, limit, done, fetching, g_seen, nb;
     uint32_t bl[kMaxBatches], bg[kMaxBatches];
 };
@@ -876,24 +879,37 @@ __device__ __forceinline__ void iq_build_wpos(AttnLds<G, 1, NWV> &L, int tid) {
 }
 
 // ---- work distribution ----------------------------------------------------------------------
-// One persistent workgroup per CU slot.  Workgroup w of NW owns the interval
-// [w*BH/NW, (w+1)*BH/NW) of the row axis, where a fraction of a row means that fraction of the
-// row's estimated cost (so a workgroup covers part of a row, or several rows).  Inside a row
-// segment the workgroup's wavefronts draw tickets (up to 128 tokens of one chunk, or 128 rows of
-// the FP16 residual) from a counter in LDS: a wavefront that runs faster -- the SIMD arbiter
-// favours the oldest ones -- just takes more tickets, and all of them finish the segment
-// together.  The workgroup then folds its wavefronts' softmax states into ONE partial per row.
-__host__ __device__ inline void wg_interval(int w, int NW, int BH, int &r0, int &f0, int &r1, int &f1) {
-    const long long a0 = (long long)w * BH, a1 = (long long)(w + 1) * BH;
-    r0 = (int)(a0 / NW); f0 = (int)(a0 % NW); r1 = (int)(a1 / NW); f1 = (int)(a1 % NW);
+// One persistent workgroup per CU slot.  The rows are laid end to end on an axis measured in bytes to
+// read (row u covers [U[u], U[u+1]): the cost of its units, added up by attn_prep_kernel from the routing
+// decisions), and workgroup w of NW owns the interval [w*Utot/NW, (w+1)*Utot/NW): part of a row, or
+// several rows, always the same amount of work whatever the rows' mixes of bit-widths.  With more than
+// kMaxWeightedRows rows every row counts the same (U[u] = u * NW) and many rows average out.
+// Inside a row segment the workgroup's wavefronts draw tickets (one unit each) from counters shared by
+// the workgroups of the row: a wavefront or workgroup that runs faster just takes more tickets, and
+// all of them finish the row together.  The workgroup then folds its wavefronts' softmax states into
+// ONE partial per row; partial slot of workgroup w in row u = w - (first workgroup that touches u).
+constexpr int kMaxWeightedRows = 1024;
+// Workgroups whose intervals meet row [ub, ue) (ue > ub): lo_w = floor(w*Utot/NW) < ue and lo_{w+1} > ub.
+__device__ inline int wg_first_of_row(unsigned long long ub, unsigned long long Utot, int NW) {
+    return (int)(((ub + 1) * (unsigned long long)NW + Utot - 1) / Utot) - 1;
 }
-// Workgroups that touch row r: first = the one containing the row's start, last = the one
-// containing its end; partial slot of workgroup w in row r = w - first.
-__host__ __device__ inline int wg_first_of_row(int r, int NW, int BH) { return (int)(((long long)r * NW) / BH); }
-__host__ __device__ inline int wg_last_of_row(int r, int NW, int BH) {
-    return (int)((((long long)(r + 1) * NW) + BH - 1) / BH) - 1;
+__device__ inline int wg_last_of_row(unsigned long long ue, unsigned long long Utot, int NW) {
+    return (int)((ue * (unsigned long long)NW + Utot - 1) / Utot) - 1;
 }
-int attn_max_partials(int NW, int BH) { return NW / BH + 2; }
+// Partial slots per row.  A row's units are at most 8 times another's (16 against 2 bits), so a row
+// holds at most 8/(BH+7) of all units and meets at most NW times that, plus two, intervals.
+int attn_max_partials(int NW, int BH) {
+    const int p = BH <= kMaxWeightedRows ? (8 * NW) / (BH + 7) + 3 : NW / BH + 2;
+    return p < NW ? p : NW;
+}
+__device__ __forceinline__ int bits_of_expert(const AttnArgs &a, int e) {
+    int b = 0;
+#pragma unroll
+    for (int k = 0; k < 8; k++) b = (e == k) ? a.bits_of[k] : b;
+    return b;
+}
+__device__ __forceinline__ int lgb_of_bits(int bits) { return bits == 2 ? 1 : (bits == 4 ? 2 : (bits == 8 ? 3 : 4)); }
+__device__ __forceinline__ uint32_t units_of_chunk(int N, int lgb) { return (uint32_t)((N + (256 >> lgb) - 1) >> (8 - lgb)); }
 
 // Chunks per row segment: at most kDescCap, and at most kUnitCap units if all of them were FP16.
 __host__ __device__ inline int attn_segment_chunks(int N) { return min(kDescCap, kUnitCap / (N / 16)); }
@@ -909,27 +925,60 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     const int w = (int)blockIdx.x, NW = (int)gridDim.x;
     const int N = a.N, C = a.n_chunks;
 
-    auto bits_of = [&](int e) {
-        int b = 0;
-#pragma unroll
-        for (int k = 0; k < 8; k++) b = (e == k) ? a.bits_of[k] : b;
-        return b;
-    };
+    auto bits_of = [&](int e) { return bits_of_expert(a, e); };
 
-    if constexpr (REP == 1) iq_build_wpos<G, NWV>(L, tid);  // made visible by the barriers of the row set-up
-    int r0, f0, r1, f1;
-    wg_interval(w, NW, a.BH, r0, f0, r1, f1);
     const int seg_chunks = attn_segment_chunks(N);
     const int n_seg = max(1, (C + seg_chunks - 1) / seg_chunks);
-    for (int u = r0; u <= r1 && u < a.BH; u++) {
-        if (u == r1 && f1 == 0) break;
+    // ---- the workgroup's interval of the unit axis
+    const bool weighted = a.BH <= kMaxWeightedRows;
+    if (weighted) {                                      // U = inclusive scan of the rows' unit counts, two rows per thread
+        static_assert(kMaxWeightedRows <= 2 * NT, "two rows per thread");
+        const uint32_t *row_units = a.counters + (size_t)a.BH * n_seg * kCounterStride;
+        const int i0 = 2 * tid;
+        const uint32_t v0 = i0 < a.BH ? row_units[i0] : 0u, v1 = i0 + 1 < a.BH ? row_units[i0 + 1] : 0u;
+        if constexpr (REP == 1) iq_build_wpos<G, NWV>(L, tid);          // behind the load
+        uint32_t incl = v0 + v1;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
+        }
+        if (lane == 63) L.wscan[wave] = incl;
+        __syncthreads();
+        uint32_t excl = incl - (v0 + v1);
+#pragma unroll
+        for (int wv = 0; wv < NWV; wv++) if (wv < wave) excl += L.wscan[wv];
+        if (tid == 0) { L.U[0] = 0u; L.r0 = 0u; }
+        if (i0 < a.BH) L.U[i0 + 1] = excl + v0;
+        if (i0 + 1 < a.BH) L.U[i0 + 2] = excl + v0 + v1;
+        __syncthreads();
+    } else {
+        if constexpr (REP == 1) iq_build_wpos<G, NWV>(L, tid);          // made visible by the barriers of the row set-up
+    }
+    auto Uof = [&](int u) -> unsigned long long { return weighted ? (unsigned long long)L.U[u] : (unsigned long long)u * NW; };
+    const unsigned long long Utot = Uof(a.BH);
+    const unsigned long long lo = (unsigned long long)w * Utot / NW, hi = (unsigned long long)(w + 1) * Utot / NW;
+    int r0 = (int)(lo / (unsigned long long)NW);         // the row that holds unit lo
+    if (weighted) {
+        for (int i = tid; i < a.BH; i += NT)
+            if ((unsigned long long)L.U[i] <= lo && lo < (unsigned long long)L.U[i + 1]) L.r0 = (uint32_t)i;
+        __syncthreads();
+        r0 = (int)L.r0;
+    }
+    uint32_t *row_wgs = a.counters + (size_t)a.BH * n_seg * kCounterStride + a.BH;   // for the merge: workgroups per row
+    for (int u = r0; u < a.BH && lo < hi && Uof(u) < hi; u++) {
+        const unsigned long long ub = Uof(u), ue = Uof(u + 1), ru = ue - ub;
+        if (ru == 0) continue;
         const uint8_t *erow = a.expert + (int64_t)u * a.desc_stride;
         const uint64_t *orow = a.chunk_off + (int64_t)u * a.desc_stride;
         // workgroups that share this row's tickets, and the share of the row inside this workgroup's
         // interval: a workgroup whose interval covers only part of the row takes at most that part of
         // the tickets (it owes the rest of its time to the neighbouring row)
-        const uint32_t P = (uint32_t)(wg_last_of_row(u, NW, a.BH) - wg_first_of_row(u, NW, a.BH) + 1);
-        const long long ov = min((long long)(w + 1) * a.BH, (long long)(u + 1) * NW) - max((long long)w * a.BH, (long long)u * NW);
+        const int wg_first = wg_first_of_row(ub, Utot, NW);
+        const uint32_t P = (uint32_t)(wg_last_of_row(ue, Utot, NW) - wg_first + 1);
+        const unsigned long long ov = min(hi, ue) - max(lo, ub);
+        const bool whole = (lo >= ub && hi <= ue) || (ub >= lo && ue <= hi);   // the interval inside the row, or the row inside it
+        if (w == wg_first && tid == 0) row_wgs[u] = P;
 
         // ---- (a) row set-up.  One round trip to memory for everything the first units need: the raw
         //      queries, the chunk descriptors of the first segment and the first batch of tickets.  The
@@ -1019,7 +1068,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             const uint32_t T = n_chunk_units + (uint32_t)(seg == n_seg - 1 ? (a.n_tail + 15) / 16 : 0);
             unsigned int *counter = a.counters + ((size_t)u * n_seg + seg) * kCounterStride;
             // no cap for a workgroup whose whole interval lies in this row, or that covers the whole row
-            const uint32_t quota = ov >= min(NW, a.BH) ? 0xffffffffu : (uint32_t)(((unsigned long long)T * (unsigned long long)ov + NW - 1) / NW);
+            const uint32_t quota = whole ? 0xffffffffu : (uint32_t)(((unsigned long long)T * ov + ru - 1) / ru);
             if (seg == 0 && tid == 0) {                  // the batch asked for during the row set-up
                 const uint32_t granted = g_first < T ? min((uint32_t)NWV, T - g_first) : 0u;
                 L.g_seen = g_first + (uint32_t)NWV;
@@ -1233,7 +1282,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             }
         }
         __syncthreads();
-        const int slot = w - wg_first_of_row(u, NW, a.BH);
+        const int slot = w - wg_first;
         for (int i = tid; i < REP * kD; i += NT) {
             const int r = i / kD, d = i % kD;
             float M = -INFINITY;
@@ -1253,31 +1302,46 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     }
 }
 
-// Zeroes the ticket counters of a decode call (a kernel rather than a memset node, so that the call
-// can be captured into a graph).
-__global__ void attn_clear_kernel(unsigned int *counters, int n) {
-    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (i < n) counters[(size_t)i * kCounterStride] = 0u;
+// Before the main kernel, one workgroup per row: zeroes the row's ticket counters (a kernel rather than a
+// memset node, so that the call can be captured into a graph) and adds up the cost of the row's units.
+__global__ __launch_bounds__(256) void attn_prep_kernel(AttnArgs a, int n_seg) {
+    __shared__ uint32_t wsum[4];
+    const int u = (int)blockIdx.x, tid = (int)threadIdx.x;
+    for (int i = tid; i < n_seg; i += 256) a.counters[((size_t)u * n_seg + i) * kCounterStride] = 0u;
+    uint32_t units = 0u;
+    const uint8_t *erow = a.expert + (int64_t)u * a.desc_stride;
+    const int NG = kD / a.G;
+    for (int c = tid; c < a.n_chunks; c += 256) {        // a unit costs its 8 KiB of codes plus its meta words, in steps of 512 bytes
+        const int lgb = lgb_of_bits(bits_of_expert(a, erow[c]));
+        units += units_of_chunk(a.N, lgb) * (uint32_t)(16 + (lgb < 4 ? (4 * NG) >> lgb : 0));
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) units += __shfl_xor(units, o);
+    if ((tid & 63) == 0) wsum[tid >> 6] = units;
+    __syncthreads();
+    if (tid == 0)
+        a.counters[(size_t)a.BH * n_seg * kCounterStride + u] = wsum[0] + wsum[1] + wsum[2] + wsum[3] + 16u * (uint32_t)((a.n_tail + 15) / 16);
 }
 int attn_row_segments(int n_chunks, int N) {
     const int sc = attn_segment_chunks(N);
     return n_chunks > sc ? (n_chunks + sc - 1) / sc : 1;
 }
 size_t attn_counter_bytes(int BH, int n_chunks, int N) {
-    return (size_t)BH * attn_row_segments(n_chunks, N) * kCounterStride * sizeof(unsigned int);
+    // ticket counters, then the rows' unit counts and workgroup counts
+    return ((size_t)BH * attn_row_segments(n_chunks, N) * kCounterStride + 2 * (size_t)BH) * sizeof(unsigned int);
 }
 
 // out[b, hq, :] = sum_p o_p 2^(m_p - M) / sum_p l_p 2^(m_p - M) over the partials of the row
 // (one per workgroup that touched the row's KV head).
 constexpr int kMergeGroups = 2;
 __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const float *__restrict__ part,
-                                                                       float *__restrict__ out, int rep, int NW,
-                                                                       int BH, int max_partials) {
+                                                                       float *__restrict__ out, int rep,
+                                                                       const uint32_t *__restrict__ row_wgs, int max_partials) {
     __shared__ float numl[kMergeGroups][kD];
     __shared__ float denl[kMergeGroups];
     const int row = (int)blockIdx.x, tid = (int)threadIdx.x, d = tid & (kD - 1), grp = tid >> 7;
     const int u = row / rep;
-    const int P = wg_last_of_row(u, NW, BH) - wg_first_of_row(u, NW, BH) + 1;
+    const int P = (int)row_wgs[u];
     const float *p0 = part + (int64_t)row * max_partials * (kD + 2);
     float M = -INFINITY;
     for (int p = 0; p < P; p++) M = fmaxf(M, p0[(int64_t)p * (kD + 2) + kD]);
@@ -1317,8 +1381,8 @@ static int resident_wgs_per_cu() {
 template <int G, int REP>
 static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     constexpr int NWV = waves_per_wg<REP>();
-    const int n_counters = a.BH * attn_row_segments(a.n_chunks, a.N);
-    hipLaunchKernelGGL(attn_clear_kernel, dim3((unsigned)((n_counters + 255) / 256)), dim3(256), 0, s, a.counters, n_counters);
+    const int n_seg = attn_row_segments(a.n_chunks, a.N);
+    hipLaunchKernelGGL(attn_prep_kernel, dim3((unsigned)a.BH), dim3(256), 0, s, a, n_seg);
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
     if (ev_begin && hipEventRecord(ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
@@ -1327,7 +1391,8 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
     if (e != hipSuccess) return e;
     if (ev_end && hipEventRecord(ev_end, s) != hipSuccess) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)(a.BH * a.rep)), dim3(kD * kMergeGroups), 0, s,
-                       (const float *)a.part, a.out, a.rep, a.n_wg, a.BH, a.max_partials);
+                       (const float *)a.part, a.out, a.rep,
+                       (const uint32_t *)(a.counters + (size_t)a.BH * n_seg * kCounterStride + a.BH), a.max_partials);
     return hipGetLastError();
 }
 

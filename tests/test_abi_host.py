@@ -39,8 +39,10 @@ def test_block_sizes_closed_form(mq):
     assert mq.chunk_block_bytes(cfg, 3) == 0
     assert mq.arena_upper_bound(cfg, 10) == 256 + 10 * 65536
     ws = mq.decode_workspace_bytes(cfg, 1024)
-    # 40 ticket counters 256 bytes apart, then whole partials (o[128], m, l) for each of the 40 query heads
-    assert ws > 40 * 256 and (ws - 40 * 256) % (40 * 130 * 4) == 0
+    # 40 ticket counters 256 bytes apart and two words per row (unit count, workgroup count), rounded up to
+    # 256 bytes; then whole partials (o[128], m, l) for each of the 40 query heads
+    head = (40 * 256 + 2 * 40 * 4 + 255) // 256 * 256
+    assert ws > head and (ws - head) % (40 * 130 * 4) == 0
 
 
 @pytest.mark.parametrize("kw", [dict(head_dim=64), dict(group=16), dict(chunk=48), dict(chunk=512),
