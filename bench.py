@@ -201,7 +201,7 @@ def main() -> int:
                    "packed_bytes": packed_bytes, "fp16_equiv_bytes": 2 * kv_bytes},
         # the dominant kernel, timed alone by a pair of HIP events the library records around it
         "roofline": dict(roof(attn_bytes, t_split), kernel="attn_split_kernel"),
-        # the decode call as a whole: attn_clear_kernel + attn_split_kernel + attn_merge_kernel and the gaps
+        # the decode call as a whole: attn_prep_kernel + attn_split_kernel + attn_merge_kernel and the gaps
         "decode_call": roof(attn_bytes, t_attn),
         "pct_of_hbm_peak": None,
     }

@@ -331,8 +331,20 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
             const int sh = code_shift(e, bits);
             w0 |= (v4 & 0xffu) << sh; w1 |= ((v4 >> 8) & 0xffu) << sh; w2 |= ((v4 >> 16) & 0xffu) << sh; w3 |= (v4 >> 24) << sh;
         }
-        uint32_t *dst = codes_w + (kib * 64 + 16 * qd + 4 * jq) * 4 + n;     // slot 16*qd + 4*jq + k, word n
-        nt_store(dst, w0); nt_store(dst + 4, w1); nt_store(dst + 8, w2); nt_store(dst + 12, w3);
+        // thread n = 0..3 of a quad holds word n of the slots 16*qd + 4*jq + k, k = 0..3: a 4 x 4 transpose inside
+        // the quad leaves every thread with one whole slot, stored with one 16-byte store
+        uint32_t wk[4] = {w0, w1, w2, w3};
+#pragma unroll
+        for (int k = 0; k < 4; k += 2) {
+            const uint32_t r = dpp_u<DPP_XOR1>((n & 1) ? wk[k] : wk[k + 1]);
+            if (n & 1) wk[k] = r; else wk[k + 1] = r;
+        }
+#pragma unroll
+        for (int k = 0; k < 2; k++) {
+            const uint32_t r = dpp_u<DPP_XOR2>((n & 2) ? wk[k] : wk[k + 2]);
+            if (n & 2) wk[k] = r; else wk[k + 2] = r;
+        }
+        nt_store(reinterpret_cast<uint4 *>(codes_w + (kib * 64 + 16 * qd + 4 * jq + n) * 4), uint4{wk[0], wk[1], wk[2], wk[3]});
     }
 }
 
