@@ -1332,33 +1332,42 @@ size_t attn_counter_bytes(int BH, int n_chunks, int N) {
 }
 
 // out[b, hq, :] = sum_p o_p 2^(m_p - M) / sum_p l_p 2^(m_p - M) over the partials of the row
-// (one per workgroup that touched the row's KV head).
-constexpr int kMergeGroups = 2;
+// (one per workgroup that touched the row's KV head).  Thread (grp, d) takes the partials grp, grp + 8, ...:
+// with the usual 6-8 partials per row every value is requested at once, one round trip to memory.
+constexpr int kMergeGroups = 8;
 __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const float *__restrict__ part,
                                                                        float *__restrict__ out, int rep,
                                                                        const uint32_t *__restrict__ row_wgs, int max_partials) {
     __shared__ float numl[kMergeGroups][kD];
-    __shared__ float denl[kMergeGroups];
+    __shared__ float denl[kMergeGroups], ml[kMergeGroups];
     const int row = (int)blockIdx.x, tid = (int)threadIdx.x, d = tid & (kD - 1), grp = tid >> 7;
     const int u = row / rep;
     const int P = (int)row_wgs[u];
     const float *p0 = part + (int64_t)row * max_partials * (kD + 2);
-    float M = -INFINITY;
-    for (int p = 0; p < P; p++) M = fmaxf(M, p0[(int64_t)p * (kD + 2) + kD]);
-    float num = 0.0f, den = 0.0f;
+    // this group's partials, merged on the way (online rescaling)
+    float m = -INFINITY, num = 0.0f, den = 0.0f;
     for (int p = grp; p < P; p += kMergeGroups) {
         const float *pp = p0 + (int64_t)p * (kD + 2);
-        const float f = (pp[kD] == -INFINITY) ? 0.0f : fast_exp2(pp[kD] - M);   // empty partial
-        num = fmaf(pp[d], f, num);
-        den = fmaf(pp[kD + 1], f, den);
+        const float mp = pp[kD], lp = pp[kD + 1], op = pp[d];
+        const float mn = fmaxf(m, mp);
+        const float fo = (m == -INFINITY) ? 0.0f : fast_exp2(m - mn), fp = (mp == -INFINITY) ? 0.0f : fast_exp2(mp - mn);   // empty partials
+        num = fmaf(num, fo, op * fp);
+        den = fmaf(den, fo, lp * fp);
+        m = mn;
     }
     numl[grp][d] = num;
-    if (d == 0) denl[grp] = den;
+    if (d == 0) { denl[grp] = den; ml[grp] = m; }
     __syncthreads();
     if (grp == 0) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int g = 0; g < kMergeGroups; g++) M = fmaxf(M, ml[g]);
         float n = 0.0f, dn = 0.0f;
 #pragma unroll
-        for (int g = 0; g < kMergeGroups; g++) { n += numl[g][d]; dn += denl[g]; }
+        for (int g = 0; g < kMergeGroups; g++) {
+            const float f = (ml[g] == -INFINITY) ? 0.0f : fast_exp2(ml[g] - M);
+            n = fmaf(numl[g][d], f, n); dn = fmaf(denl[g], f, dn);
+        }
         out[(int64_t)row * kD + d] = n / dn;
     }
 }
