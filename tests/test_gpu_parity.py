@@ -243,6 +243,27 @@ def test_attention_single_bit_width(mq, ref, bits, N, G, rep):
     assert err <= ATTN_TOL, err
 
 
+@pytest.mark.parametrize("heavy,B,Hkv,rep,N,C,T", [
+    (3, 1, 8, 1, 128, 160, 40),      # one row of 16-bit chunks among 2-bit rows: that row takes most workgroups
+    (0, 2, 4, 1, 64, 300, 0),
+    (-1, 1, 8, 1, 128, 160, 0),      # the reverse: one 2-bit row among 16-bit rows
+    (5, 1, 8, 4, 256, 60, 100),      # grouped queries
+    (2, 1, 40, 1, 128, 48, 7),       # more rows than some workgroup counts divide evenly
+])
+def test_attention_rows_of_unequal_cost(mq, ref, heavy, B, Hkv, rep, N, C, T):
+    # the workgroups split the rows by their cost (bytes to read): rows whose mixes differ as much as they can
+    bits = (2, 4, 8, 16)
+    BH = B * Hkv
+    expert = np.zeros((BH, C), np.uint8)                          # 2 bits everywhere ...
+    if heavy >= 0:
+        expert[heavy % BH] = 3                                    # ... but one row of 16-bit chunks
+    else:
+        expert[:] = 3; expert[BH // 2] = 0
+    expert[:, 1::7] = 1                                           # and a few 4-bit chunks in every row
+    err = _attn_case(mq, ref, B, Hkv * rep, Hkv, N, 64, C, T, bits, seed=BH + C, expert=expert, freeze=0)
+    assert err <= ATTN_TOL, err
+
+
 def test_attention_degenerate_cases(mq, ref):
     # residual rows only (no packed chunk), down to a single cached token
     assert _attn_case(mq, ref, 1, 4, 2, 64, 32, 0, 1, (2, 16), seed=1) <= ATTN_TOL
