@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # HBM bytes per decode call (attn_split_kernel + attn_merge_kernel, fetched + written) from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_<workload>.md; counters cannot be read
 # from inside this process, so a workload without such a run reports null.
-MEASURED_TRAFFIC = {"llama13b_128k": 693527135}
+MEASURED_TRAFFIC = {"llama13b_128k": 693653741}
 
 
 def log(*a):

@@ -146,8 +146,9 @@ int moqae_quantize_pack(const moqae_cfg *cfg,
  * [B, Hkv, N, D] of which rows [0, n_tail) are valid, 0 <= n_tail < N (may be
  * NULL when n_tail == 0); n_chunks + n_tail must be > 0.
  * out: fp32 [B, Hq, D].  workspace: at least moqae_decode_workspace_bytes()
- * bytes, 256-byte aligned, contents irrelevant on entry (one partial softmax
- * state per workgroup and row, merged by a second kernel of the same call).
+ * bytes, 256-byte aligned, contents irrelevant on entry (ticket counters and
+ * the cost of every row, written by the first kernel of the call; one partial
+ * softmax state per workgroup and row, merged by its last kernel).
  */
 int moqae_decode_attn(const moqae_cfg *cfg,
                       const void *q,
