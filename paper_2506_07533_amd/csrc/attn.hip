@@ -86,6 +86,17 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     uint32_t bl[kMaxBatches], bg[kMaxBatches];
 };
 
+// Inclusive prefix sum over the 64 lanes, on the vector ALU (row shifts, then the row totals handed on).
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xF, 0xF, false);   // row_shr:1
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xF, 0xF, false);   // row_shr:2
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, false);   // row_shr:4
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xF, 0xF, false);   // row_shr:8
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, DPP_BCAST15, 0xA, 0xF, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, DPP_BCAST31, 0xC, 0xF, false);
+    return x;
+}
+
 // Orders this wavefront's LDS traffic between phases that exchange data across lanes.
 __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -937,12 +948,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
         const int i0 = 2 * tid;
         const uint32_t v0 = i0 < a.BH ? row_units[i0] : 0u, v1 = i0 + 1 < a.BH ? row_units[i0 + 1] : 0u;
         if constexpr (REP == 1) iq_build_wpos<G, NWV>(L, tid);          // behind the load
-        uint32_t incl = v0 + v1;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t v = __shfl_up(incl, o);
-            if (lane >= o) incl += v;
-        }
+        const uint32_t incl = wave_incl_scan(v0 + v1);
         if (lane == 63) L.wscan[wave] = incl;
         __syncthreads();
         uint32_t excl = incl - (v0 + v1);
@@ -1053,14 +1059,9 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     mine += ucnt[k];
                 }
             }
-            uint32_t incl = mine;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t v = __shfl_up(incl, o);
-                if (lane >= o) incl += v;
-            }
+            const uint32_t incl = wave_incl_scan(mine);
             if (lane == 63) L.wscan[wave] = incl;
-            if (tid == 0) { L.next = 0; L.limit = 0; L.done = 0; L.fetching = 0; L.g_seen = 0; L.nb = 0; }
+            if (tid == 0) { L.next = (uint32_t)NWV; L.limit = 0; L.done = 0; L.fetching = 0; L.g_seen = 0; L.nb = 0; }   // the first draws are fixed: wavefront v holds local ticket v
             __syncthreads();
             uint32_t pos = incl - mine, n_chunk_units = 0;
 #pragma unroll
@@ -1125,7 +1126,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             };
 
             // tickets: the draw for the next unit is issued when the current one is taken
-            uint32_t pend = 0;
+            uint32_t pend = (uint32_t)wave;              // the first draw (L.next starts at NWV)
             int bcur = 0;                                // batch of this wavefront's latest ticket
             auto issue_draw = [&]() { if (lane == 0) pend = atomicAdd(&L.next, 1u); };
             auto next_unit = [&](Unit &un) -> bool {     // the pending draw becomes the next unit
@@ -1180,7 +1181,6 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                 }
                 return true;
             };
-            issue_draw();
 
             // K is requested half a unit ahead (right after the scores of the current unit), V a
             // whole unit ahead into the buffer the current unit does not use.
