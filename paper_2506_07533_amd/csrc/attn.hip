@@ -62,6 +62,7 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     v4i qa[REP == 1 ? 8 : 1][64];
     v4i wa[REP == 1 ? NWV : 1][2][64];                   // per wavefront: weight digits of up to two token blocks
     uint32_t wpos[REP == 1 ? 3 : 1][8][64];
+    alignas(16) float vf[REP < 4 ? NWV : 1][512];                  // raw fp16 units: the value sums of the four row groups on their way to the lanes that own the dims
     uint4 kx[REP == 1 ? NWV : 1][4 * 72];                // per wavefront: the K codes of a unit on their way to the lanes that use them
     int iq[kD];
     int iqs16[8];
@@ -69,7 +70,7 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     float iqscale[4];
     float sc[NWV][REP][128];                             // scores (log2 domain) / fp16-path weights of a unit
     static constexpr int WLS = 136;                      // weight row stride in halfs: rows fall on different banks
-    uint16_t wl[NWV][REP][NG][WLS];                      // fp16 softmax weight * V scale, pre-scaled per pair
+    alignas(16) uint16_t wl[NWV][REP][NG][WLS];                     // fp16 softmax weight * V scale, pre-scaled per pair
     uint16_t zrow[WLS];                                  // zeros: the weight row of the unused tile rows
     float qsumg[REP][NG];                                // sum of q over a group, times 2^-24
     v4u qmc[REP > 1 ? 3 : 1][4][REP > 1 ? 64 : 1];       // grouped queries: score operands A per (bit-width, pass, lane)
@@ -250,41 +251,60 @@ __device__ __forceinline__ void fp16_values(const Unit &u, const VRegs<G> &v, in
                                             AttnLds<G, REP, NWV> &L, WaveState<REP> &st, const float (&p4)[REP][4]) {
     const int tok_l = lane >> 4;
     const int nvalid = u.nvalid;
+    // staging buffer of the wavefront, 2 KiB: [row group l/16][half of the lane's 8 dims][column block l%16][4];
+    // with four or more heads it lies over the weight rows, which only quantised units use
+    float *stage;
+    if constexpr (REP >= 4) stage = reinterpret_cast<float *>(&L.wl[wave][0][0][0]);
+    else                    stage = &L.vf[wave][0];
+    static_assert(REP < 4 || sizeof(L.wl[0]) >= 2048, "staging buffer");
 #pragma unroll
     for (int r = 0; r < REP; r++) {
         float acc8[8];
 #pragma unroll
         for (int e = 0; e < 8; e++) acc8[e] = 0.0f;
+        // the packed halves feed the multiply-add directly (mixed-precision FMA), nothing is unpacked
+        if (nvalid == 16) {
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const float p24 = p4[r][j] * kTwoM24;                     // accumulators carry a factor 2^-24
-            const bool ok = 4 * j + tok_l < nvalid;                   // rows past nvalid may hold NaN / Inf
-            // the packed halves feed the multiply-add directly (mixed-precision FMA), nothing is unpacked
-            const uint32_t w[4] = {ok ? v.c[j].x : 0u, ok ? v.c[j].y : 0u, ok ? v.c[j].z : 0u, ok ? v.c[j].w : 0u};
+            for (int j = 0; j < 4; j++) {
+                const float p24 = p4[r][j] * kTwoM24;                 // accumulators carry a factor 2^-24
+                const uint32_t w[4] = {v.c[j].x, v.c[j].y, v.c[j].z, v.c[j].w};
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const half2_t h = as_half2(w[e >> 1]);
-                acc8[e] = fmaf(p24, (float)((e & 1) ? h.y : h.x), acc8[e]);
+                for (int e = 0; e < 8; e++) {
+                    const half2_t h = as_half2(w[e >> 1]);
+                    acc8[e] = fmaf(p24, (float)((e & 1) ? h.y : h.x), acc8[e]);
+                }
+            }
+        } else {                                                      // the last rows of the residual
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float p24 = p4[r][j] * kTwoM24;
+                const bool ok = 4 * j + tok_l < nvalid;               // rows past nvalid may hold NaN / Inf
+                const uint32_t w[4] = {ok ? v.c[j].x : 0u, ok ? v.c[j].y : 0u, ok ? v.c[j].z : 0u, ok ? v.c[j].w : 0u};
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    const half2_t h = as_half2(w[e >> 1]);
+                    acc8[e] = fmaf(p24, (float)((e & 1) ? h.y : h.x), acc8[e]);
+                }
             }
         }
-        // fold the four row groups, then hand every dim to the lane that owns it (2l, 2l+1)
+        // fold the four row groups through LDS and hand every dim to the lane that owns it (2l, 2l+1)
+        float4 t0, t1;
+        t0.x = acc8[0]; t0.y = acc8[1]; t0.z = acc8[2]; t0.w = acc8[3];
+        t1.x = acc8[4]; t1.y = acc8[5]; t1.z = acc8[6]; t1.w = acc8[7];
+        float *mine_w = stage + (lane >> 4) * 128 + (lane & 15) * 4;
+        *reinterpret_cast<float4 *>(mine_w) = t0;
+        *reinterpret_cast<float4 *>(mine_w + 64) = t1;
+        wave_sync();
+        // dims 2l, 2l+1: column block l/4, element 2*(l%4) of its 8: half (l%4)/2, word 2*(l%2)
+        const float *mine_r = stage + ((lane & 3) >> 1) * 64 + (lane >> 2) * 4 + (lane & 1) * 2;
+        float2 s = *reinterpret_cast<const float2 *>(mine_r);
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            acc8[e] += __shfl_xor(acc8[e], 16);
-            acc8[e] += __shfl_xor(acc8[e], 32);
+        for (int rg = 1; rg < 4; rg++) {
+            const float2 t = *reinterpret_cast<const float2 *>(mine_r + rg * 128);
+            s.x += t.x; s.y += t.y;
         }
-        wave_sync();
-        if (lane < 16) {
-            float4 t0, t1;
-            t0.x = acc8[0]; t0.y = acc8[1]; t0.z = acc8[2]; t0.w = acc8[3];
-            t1.x = acc8[4]; t1.y = acc8[5]; t1.z = acc8[6]; t1.w = acc8[7];
-            *reinterpret_cast<float4 *>(&L.sc[wave][r][8 * lane]) = t0;
-            *reinterpret_cast<float4 *>(&L.sc[wave][r][8 * lane + 4]) = t1;
-        }
-        wave_sync();
-        const float2 mine = *reinterpret_cast<const float2 *>(&L.sc[wave][r][2 * lane]);
-        st.acc[r][0] += mine.x;
-        st.acc[r][1] += mine.y;
+        st.acc[r][0] += s.x;
+        st.acc[r][1] += s.y;
         wave_sync();
     }
 }
