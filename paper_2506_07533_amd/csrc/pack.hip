@@ -227,7 +227,111 @@ constexpr int kPackThreads = 256;
 constexpr int kVRow = kD + 4;                        // bytes per token row of the V staging buffer
 
 // Position of the code with in-word index e (b bits): even e in the low half-word, odd e high.
-__device__ __forceinline__ int code_shift(int e, int b) { return 16 * (e & 1) + b * (e >> 1); }
+__device__ __forceinline__ constexpr int code_shift(int e, int b) { return 16 * (e & 1) + b * (e >> 1); }
+
+// Element-wise minimum / maximum of two fp16 pairs (finite inputs).
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t x, uint32_t y) {
+    uint32_t r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t x, uint32_t y) {
+    uint32_t r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+// binary32 sum of one fp16 half of w and c, rounded once: the conversion of the half is exact and rides
+// along in the mixed-precision multiply-add (x * 1 + c), so this is the binary32 subtraction x - (-c).
+__device__ __forceinline__ float add_lo_f16(uint32_t w, float c) {
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float add_hi_f16(uint32_t w, float c) {
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(c));
+    return r;
+}
+
+// rint(t) for 0 <= t < 2^22 without a conversion: t + 1.5 * 2^23 is rounded to an integer by the addition
+// itself (ties to even), and the integer sits in the low mantissa bits: bits(result) = kMagicBits + rint(t).
+constexpr float kMagic = 12582912.0f;
+constexpr uint32_t kMagicBits = 0x4B400000u;
+
+// One (token row, group) item of a quantised chunk: G consecutive dims, all in one lane.  No lane ever
+// needs another lane's data: minimum and maximum come from packed fp16 operations on the words as
+// loaded, scale and reciprocal are computed once per group, and a code costs four operations: x - min
+// (with the conversion folded in), * 1/scale, + magic (the rounding), shift-and-add into its word.  The
+// words are sums of bits(t + magic) << shift, i.e. of the codes plus a constant that is taken off at
+// the end; no code is ever masked.  No clamp is needed: the scale is rounded up, so that
+// (x - min) * (1/scale) <= qmax * (1 + 2e-7) and rounds to at most qmax, and x >= min.
+template <int G, int BITS>
+__device__ __forceinline__ void pack_item(const uint4 *__restrict__ p, bool isV, uint32_t *__restrict__ meta_dst,
+                                          uint32_t *__restrict__ k_dst, uint32_t *__restrict__ v_lds) {
+    constexpr int NW = G / 2;                        // input words (fp16 pairs) of the item
+    static_assert(NW >= 16, "G >= 32");
+    uint32_t w[NW];
+#pragma unroll
+    for (int j = 0; j < G / 8; j++) {                // the whole item is requested at once: its 128-byte line arrives once
+        const uint4 t = p[j];
+        w[4 * j] = t.x; w[4 * j + 1] = t.y; w[4 * j + 2] = t.z; w[4 * j + 3] = t.w;
+    }
+    uint32_t mn4[4], mx4[4];                          // four independent chains, folded at the end
+#pragma unroll
+    for (int k = 0; k < 4; k++) { mn4[k] = pk_min_f16(w[k], w[k + 4]); mx4[k] = pk_max_f16(w[k], w[k + 4]); }
+#pragma unroll
+    for (int k = 8; k < NW; k++) { mn4[k & 3] = pk_min_f16(mn4[k & 3], w[k]); mx4[k & 3] = pk_max_f16(mx4[k & 3], w[k]); }
+    const uint32_t mnp = pk_min_f16(pk_min_f16(mn4[0], mn4[1]), pk_min_f16(mn4[2], mn4[3]));
+    const uint32_t mxp = pk_max_f16(pk_max_f16(mx4[0], mx4[1]), pk_max_f16(mx4[2], mx4[3]));
+    float mn = fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16));
+    float mx = fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16));
+    if (mn == 0.0f) mn = 0.0f;                        // -0 is stored as +0
+    if (mx == 0.0f) mx = 0.0f;
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    const float R = __fsub_rn(mx, mn);
+    const float s32 = __fdiv_rn(R, qmax);
+    uint32_t s16 = float_to_half_bits(s32);
+    if (half_bits_to_float(s16) < s32) s16 += 1;      // the scale is rounded up
+    if (s16 == 0) s16 = 0x3C00u;                      // constant group: scale 1
+    const float inv = __fdiv_rn(1.0f, half_bits_to_float(s16));
+    nt_store(meta_dst, s16 | (float_to_half_bits(mn) << 16));
+    const float nmn = -mn;
+    auto ubits = [&](int d) -> uint32_t {             // kMagicBits + code of dim d of the item
+        const float diff = (d & 1) ? add_hi_f16(w[d >> 1], nmn) : add_lo_f16(w[d >> 1], nmn);
+        return __builtin_bit_cast(uint32_t, __fadd_rn(__fmul_rn(diff, inv), kMagic));
+    };
+    if (isV) {                                        // one code per byte into the staging rows
+        constexpr uint32_t KC = kMagicBits * 0x01010101u;
+#pragma unroll
+        for (int k = 0; k < G / 4; k++) {
+            uint32_t acc = ubits(4 * k);
+            acc += ubits(4 * k + 1) << 8; acc += ubits(4 * k + 2) << 16; acc += ubits(4 * k + 3) << 24;
+            v_lds[k] = acc - KC;
+        }
+    } else {                                          // the words of the token-major K layout
+        constexpr int CPW = 32 / BITS, WPL = G / CPW;
+        uint32_t ksum = 0;
+#pragma unroll
+        for (int e = 0; e < CPW; e++) ksum += 1u << code_shift(e, BITS);
+        const uint32_t KC = kMagicBits * ksum;        // constant folded (wraps like the sums do)
+        uint32_t out[WPL];
+#pragma unroll
+        for (int k = 0; k < WPL; k++) {
+            uint32_t acc = ubits(k * CPW);
+#pragma unroll
+            for (int e = 1; e < CPW; e++) acc += ubits(k * CPW + e) << code_shift(e, BITS);
+            out[k] = acc - KC;
+        }
+        if constexpr (WPL >= 4) {
+#pragma unroll
+            for (int k = 0; k < WPL; k += 4)
+                nt_store(reinterpret_cast<uint4 *>(k_dst + k), uint4{out[k], out[k + 1], out[k + 2], out[k + 3]});
+        } else {
+            static_assert(WPL == 2, "G = 32 at 2 bits");
+            nt_store(reinterpret_cast<uint2 *>(k_dst), uint2{out[0], out[1]});
+        }
+    }
+}
 
 template <int G>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
@@ -244,10 +348,9 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     const int b = u / a.Hkv, h = u % a.Hkv;
     const uint16_t *src = (isV ? a.V : a.K) + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h
                         + (int64_t)c * N * a.stride_s;
-    const int lane16 = tid & 15;                      // which 8 dims of the row
-    const int rsub = tid >> 4;                        // row inside a pass of 16 rows
 
     if (bits == 16) {                                 // FP16 expert: rows copied verbatim
+        const int lane16 = tid & 15, rsub = tid >> 4;
         uint4 *dst = reinterpret_cast<uint4 *>(blk + (isV ? (size_t)N * kD * 2 : 0));
         for (int row = rsub; row < N; row += kPackThreads / 16)
             nt_store(&dst[row * 16 + lane16], nt_load(reinterpret_cast<const uint4 *>(src + (int64_t)row * a.stride_s + lane16 * 8)));
@@ -255,63 +358,19 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     }
 
     constexpr int NG = kD / G;                        // groups per row
-    constexpr int LPG = G / 8;                        // lanes per group
     const size_t code_bytes = (size_t)N * kD * bits / 8, meta_bytes = (size_t)N * NG * 4;
     uint8_t *area = blk + (isV ? code_bytes + meta_bytes : 0);
     uint32_t *codes_w = reinterpret_cast<uint32_t *>(area);
     uint32_t *meta_w = reinterpret_cast<uint32_t *>(area + code_bytes);
-    const float qmax = (float)((1 << bits) - 1);
 
-    for (int row = rsub; row < N; row += kPackThreads / 16) {
-        const uint4 xv = nt_load(reinterpret_cast<const uint4 *>(src + (int64_t)row * a.stride_s + lane16 * 8));
-        const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) x[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-        float mn = x[0], mx = x[0];
-#pragma unroll
-        for (int e = 1; e < 8; e++) { mn = fminf(mn, x[e]); mx = fmaxf(mx, x[e]); }
-        mn = group_min<LPG>(mn);
-        mx = group_max<LPG>(mx);
-        if (mn == 0.0f) mn = 0.0f;                    // -0 is stored as +0
-        if (mx == 0.0f) mx = 0.0f;
-        const float R = __fsub_rn(mx, mn);
-        const float s32 = __fdiv_rn(R, qmax);
-        uint32_t s16 = float_to_half_bits(s32);
-        if (half_bits_to_float(s16) < s32) s16 += 1;  // the scale is rounded up
-        if (s16 == 0) s16 = 0x3C00u;                  // constant group: scale 1
-        const float inv = __fdiv_rn(1.0f, half_bits_to_float(s16));
-        uint32_t code[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-            float t = rintf(__fmul_rn(__fsub_rn(x[e], mn), inv));
-            t = fminf(fmaxf(t, 0.0f), qmax);
-            code[e] = (uint32_t)t;
-        }
-        if ((lane16 % LPG) == 0) nt_store(&meta_w[row * NG + lane16 / LPG], s16 | (float_to_half_bits(mn) << 16));
-
-        if (isV) {
-            uint32_t *dstv = reinterpret_cast<uint32_t *>(vcodes + row * kVRow + lane16 * 8);
-            dstv[0] = code[0] | code[1] << 8 | code[2] << 16 | code[3] << 24;
-            dstv[1] = code[4] | code[5] << 8 | code[6] << 16 | code[7] << 24;
-        } else if (bits == 2) {                       // 16 dims per word: two lanes per word
-            uint32_t w = 0;
-#pragma unroll
-            for (int e = 0; e < 8; e++) w |= code[e] << code_shift(e, 2);
-            if (lane16 & 1) w <<= 8;                  // in-word indices 8..15
-            w |= dpp_u<DPP_XOR1>(w);
-            if (!(lane16 & 1)) nt_store(&codes_w[row * 8 + (lane16 >> 1)], w);
-        } else if (bits == 4) {                       // 8 dims per word: one lane per word
-            uint32_t w = 0;
-#pragma unroll
-            for (int e = 0; e < 8; e++) w |= code[e] << code_shift(e, 4);
-            nt_store(&codes_w[row * 16 + lane16], w);
-        } else {                                      // 8 bits, 4 dims per word: two words per lane
-            uint2 w;
-            w.x = code[0] | code[2] << 8 | code[1] << 16 | code[3] << 24;
-            w.y = code[4] | code[6] << 8 | code[5] << 16 | code[7] << 24;
-            nt_store(reinterpret_cast<uint2 *>(codes_w + row * 32 + lane16 * 2), w);
-        }
+    // item = (token row, group): consecutive lanes take consecutive 2G-byte pieces of the chunk
+    for (int item = tid; item < N * NG; item += kPackThreads) {
+        const int row = item / NG, g = item % NG;
+        const uint4 *p = reinterpret_cast<const uint4 *>(src + (int64_t)row * a.stride_s + g * G);
+        uint32_t *vl = reinterpret_cast<uint32_t *>(vcodes + row * kVRow + g * G);
+        if (bits == 2)      pack_item<G, 2>(p, isV, &meta_w[item], codes_w + item * (G / 16), vl);
+        else if (bits == 4) pack_item<G, 4>(p, isV, &meta_w[item], codes_w + item * (G / 8), vl);
+        else                pack_item<G, 8>(p, isV, &meta_w[item], codes_w + item * (G / 4), vl);
     }
     if (!isV) return;
 
