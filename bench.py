@@ -73,6 +73,10 @@ def main() -> int:
                     help="profiling aid: after set-up run only decode calls in the timed loop")
     ap.add_argument("--force-bits", type=int, default=0,
                     help="sweep aid (implies --decode-only): every chunk takes the expert of this bit-width")
+    ap.add_argument("--sweep", choices=["chunk", "share"], default=None,
+                    help="trend sweeps on synthetic data (the paper's ablations, Table 3 and Table 5): 'chunk' runs the "
+                         "chosen single-layer workload at chunk sizes 64, 128 and 256; 'share' runs an 8-layer cut of the "
+                         "stack workload with routing-sharing groups of 1, 2, 4 and 8 layers")
     ap.add_argument("--copy-probe", action="store_true",
                     help="counter calibration: run a plain elementwise kernel that reads 1 GiB and writes 1 GiB, "
                          "five times, and exit (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE are scaled by what they read for it)")
@@ -92,12 +96,48 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
 
-    import torch
-    from paper_2506_07533_amd import binding as mq, synth
+    from paper_2506_07533_amd import synth
 
     w = synth.WORKLOADS[args.workload]
-    if w.n_layers > 1:
-        return bench_stack(args, w)
+    if args.sweep == "chunk":
+        if w.n_layers > 1:
+            print("bench.py: --sweep chunk takes a single-layer workload", file=sys.stderr)
+            return 2
+        args.no_cpu_baseline = True
+        rows = []
+        for N in (64, 128, 256):
+            r = bench_layer(args, dataclasses.replace(w, chunk=N, name=f"{w.name}/chunk{N}"))
+            rows.append({"chunk": N, "chunks": r["config"]["chunks"], "packed_bytes": r["config"]["packed_bytes"],
+                         "realised_mix": r["config"]["realised_mix"],
+                         "route_us": round(r["roofline_route"]["avg_ms"] * 1e3, 1),
+                         "pack_us": round(r["roofline_pack"]["avg_ms"] * 1e3, 1),
+                         "decode_call_us": round(r["decode_call"]["avg_ms"] * 1e3, 1),
+                         "decode_kernel_us": round(r["roofline"]["avg_ms"] * 1e3, 1),
+                         "decode_GBps": r["value"], "route_pack_chunks_per_s": r["route_pack_chunks_per_s"]})
+            log(f"[sweep] {rows[-1]}")
+        print(json.dumps({"sweep": "chunk", "workload": w.name, "data": "synthetic", "rows": rows}), flush=True)
+        return 0
+    if args.sweep == "share":
+        base = synth.WORKLOADS["stack32_32k"]
+        rows = []
+        for g in (1, 2, 4, 8):
+            r = bench_stack(args, dataclasses.replace(base, n_layers=8, share_group=g, name=f"{base.name}/8layers/share{g}"))
+            rows.append({"share_group": g, "layers": 8, "routed_layers": r["routed_layers"],
+                         "prefill_route_ms": r["prefill_route_ms"], "prefill_pack_ms": r["prefill_pack_ms"],
+                         "route_pack_chunks_per_s": r["route_pack_chunks_per_s"],
+                         "decode_step_ms": round(r["roofline"]["avg_ms"] * 8, 4)})
+            log(f"[sweep] {rows[-1]}")
+        print(json.dumps({"sweep": "share", "workload": base.name + " (8 layers)", "data": "synthetic", "rows": rows}), flush=True)
+        return 0
+    res = bench_stack(args, w) if w.n_layers > 1 else bench_layer(args, w)
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+def bench_layer(args, w):
+    """One layer: a step = route + pack + one decode call (see the module docstring)."""
+    import torch
+    from paper_2506_07533_amd import binding as mq, synth
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     BH, C, T, M = w.batch * w.n_kv_heads, w.n_chunks, w.n_tail, len(w.expert_bits)
@@ -218,8 +258,7 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, scale)
-    print(json.dumps(res), flush=True)
-    return 0
+    return res
 
 
 def bench_stack(args, w):
@@ -249,6 +288,8 @@ def bench_stack(args, w):
         # milliseconds of address-translation warm-up that has nothing to do with the method)
         if stack.is_leader(l):
             lc.route(d["K"], 0, C0, routers[l])
+        else:
+            lc.share_decisions_from(stack.layers[stack.leader_of(l)], 0, C0)
         lc.pack(d["K"], d["V"], 0, C0)
         lc.arena_used.zero_()
         torch.cuda.synchronize()
@@ -265,7 +306,8 @@ def bench_stack(args, w):
         t_route += ev[0].elapsed_time(ev[1]); t_pack += ev[1].elapsed_time(ev[2])
         lc.check_status()
         del d
-        log(f"[bench] layer {l} compressed")
+        log(f"[bench] layer {l} compressed: {'route' if stack.is_leader(l) else 'share'} {ev[0].elapsed_time(ev[1]):.3f} ms, "
+            f"pack {ev[1].elapsed_time(ev[2]):.3f} ms")
     packed = sum(int(lc.arena_used.item()) for lc in stack.layers)
     n_units = B * H * C0 * w.n_layers
 
@@ -311,10 +353,9 @@ def bench_stack(args, w):
         "pct_of_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
         "prefill_route_ms": round(t_route, 3), "prefill_pack_ms": round(t_pack, 3),
         "route_pack_chunks_per_s": round(n_units / ((t_route + t_pack) * 1e-3), 1),
-        "routed_layers": w.n_layers // max(1, w.share_group),
+        "routed_layers": sum(1 for l in range(w.n_layers) if stack.is_leader(l)),
     }
-    print(json.dumps(res), flush=True)
-    return 0
+    return res
 
 
 def cpu_baseline(w, d, scale):
