@@ -40,36 +40,59 @@ constexpr int DPP_MIRROR = 0x140;        // lane i <-> 15-i inside a row of 16
 constexpr int DPP_BCAST15 = 0x142;       // lane 15 of a row -> the next row
 constexpr int DPP_BCAST31 = 0x143;       // lane 31 -> rows 2, 3
 
+// Cross-lane reductions with the lane permutation folded into the arithmetic instruction (one vector
+// instruction per step).  Written as instructions because the compiler keeps the permutation as a move of
+// its own and re-canonicalises its result (four instructions per step).  The compiler does not see what
+// an asm statement executes and inserts no wait states for it, so every step brings its own: a DPP
+// operand must not be read within two wait states of an ordinary vector instruction that wrote it, nor
+// within three of a dot-product instruction (v_dot2_f32_f16 feeds group_sum directly); the first step
+// therefore waits three, the later ones (whose producer is the previous step) two, and a last s_nop
+// covers whatever DPP instruction may follow.  The input must not be the direct result of a matrix-core
+// instruction (their results need far longer).  All lanes must be active.
+#define MOQAE_DPP_FIRST(OP, CTRL) asm("s_nop 2\n\t" OP "_dpp %0, %0, %0 " CTRL : "+v"(x))
+#define MOQAE_DPP_STEP(OP, CTRL) asm("s_nop 1\n\t" OP "_dpp %0, %0, %0 " CTRL : "+v"(x))
+#define MOQAE_DPP_END() asm("s_nop 1" : "+v"(x))
+#define MOQAE_DPP_FULL " row_mask:0xf bank_mask:0xf"
+
 // Sum over aligned groups of LANES consecutive lanes (2, 4, 8 or 16); every lane gets the sum.
 template <int LANES>
 __device__ __forceinline__ float group_sum(float x) {
-    if constexpr (LANES >= 2)  x += dpp_f<DPP_XOR1>(x);
-    if constexpr (LANES >= 4)  x += dpp_f<DPP_XOR2>(x);
-    if constexpr (LANES >= 8)  x += dpp_f<DPP_HALF_MIRROR>(x);
-    if constexpr (LANES >= 16) x += dpp_f<DPP_MIRROR>(x);
+    if constexpr (LANES >= 2)  MOQAE_DPP_FIRST("v_add_f32", "quad_perm:[1,0,3,2]" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 4)  MOQAE_DPP_STEP("v_add_f32", "quad_perm:[2,3,0,1]" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 8)  MOQAE_DPP_STEP("v_add_f32", "row_half_mirror" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 16) MOQAE_DPP_STEP("v_add_f32", "row_mirror" MOQAE_DPP_FULL);
+    MOQAE_DPP_END();
     return x;
 }
 template <int LANES>
 __device__ __forceinline__ float group_min(float x) {
-    if constexpr (LANES >= 2)  x = fminf(x, dpp_f<DPP_XOR1>(x));
-    if constexpr (LANES >= 4)  x = fminf(x, dpp_f<DPP_XOR2>(x));
-    if constexpr (LANES >= 8)  x = fminf(x, dpp_f<DPP_HALF_MIRROR>(x));
-    if constexpr (LANES >= 16) x = fminf(x, dpp_f<DPP_MIRROR>(x));
+    if constexpr (LANES >= 2)  MOQAE_DPP_FIRST("v_min_f32", "quad_perm:[1,0,3,2]" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 4)  MOQAE_DPP_STEP("v_min_f32", "quad_perm:[2,3,0,1]" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 8)  MOQAE_DPP_STEP("v_min_f32", "row_half_mirror" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 16) MOQAE_DPP_STEP("v_min_f32", "row_mirror" MOQAE_DPP_FULL);
+    MOQAE_DPP_END();
     return x;
 }
 template <int LANES>
 __device__ __forceinline__ float group_max(float x) {
-    if constexpr (LANES >= 2)  x = fmaxf(x, dpp_f<DPP_XOR1>(x));
-    if constexpr (LANES >= 4)  x = fmaxf(x, dpp_f<DPP_XOR2>(x));
-    if constexpr (LANES >= 8)  x = fmaxf(x, dpp_f<DPP_HALF_MIRROR>(x));
-    if constexpr (LANES >= 16) x = fmaxf(x, dpp_f<DPP_MIRROR>(x));
+    if constexpr (LANES >= 2)  MOQAE_DPP_FIRST("v_max_f32", "quad_perm:[1,0,3,2]" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 4)  MOQAE_DPP_STEP("v_max_f32", "quad_perm:[2,3,0,1]" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 8)  MOQAE_DPP_STEP("v_max_f32", "row_half_mirror" MOQAE_DPP_FULL);
+    if constexpr (LANES >= 16) MOQAE_DPP_STEP("v_max_f32", "row_mirror" MOQAE_DPP_FULL);
+    MOQAE_DPP_END();
     return x;
 }
-// Maximum over the whole wavefront, returned wave-uniform.
+// Maximum over the whole wavefront, returned wave-uniform.  After the rows: lane 15 of rows 0 and 2 is
+// folded into rows 1 and 3 (the other rows keep their value), then lane 31 into rows 2 and 3; lane 63
+// holds the maximum of all.
 __device__ __forceinline__ float wave_max(float x) {
-    x = group_max<16>(x);
-    x = fmaxf(x, dpp_f<DPP_BCAST15, 0xA>(x));
-    x = fmaxf(x, dpp_f<DPP_BCAST31, 0xC>(x));
+    MOQAE_DPP_FIRST("v_max_f32", "quad_perm:[1,0,3,2]" MOQAE_DPP_FULL);
+    MOQAE_DPP_STEP("v_max_f32", "quad_perm:[2,3,0,1]" MOQAE_DPP_FULL);
+    MOQAE_DPP_STEP("v_max_f32", "row_half_mirror" MOQAE_DPP_FULL);
+    MOQAE_DPP_STEP("v_max_f32", "row_mirror" MOQAE_DPP_FULL);
+    MOQAE_DPP_STEP("v_max_f32", "row_bcast:15 row_mask:0xa bank_mask:0xf");
+    MOQAE_DPP_STEP("v_max_f32", "row_bcast:31 row_mask:0xc bank_mask:0xf");
+    MOQAE_DPP_END();
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
