@@ -146,6 +146,34 @@ def test_pack_bit_exact(mq, ref, B, Hkv, N, G, C):
     assert bad.size == 0, f"{bad.size} bytes differ, first at {bad[:5]}"
 
 
+@pytest.mark.parametrize("G", [32, 64])
+def test_pack_arbitrary_finite_halves(mq, ref, G):
+    """Every finite fp16 bit pattern, both signs, subnormals and the largest magnitudes side by side in one group:
+    ranges whose scale rounds up by a whole fp16 step, groups spanning 40 binades, near-constant groups.  The
+    kernel takes no clamp and no conversion for the codes (the rounding is an addition, the words are sums of bit
+    patterns), so one code outside [0, qmax] anywhere would carry into its neighbour and show up here."""
+    rng = np.random.default_rng(1000 + G)
+    B, Hkv, N, C = 1, 4, 64, 12
+    cfg, rcfg = _cfgs(mq, ref, B, Hkv, Hkv, N, G, (2, 4, 8, 16), 0)
+    S = C * N
+
+    def halves(shape):
+        bits = rng.integers(0, 1 << 16, shape, dtype=np.uint16)
+        bits[(bits & 0x7C00) == 0x7C00] &= 0xBFFF                 # no Inf / NaN: clear one exponent bit
+        return bits.view(np.float16)
+    K, V = halves((B, Hkv, S, 128)), halves((B, Hkv, S, 128))
+    # narrow groups: a few ulps around one value, so that (x - min) / scale lands on and next to .5 ties
+    base = halves((B, Hkv, S // 2, 128 // G, 1)).astype(np.float32)
+    step = np.abs(base) * 2.0 ** -10 + 2.0 ** -24
+    K[:, :, : S // 2] = (base + step * rng.integers(0, 9, (B, Hkv, S // 2, 128 // G, G))).reshape(B, Hkv, S // 2, 128).astype(np.float16)
+    K[~np.isfinite(K)] = 0
+    expert = (np.arange(B * Hkv * C).reshape(B * Hkv, C) % 3).astype(np.uint8)   # 2, 4 and 8 bits
+    (arena, used, off, status), (arena_ref, used_ref, off_ref, st_ref) = _pack_both(mq, ref, cfg, rcfg, K, V, 0, C, expert)
+    assert st_ref == 0 and int(status.item()) == 0 and int(used.item()) == int(used_ref[0])
+    bad = np.nonzero(arena.cpu().numpy() != arena_ref)[0]
+    assert bad.size == 0, f"{bad.size} bytes differ, first at {bad[:5]}"
+
+
 def test_pack_subrange_append_and_status(mq, ref):
     """Chunks appended by a second call land after the first; capacity and bad ids set the status word."""
     rng = np.random.default_rng(77)
