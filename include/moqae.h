@@ -160,6 +160,30 @@ int moqae_decode_attn(const moqae_cfg *cfg,
                       void *workspace, uint64_t workspace_bytes,
                       void *stream);
 
+/*
+ * The same attention for a batch whose sequences have different lengths (the residual rule of Sec. 3.2
+ * applies per sequence: each keeps its own last S mod N tokens in FP16, so a batch served together ends
+ * up with different numbers of packed chunks and of residual rows).
+ * n_chunks_seq, n_tail_seq: DEVICE int32 [B], read by the kernels of the call: sequence b attends to its
+ * first n_chunks_seq[b] packed chunks (<= max_chunks, values outside [0, max_chunks] are clamped) and to
+ * the first n_tail_seq[b] rows of its residual (clamped to [0, N-1]).  A sequence with neither gets
+ * zeros in `out`.  max_chunks (host) bounds the chunk counts and sizes the workspace; the tables' row
+ * stride desc_stride must be >= max_chunks.  K_tail, V_tail must not be NULL.  Everything else as in
+ * moqae_decode_attn; workspace: at least moqae_decode_workspace_bytes_ragged(cfg, max_chunks) bytes
+ * (larger than the uniform call's: one long sequence among short ones can be shared by all workgroups).
+ */
+int moqae_decode_attn_ragged(const moqae_cfg *cfg,
+                             const void *q,
+                             const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                             int64_t desc_stride,
+                             const int32_t *n_chunks_seq, int32_t max_chunks,
+                             const void *K_tail, const void *V_tail, const int32_t *n_tail_seq,
+                             float softmax_scale,
+                             float *out,
+                             void *workspace, uint64_t workspace_bytes,
+                             void *stream);
+uint64_t moqae_decode_workspace_bytes_ragged(const moqae_cfg *cfg, int32_t max_chunks);   /* host; 0 if cfg invalid */
+
 /* Host helpers (no GPU work). */
 uint64_t moqae_chunk_block_bytes(const moqae_cfg *cfg, int32_t bits);            /* K+V block of one chunk; 0 if invalid */
 uint64_t moqae_arena_upper_bound(const moqae_cfg *cfg, int64_t n_chunks_total);  /* all-16-bit worst case + alignment    */

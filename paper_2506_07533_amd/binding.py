@@ -51,7 +51,7 @@ class Cfg:
 _lib = None
 EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "moqae_chunk_block_bytes",
            "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version",
-           "moqae_debug_time_decode_kernel"]
+           "moqae_debug_time_decode_kernel", "moqae_decode_attn_ragged", "moqae_decode_workspace_bytes_ragged"]
 
 
 def lib():
@@ -70,6 +70,11 @@ def lib():
         L.moqae_decode_attn.restype = C.c_int
         L.moqae_decode_attn.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i64, i32, vp, vp, i32, C.c_float, vp,
                                         vp, u64, vp]
+        L.moqae_decode_attn_ragged.restype = C.c_int
+        L.moqae_decode_attn_ragged.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i64, vp, i32, vp, vp, vp, C.c_float, vp,
+                                               vp, u64, vp]
+        L.moqae_decode_workspace_bytes_ragged.restype = u64
+        L.moqae_decode_workspace_bytes_ragged.argtypes = [C.POINTER(_Cfg), i32]
         L.moqae_chunk_block_bytes.restype = u64
         L.moqae_chunk_block_bytes.argtypes = [C.POINTER(_Cfg), i32]
         L.moqae_arena_upper_bound.restype = u64
@@ -101,6 +106,10 @@ def arena_upper_bound(cfg: Cfg, n_chunks_total: int) -> int:
 
 def decode_workspace_bytes(cfg: Cfg, n_chunks: int) -> int:
     return int(lib().moqae_decode_workspace_bytes(C.byref(cfg.c()), n_chunks))
+
+
+def decode_workspace_bytes_ragged(cfg: Cfg, max_chunks: int) -> int:
+    return int(lib().moqae_decode_workspace_bytes_ragged(C.byref(cfg.c()), max_chunks))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -182,3 +191,29 @@ def decode_attn(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_
                                    n_chunks, _ptr(K_tail), _ptr(V_tail), n_tail, float(softmax_scale), _ptr(out),
                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "moqae_decode_attn")
+
+
+def decode_attn_ragged(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_off: Optional[torch.Tensor],
+                       expert: Optional[torch.Tensor], n_chunks_seq: torch.Tensor, max_chunks: int,
+                       K_tail: torch.Tensor, V_tail: torch.Tensor, n_tail_seq: torch.Tensor,
+                       softmax_scale: float, out: torch.Tensor, workspace: torch.Tensor) -> None:
+    """As decode_attn with per-sequence lengths: n_chunks_seq, n_tail_seq int32 [B] on the GPU;
+    workspace: uint8, >= decode_workspace_bytes_ragged(cfg, max_chunks)."""
+    assert q.is_cuda and q.dtype == torch.float16 and q.is_contiguous()
+    assert q.shape == (cfg.batch, cfg.n_q_heads, cfg.head_dim)
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+    for t in (n_chunks_seq, n_tail_seq):
+        assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.shape == (cfg.batch,)
+    stride = 0
+    if max_chunks > 0:
+        assert expert.dtype == torch.uint8 and chunk_off.dtype == torch.int64
+        assert expert.shape == chunk_off.shape and expert.is_contiguous() and chunk_off.is_contiguous()
+        stride = expert.shape[1]
+    for t in (K_tail, V_tail):
+        assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous()
+        assert t.shape == (cfg.batch, cfg.n_kv_heads, cfg.chunk, cfg.head_dim)
+    _check(lib().moqae_decode_attn_ragged(C.byref(cfg.c()), _ptr(q), _ptr(arena), _ptr(chunk_off), _ptr(expert), stride,
+                                          _ptr(n_chunks_seq), max_chunks, _ptr(K_tail), _ptr(V_tail), _ptr(n_tail_seq),
+                                          float(softmax_scale), _ptr(out), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream()),
+           "moqae_decode_attn_ragged")

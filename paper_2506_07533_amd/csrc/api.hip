@@ -90,6 +90,12 @@ uint64_t workspace_bytes(const moqae_cfg *c, int n_chunks) {
     const uint64_t rows = (uint64_t)c->batch * c->n_q_heads;
     return counters_bytes(c, n_chunks) + rows * (uint64_t)attn_max_partials(n_wg, BH) * (kD + 2) * sizeof(float);
 }
+// Ragged batches: one long sequence among short ones can meet every workgroup's interval.
+uint64_t workspace_bytes_ragged(const moqae_cfg *c, int max_chunks) {
+    const int n_wg = choose_wgs(c, max_chunks, c->chunk - 1);
+    const uint64_t rows = (uint64_t)c->batch * c->n_q_heads;
+    return counters_bytes(c, max_chunks) + rows * (uint64_t)n_wg * (kD + 2) * sizeof(float);
+}
 
 thread_local hipEvent_t g_time_begin = nullptr, g_time_end = nullptr;   // measurement aid, see moqae.h
 
@@ -211,6 +217,7 @@ int moqae_decode_attn(const moqae_cfg *cfg,
     a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
+    a.seq_chunks = nullptr; a.seq_tail = nullptr;
     a.counters = static_cast<unsigned int *>(workspace);
     a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, n_chunks)); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;
@@ -222,6 +229,49 @@ int moqae_decode_attn(const moqae_cfg *cfg,
     for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;
     hipError_t e = launch_attn(a, static_cast<hipStream_t>(stream), g_time_begin, g_time_end);
     return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+int moqae_decode_attn_ragged(const moqae_cfg *cfg,
+                             const void *q,
+                             const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                             int64_t desc_stride,
+                             const int32_t *n_chunks_seq, int32_t max_chunks,
+                             const void *K_tail, const void *V_tail, const int32_t *n_tail_seq,
+                             float softmax_scale,
+                             float *out,
+                             void *workspace, uint64_t workspace_bytes,
+                             void *stream) {
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !q || !out || !workspace || !n_chunks_seq || !n_tail_seq) return MOQAE_E_INVAL;
+    if (max_chunks < 0) return MOQAE_E_INVAL;
+    if (max_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride < max_chunks)) return MOQAE_E_INVAL;
+    if (!K_tail || !V_tail) return MOQAE_E_INVAL;
+    if (!aligned(q, 4) || !aligned(out, 8) || !aligned(workspace, 256)) return MOQAE_E_INVAL;
+    if (!aligned(n_chunks_seq, 4) || !aligned(n_tail_seq, 4)) return MOQAE_E_INVAL;
+    if (max_chunks > 0 && (!aligned(arena, 256) || !aligned(chunk_off, 8))) return MOQAE_E_INVAL;
+    if (!aligned(K_tail, 16) || !aligned(V_tail, 16)) return MOQAE_E_INVAL;
+    if (workspace_bytes < workspace_bytes_ragged(cfg, max_chunks)) return MOQAE_E_WORKSPACE;
+
+    AttnArgs a;
+    a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
+    a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
+    a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
+    a.seq_chunks = n_chunks_seq; a.seq_tail = n_tail_seq;
+    a.counters = static_cast<unsigned int *>(workspace);
+    a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, max_chunks)); a.out = out;
+    a.scale_log2 = softmax_scale * 1.4426950408889634f;
+    a.n_chunks = max_chunks; a.n_tail = cfg->chunk - 1;
+    a.n_wg = choose_wgs(cfg, max_chunks, cfg->chunk - 1);
+    a.max_partials = a.n_wg;
+    a.N = cfg->chunk; a.G = cfg->group; a.Hkv = cfg->n_kv_heads; a.rep = cfg->n_q_heads / cfg->n_kv_heads;
+    a.BH = cfg->batch * cfg->n_kv_heads;
+    for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;
+    hipError_t e = launch_attn(a, static_cast<hipStream_t>(stream), g_time_begin, g_time_end);
+    return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+uint64_t moqae_decode_workspace_bytes_ragged(const moqae_cfg *cfg, int32_t max_chunks) {
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || max_chunks < 0) return 0;
+    return workspace_bytes_ragged(cfg, max_chunks);
 }
 
 }  // extern "C"

@@ -945,7 +945,9 @@ __device__ __forceinline__ uint32_t units_of_chunk(int N, int lgb) { return (uin
 // Chunks per row segment: at most kDescCap, and at most kUnitCap units if all of them were FP16.
 __host__ __device__ inline int attn_segment_chunks(int N) { return min(kDescCap, kUnitCap / (N / 16)); }
 
-template <int G, int REP, int NWV>
+// RAGGED: the sequences of the batch have their own numbers of chunks and residual rows (a.seq_chunks,
+// a.seq_tail, device arrays indexed by sequence); a.n_chunks is then the bound that sizes the segments.
+template <int G, int REP, int NWV, bool RAGGED>
 __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     __shared__ AttnLds<G, REP, NWV> L;
     constexpr int NG = kD / G;
@@ -954,12 +956,12 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     const int tid = (int)threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // wave-uniform, kept scalar
     const int w = (int)blockIdx.x, NW = (int)gridDim.x;
-    const int N = a.N, C = a.n_chunks;
+    const int N = a.N;
 
     auto bits_of = [&](int e) { return bits_of_expert(a, e); };
 
     const int seg_chunks = attn_segment_chunks(N);
-    const int n_seg = max(1, (C + seg_chunks - 1) / seg_chunks);
+    const int n_seg = max(1, (a.n_chunks + seg_chunks - 1) / seg_chunks);
     // ---- the workgroup's interval of the unit axis
     const bool weighted = a.BH <= kMaxWeightedRows;
     if (weighted) {                                      // U = inclusive scan of the rows' unit counts, two rows per thread
@@ -997,6 +999,11 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
         if (ru == 0) continue;
         const uint8_t *erow = a.expert + (int64_t)u * a.desc_stride;
         const uint64_t *orow = a.chunk_off + (int64_t)u * a.desc_stride;
+        int C = a.n_chunks, n_tail = a.n_tail;           // of this row
+        if constexpr (RAGGED) {
+            C = min(max(a.seq_chunks[u / a.Hkv], 0), a.n_chunks);
+            n_tail = min(max(a.seq_tail[u / a.Hkv], 0), N - 1);
+        }
         // workgroups that share this row's tickets, and the share of the row inside this workgroup's
         // interval: a workgroup whose interval covers only part of the row takes at most that part of
         // the tickets (it owes the rest of its time to the neighbouring row)
@@ -1086,7 +1093,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             uint32_t pos = incl - mine, n_chunk_units = 0;
 #pragma unroll
             for (int wv = 0; wv < NWV; wv++) { if (wv < wave) pos += L.wscan[wv]; n_chunk_units += L.wscan[wv]; }
-            const uint32_t T = n_chunk_units + (uint32_t)(seg == n_seg - 1 ? (a.n_tail + 15) / 16 : 0);
+            const uint32_t T = n_chunk_units + (uint32_t)(seg == n_seg - 1 ? (n_tail + 15) / 16 : 0);
             unsigned int *counter = a.counters + ((size_t)u * n_seg + seg) * kCounterStride;
             // no cap for a workgroup whose whole interval lies in this row, or that covers the whole row
             const uint32_t quota = whole ? 0xffffffffu : (uint32_t)(((unsigned long long)T * ov + ru - 1) / ru);
@@ -1193,7 +1200,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     }
                 } else {                                 // 16 rows of the FP16 residual
                     const int row0 = (int)(tk - n_chunk_units) * 16;
-                    un.lgb = 4; un.nsub = 4; un.nvalid = min(16, a.n_tail - row0);
+                    un.lgb = 4; un.nsub = 4; un.nvalid = min(16, n_tail - row0);
                     un.kb = reinterpret_cast<const uint8_t *>(a.K_tail) + (size_t)u * N * 256;
                     un.vb = reinterpret_cast<const uint8_t *>(a.V_tail) + (size_t)u * N * 256;
                     un.kc = un.vc = (uint32_t)row0 * 256u;
@@ -1331,7 +1338,12 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(AttnArgs a, int n_seg) {
     uint32_t units = 0u;
     const uint8_t *erow = a.expert + (int64_t)u * a.desc_stride;
     const int NG = kD / a.G;
-    for (int c = tid; c < a.n_chunks; c += 256) {        // a unit costs its 8 KiB of codes plus its meta words, in steps of 512 bytes
+    int C = a.n_chunks, n_tail = a.n_tail;
+    if (a.seq_chunks) {                                   // ragged batch: this row's own length
+        C = min(max(a.seq_chunks[u / a.Hkv], 0), a.n_chunks);
+        n_tail = min(max(a.seq_tail[u / a.Hkv], 0), a.N - 1);
+    }
+    for (int c = tid; c < C; c += 256) {                 // a unit costs its 8 KiB of codes plus its meta words, in steps of 512 bytes
         const int lgb = lgb_of_bits(bits_of_expert(a, erow[c]));
         units += units_of_chunk(a.N, lgb) * (uint32_t)(16 + (lgb < 4 ? (4 * NG) >> lgb : 0));
     }
@@ -1339,8 +1351,10 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(AttnArgs a, int n_seg) {
     for (int o = 32; o >= 1; o >>= 1) units += __shfl_xor(units, o);
     if ((tid & 63) == 0) wsum[tid >> 6] = units;
     __syncthreads();
-    if (tid == 0)
-        a.counters[(size_t)a.BH * n_seg * kCounterStride + u] = wsum[0] + wsum[1] + wsum[2] + wsum[3] + 16u * (uint32_t)((a.n_tail + 15) / 16);
+    if (tid == 0) {
+        a.counters[(size_t)a.BH * n_seg * kCounterStride + u] = wsum[0] + wsum[1] + wsum[2] + wsum[3] + 16u * (uint32_t)((n_tail + 15) / 16);
+        a.counters[(size_t)a.BH * n_seg * kCounterStride + a.BH + u] = 0u;   // workgroups of the row: stays 0 for a row without tokens
+    }
 }
 int attn_row_segments(int n_chunks, int N) {
     const int sc = attn_segment_chunks(N);
@@ -1388,7 +1402,7 @@ __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const floa
             const float f = (ml[g] == -INFINITY) ? 0.0f : fast_exp2(ml[g] - M);
             n = fmaf(numl[g][d], f, n); dn = fmaf(denl[g], f, dn);
         }
-        out[(int64_t)row * kD + d] = n / dn;
+        out[(int64_t)row * kD + d] = dn > 0.0f ? n / dn : 0.0f;         // a sequence without tokens: zeros
     }
 }
 
@@ -1400,7 +1414,7 @@ static int resident_wgs_per_cu() {
     if (cached == 0) {
         int n = 0;
         constexpr int NWV = waves_per_wg<REP>();
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_split_kernel<G, REP, NWV>, NWV * 64, 0) != hipSuccess || n < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_split_kernel<G, REP, NWV, false>, NWV * 64, 0) != hipSuccess || n < 1)
             n = 1;
         cached = n;
     }
@@ -1415,7 +1429,8 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
     if (ev_begin && hipEventRecord(ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
+    if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
+    else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev_end && hipEventRecord(ev_end, s) != hipSuccess) return hipErrorInvalidValue;

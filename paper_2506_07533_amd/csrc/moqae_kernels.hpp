@@ -28,6 +28,7 @@ struct AttnArgs {
     const uint16_t *q; const uint8_t *arena; const uint64_t *chunk_off; const uint8_t *expert;
     int64_t desc_stride;
     const uint16_t *K_tail, *V_tail;
+    const int32_t *seq_chunks, *seq_tail;   // ragged batch: chunks / residual rows per sequence (device), else null
     float *part; float *out;
     unsigned int *counters;     // ticket counters, one per (row, row segment), attn_counter_bytes() in all
     float scale_log2;           // softmax_scale * log2(e)

@@ -330,3 +330,82 @@ def test_argument_errors(mq):
         mq.route_chunks(nofp16, Kt, 0, 1, W, W, torch.zeros((3, 3), dtype=torch.float16, device="cuda"), None,
                         torch.zeros((2, 1), dtype=torch.uint8, device="cuda"))
     assert e.value.code == mq.E_INVAL
+
+
+# ----------------------------------------------------------------------------------------------
+# decode attention over a batch of sequences of different lengths
+# ----------------------------------------------------------------------------------------------
+
+def _ragged_case(mq, ref, Hq, Hkv, N, G, lens, bits=(2, 4, 8, 16), seed=0):
+    """lens: tokens per sequence.  Every sequence's cache is packed up to its own last full chunk; the oracle is
+    called per sequence (batch 1) on that sequence's slice of the tables."""
+    rng = np.random.default_rng(seed)
+    B = len(lens)
+    Cs = [L // N for L in lens]; Ts = [L % N for L in lens]
+    Cmax = max(max(Cs), 1)
+    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, 1)
+    _, rcfg1 = _cfgs(mq, ref, 1, Hq, Hkv, N, G, bits, 1)
+    K, V = _rand_kv(rng, B, Hkv, Cmax * N + N)
+    q = rng.standard_normal((B, Hq, 128), dtype=np.float32).astype(np.float16)
+    expert = rng.integers(0, len(bits), (B * Hkv, Cmax)).astype(np.uint8)
+    scale = 1 / math.sqrt(128)
+    Kt = np.full((B, Hkv, N, 128), np.nan, np.float16); Vt = np.full((B, Hkv, N, 128), np.inf, np.float16)
+    for b in range(B):
+        Kt[b, :, :Ts[b]] = K[b, :, Cs[b] * N:Cs[b] * N + Ts[b]]; Vt[b, :, :Ts[b]] = V[b, :, Cs[b] * N:Cs[b] * N + Ts[b]]
+    # all Cmax chunks of every sequence are packed; a sequence only attends to its first Cs[b]
+    (arena, used, off, status), (arena_ref, used_ref, off_ref, st_ref) = _pack_both(mq, ref, cfg, rcfg, K, V, 0, Cmax, expert)
+    assert np.array_equal(arena.cpu().numpy(), arena_ref)
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(mq.decode_workspace_bytes_ragged(cfg, Cmax), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    nc = torch.tensor(Cs, dtype=torch.int32, device="cuda"); nt = torch.tensor(Ts, dtype=torch.int32, device="cuda")
+    mq.decode_attn_ragged(cfg, _dev(q), arena, off, _dev(expert), nc, Cmax, _dev(Kt), _dev(Vt), nt, scale, out, ws)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for b in range(B):
+        if lens[b] == 0:
+            assert (o[b] == 0).all()                              # a sequence without tokens: zeros
+            continue
+        rows = slice(b * Hkv, (b + 1) * Hkv)
+        o_ref = ref.decode_attn(rcfg1, q[b:b + 1], arena_ref, off_ref[rows], expert[rows], Cs[b],
+                                np.nan_to_num(Kt[b:b + 1], nan=0.0, posinf=0.0), np.nan_to_num(Vt[b:b + 1], nan=0.0, posinf=0.0),
+                                Ts[b], scale)
+        assert np.isfinite(o[b]).all()
+        worst = max(worst, (np.abs(o[b] - o_ref[0]).max(-1) / np.abs(o_ref[0]).max(-1)).max())
+    return worst
+
+
+@pytest.mark.parametrize("Hq,Hkv,N,G,lens", [
+    (4, 4, 64, 32, [64 * 30 + 5, 17, 64 * 7, 0, 64 * 12 + 63, 1]),          # long, residual only, whole chunks, empty, one token
+    (8, 2, 128, 64, [128 * 40 + 100, 128 * 3, 90, 128 * 17 + 1]),           # grouped queries x4
+    (2, 2, 256, 64, [256 * 9 + 255, 256, 255, 256 * 4]),
+    (2, 1, 64, 64, [64 * 300, 64 * 2 + 1, 5]),                              # grouped queries x2, one row much longer than the rest
+    (3, 3, 128, 64, [0, 0, 77]),                                            # almost everything empty
+])
+def test_attention_ragged_batch(mq, ref, Hq, Hkv, N, G, lens):
+    err = _ragged_case(mq, ref, Hq, Hkv, N, G, lens, seed=len(lens) * 31 + N)
+    assert err <= ATTN_TOL, err
+
+
+def test_attention_ragged_equals_uniform(mq, ref):
+    """With equal lengths the ragged call reproduces the uniform call (same kernels, same tickets) to rounding."""
+    rng = np.random.default_rng(5)
+    B, Hq, Hkv, N, G, C, T = 3, 4, 4, 128, 64, 21, 40
+    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, (2, 4, 8, 16), 1)
+    K, V = _rand_kv(rng, B, Hkv, C * N + T)
+    q = _dev(rng.standard_normal((B, Hq, 128), dtype=np.float32).astype(np.float16))
+    expert = rng.integers(0, 4, (B * Hkv, C)).astype(np.uint8)
+    (arena, used, off, status), _ = _pack_both(mq, ref, cfg, rcfg, K, V, 0, C, expert)
+    Kt = np.zeros((B, Hkv, N, 128), np.float16); Vt = np.zeros_like(Kt)
+    Kt[:, :, :T] = K[:, :, C * N:]; Vt[:, :, :T] = V[:, :, C * N:]
+    Ktd, Vtd, ed = _dev(Kt), _dev(Vt), _dev(expert)
+    out_u = torch.zeros((B, Hq, 128), dtype=torch.float32, device="cuda"); out_r = torch.zeros_like(out_u)
+    ws = torch.zeros(mq.decode_workspace_bytes_ragged(cfg, C), dtype=torch.uint8, device="cuda")
+    scale = 1 / math.sqrt(128)
+    mq.decode_attn(cfg, q, arena, off, ed, C, Ktd, Vtd, T, scale, out_u, ws)
+    nc = torch.full((B,), C, dtype=torch.int32, device="cuda"); nt = torch.full((B,), T, dtype=torch.int32, device="cuda")
+    mq.decode_attn_ragged(cfg, q, arena, off, ed, nc, C, Ktd, Vtd, nt, scale, out_r, ws)
+    torch.cuda.synchronize()
+    a, b = out_u.cpu().numpy(), out_r.cpu().numpy()
+    assert np.abs(a - b).max() <= 1e-5 * np.abs(a).max()
