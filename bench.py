@@ -77,6 +77,9 @@ def main() -> int:
                     help="trend sweeps on synthetic data (the paper's ablations, Table 3 and Table 5): 'chunk' runs the "
                          "chosen single-layer workload at chunk sizes 64, 128 and 256; 'share' runs an 8-layer cut of the "
                          "stack workload with routing-sharing groups of 1, 2, 4 and 8 layers")
+    ap.add_argument("--ragged", action="store_true",
+                    help="decode attention over a batch of 16 sequences of 2k ... 32k tokens (one layer of the stack "
+                         "workload's shape) through moqae_decode_attn_ragged, beside the uniform call at full length")
     ap.add_argument("--copy-probe", action="store_true",
                     help="counter calibration: run a plain elementwise kernel that reads 1 GiB and writes 1 GiB, "
                          "five times, and exit (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE are scaled by what they read for it)")
@@ -128,6 +131,9 @@ def main() -> int:
                          "decode_step_ms": round(r["roofline"]["avg_ms"] * 8, 4)})
             log(f"[sweep] {rows[-1]}")
         print(json.dumps({"sweep": "share", "workload": base.name + " (8 layers)", "data": "synthetic", "rows": rows}), flush=True)
+        return 0
+    if args.ragged:
+        print(json.dumps(bench_ragged(args)), flush=True)
         return 0
     res = bench_stack(args, w) if w.n_layers > 1 else bench_layer(args, w)
     print(json.dumps(res), flush=True)
@@ -356,6 +362,76 @@ def bench_stack(args, w):
         "routed_layers": sum(1 for l in range(w.n_layers) if stack.is_leader(l)),
     }
     return res
+
+
+def bench_ragged(args):
+    """One layer of the stack workload's shape (16 sequences x 32 KV heads, chunk 128, planted mix) packed to 32k
+    tokens; the sequences then attend to 2k, 4k, ... 32k tokens of it (plus residuals of different lengths)."""
+    import math
+    import torch
+    from paper_2506_07533_amd import binding as mq, cache, synth
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = dataclasses.replace(synth.WORKLOADS["stack32_32k"], n_layers=1, share_group=1, name="ragged16_2k-32k")
+    N, D, B, H = w.chunk, w.head_dim, w.batch, w.n_kv_heads
+    C0 = w.seq // N
+    cfg = mq.Cfg(B, w.n_q_heads, H, D, N, w.group, w.expert_bits, w.freeze_chunks)
+    d = synth.make_layer_device(w, 0, dev)
+    lc = cache.LayerCache(cfg, C0)
+    lc.route(d["K"], 0, C0, (d["W1"], d["W2"], d["W3"], None))
+    lc.pack(d["K"], d["V"], 0, C0)
+    torch.cuda.synchronize()
+    lc.check_status()
+    lens_c = [(b + 1) * C0 // B for b in range(B)]                 # 16, 32, ... 256 chunks
+    lens_t = [(37 * b) % N for b in range(B)]
+    lc.K_tail.copy_(d["K"][:, :, :N]); lc.V_tail.copy_(d["V"][:, :, :N])
+    nc = torch.tensor(lens_c, dtype=torch.int32, device=dev); nt = torch.tensor(lens_t, dtype=torch.int32, device=dev)
+    q = d["q"]
+    out = torch.zeros((B, w.n_q_heads, D), dtype=torch.float32, device=dev)
+    ws = torch.zeros(mq.decode_workspace_bytes_ragged(cfg, C0), dtype=torch.uint8, device=dev)
+    scale = 1.0 / math.sqrt(D)
+    e_host = lc.expert[:, :C0].cpu().numpy()
+    blk = np.array([mq.chunk_block_bytes(cfg, b) for b in w.expert_bits], np.int64)
+    sizes = blk[e_host]                                             # [B*H, C0]
+    bytes_r = sum(int(sizes[b * H:(b + 1) * H, :lens_c[b]].sum()) + lens_c[b] * H * 9 + 2 * H * lens_t[b] * D * 2 for b in range(B))
+    bytes_u = int(sizes.sum()) + B * H * C0 * 9
+    bytes_r += q.numel() * 2 + out.numel() * 4; bytes_u += q.numel() * 2 + out.numel() * 4
+    # a second cache of the same contents, so that consecutive calls do not read what the last-level cache holds
+    lc2 = cache.LayerCache(cfg, C0)
+    lc2.expert.copy_(lc.expert); lc2.pack(d["K"], d["V"], 0, C0); lc2.K_tail.copy_(lc.K_tail); lc2.V_tail.copy_(lc.V_tail)
+    torch.cuda.synchronize()
+    caches = [lc, lc2]
+
+    def run(ragged, i):
+        c = caches[i & 1]
+        if ragged:
+            mq.decode_attn_ragged(cfg, q, c.arena, c.chunk_off, c.expert, nc, C0, c.K_tail, c.V_tail, nt, scale, out, ws)
+        else:
+            mq.decode_attn(cfg, q, c.arena, c.chunk_off, c.expert, C0, None, None, 0, scale, out, ws)
+
+    def timed(ragged):
+        for i in range(args.warmup):
+            run(ragged, i)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for i, (e0, e1) in enumerate(ev):
+            e0.record(); run(ragged, i); e1.record()
+        torch.cuda.synchronize()
+        return np.array([e0.elapsed_time(e1) for e0, e1 in ev])
+
+    t_r, t_u = timed(True), timed(False)
+    g_r = bytes_r / (t_r.mean() * 1e-3) / 1e9; g_u = bytes_u / (t_u.mean() * 1e-3) / 1e9
+    return {"metric": "decode_attn_hbm_GBps", "value": round(g_r, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(float(t_r.mean()), 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": w.name, "batch": B, "q_heads": w.n_q_heads, "kv_heads": H, "head_dim": D, "chunk": N,
+                       "group": w.group, "chunks_per_sequence": lens_c, "residual_rows": lens_t, "packed_bytes_read": bytes_r},
+            "roofline": {"bound": "hbm", "achieved": round(g_r, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": round(g_r / HBM_PEAK_GBPS, 4), "traffic": None, "bytes_per_launch": bytes_r,
+                         "avg_ms": round(float(t_r.mean()), 4), "min_ms": round(float(t_r.min()), 4),
+                         "kernel": "whole moqae_decode_attn_ragged call"},
+            "uniform_call_full_length": {"achieved": round(g_u, 1), "frac": round(g_u / HBM_PEAK_GBPS, 4),
+                                         "bytes_per_launch": bytes_u, "avg_ms": round(float(t_u.mean()), 4)}}
 
 
 def cpu_baseline(w, d, scale):

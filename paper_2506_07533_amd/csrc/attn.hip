@@ -54,6 +54,7 @@ constexpr int kUnitCap = 8192;                            // units of a row segm
 constexpr int kCounterStride = 64;                        // uint32 slots between two ticket counters (256 bytes)
 constexpr int kMaxWeightedRowsLds = 1024;                // == kMaxWeightedRows
 constexpr int kMaxBatches = 64;                           // ticket batches a workgroup can be granted per row segment
+constexpr uint32_t kRowSetupCost = 40u * 16u;             // a row's set-up in the cost unit of attn_prep_kernel (512 bytes of codes)
 
 template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     static constexpr int NG = kD / G;
@@ -1352,7 +1353,10 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(AttnArgs a, int n_seg) {
     if ((tid & 63) == 0) wsum[tid >> 6] = units;
     __syncthreads();
     if (tid == 0) {
-        a.counters[(size_t)a.BH * n_seg * kCounterStride + u] = wsum[0] + wsum[1] + wsum[2] + wsum[3] + 16u * (uint32_t)((n_tail + 15) / 16);
+        // plus what the set-up of a row costs a workgroup (three round trips to memory and the tables: about as long
+        // as 27 units take its eight wavefronts; 40 measured best), so that many short rows are not all handed to one workgroup
+        const uint32_t units_cost = wsum[0] + wsum[1] + wsum[2] + wsum[3] + 16u * (uint32_t)((n_tail + 15) / 16);
+        a.counters[(size_t)a.BH * n_seg * kCounterStride + u] = units_cost ? units_cost + kRowSetupCost : 0u;
         a.counters[(size_t)a.BH * n_seg * kCounterStride + a.BH + u] = 0u;   // workgroups of the row: stays 0 for a row without tokens
     }
 }
