@@ -63,3 +63,6 @@ def test_null_pointers_are_rejected_before_any_launch(mq):
     assert L.moqae_route_chunks(C.byref(cfg), None, 0, 0, 128, 0, 1, None, None, None, None, None, 1, None, None) == mq.E_INVAL
     assert L.moqae_quantize_pack(C.byref(cfg), None, None, 0, 0, 128, 0, 1, None, 1, None, 0, None, None, 1, None, None) == mq.E_INVAL
     assert L.moqae_decode_attn(C.byref(cfg), None, None, None, None, 0, 0, None, None, 0, 1.0, None, None, 0, None) == mq.E_INVAL
+    assert L.moqae_decode_attn_ragged(C.byref(cfg), None, None, None, None, 0, None, 4, None, None, None, 1.0, None, None, 0,
+                                      None) == mq.E_INVAL
+    assert mq.decode_workspace_bytes_ragged(mq.Cfg(1, 8, 8), 16) >= mq.decode_workspace_bytes(mq.Cfg(1, 8, 8), 16)
