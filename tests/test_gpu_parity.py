@@ -409,3 +409,70 @@ def test_attention_ragged_equals_uniform(mq, ref):
     torch.cuda.synchronize()
     a, b = out_u.cpu().numpy(), out_r.cpu().numpy()
     assert np.abs(a - b).max() <= 1e-5 * np.abs(a).max()
+
+
+# ----------------------------------------------------------------------------------------------
+# the calls under HIP graph capture
+# ----------------------------------------------------------------------------------------------
+
+def test_hot_path_replays_from_a_hip_graph(mq, ref):
+    """Route + pack + decode captured once into a HIP graph and replayed with new inputs in the same buffers: every
+    replay must equal the eager calls on those inputs (the library clears its counters with kernels, not with
+    memset nodes, and allocates nothing)."""
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, N, G, C, T = 2, 8, 4, 128, 64, 12, 30
+    cfg, _ = _cfgs(mq, ref, B, Hq, Hkv, N, G, (2, 4, 8, 16), 1)
+    M = 4
+    W = [_dev((rng.standard_normal(s) * 0.3).astype(np.float16)) for s in [(128, M), (128, M), (M, M)]]
+    Kd = torch.zeros((B, Hkv, C * N, 128), dtype=torch.float16, device="cuda"); Vd = torch.zeros_like(Kd)
+    q = torch.zeros((B, Hq, 128), dtype=torch.float16, device="cuda")
+    Kt = torch.zeros((B, Hkv, N, 128), dtype=torch.float16, device="cuda"); Vt = torch.zeros_like(Kt)
+    cap = mq.arena_upper_bound(cfg, B * Hkv * C)
+
+    def buffers():
+        return dict(expert=torch.zeros((B * Hkv, C), dtype=torch.uint8, device="cuda"),
+                    arena=torch.zeros(cap, dtype=torch.uint8, device="cuda"),
+                    used=torch.zeros(1, dtype=torch.int64, device="cuda"),
+                    off=torch.zeros((B * Hkv, C), dtype=torch.int64, device="cuda"),
+                    status=torch.zeros(1, dtype=torch.int32, device="cuda"),
+                    out=torch.zeros((B, Hq, 128), dtype=torch.float32, device="cuda"),
+                    ws=torch.zeros(mq.decode_workspace_bytes(cfg, C), dtype=torch.uint8, device="cuda"))
+
+    def path(b):
+        b["used"].zero_()
+        mq.route_chunks(cfg, Kd, 0, C, *W, None, b["expert"], None)
+        mq.quantize_pack(cfg, Kd, Vd, 0, C, b["expert"], b["arena"], b["used"], b["off"], b["status"])
+        mq.decode_attn(cfg, q, b["arena"], b["off"], b["expert"], C, Kt, Vt, T, 1 / math.sqrt(128), b["out"], b["ws"])
+
+    def new_inputs(seed):
+        r = np.random.default_rng(seed)
+        K, V = _rand_kv(r, B, Hkv, C * N + T)
+        Kd.copy_(_dev(K[:, :, :C * N])); Vd.copy_(_dev(V[:, :, :C * N]))
+        Kt[:, :, :T].copy_(_dev(K[:, :, C * N:])); Vt[:, :, :T].copy_(_dev(V[:, :, C * N:]))
+        q.copy_(_dev(r.standard_normal((B, Hq, 128), dtype=np.float32).astype(np.float16)))
+
+    bg, be = buffers(), buffers()
+    new_inputs(100)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        path(bg)                                                  # warm-up outside the capture (occupancy query, module load)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path(bg)
+    for rep in range(3):
+        new_inputs(200 + rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        path(be)                                                  # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        assert int(bg["status"].item()) == 0 and int(be["status"].item()) == 0
+        assert torch.equal(bg["expert"], be["expert"]) and torch.equal(bg["off"], be["off"])
+        n_used = int(be["used"].item())                          # beyond it the arenas hold what earlier inputs left
+        assert int(bg["used"].item()) == n_used and torch.equal(bg["arena"][:n_used], be["arena"][:n_used])
+        a, b = bg["out"].cpu().numpy(), be["out"].cpu().numpy()
+        # attention: equal up to the order in which the wavefronts drew their units (grouped queries round their
+        # weights to fp16 relative to the running maximum of the moment), far inside the 2e-3 bar
+        assert np.isfinite(a).all() and np.abs(a - b).max() <= 2e-4 * np.abs(b).max()
