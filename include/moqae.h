@@ -118,7 +118,8 @@ int moqae_route_chunks(const moqae_cfg *cfg,
  * Blocks are appended to `arena` in (b, h, c) order starting at *arena_used
  * rounded up to 256 bytes; each block start is 256-byte aligned;
  * chunk_off[(b*Hkv+h)*off_stride + c] receives the block's byte offset and
- * *arena_used the new end.  `arena` must be 256-byte aligned.
+ * *arena_used the new end.  `arena` must be 256-byte aligned.  At most 65535
+ * chunks per (sequence, KV head) and call (MOQAE_E_INVAL beyond; call again for more).
  * *status (device int32) must be 0 on entry, otherwise the call is a no-op; if
  * the blocks do not fit below arena_capacity, or an expert index is >= M,
  * *status becomes MOQAE_E_ARENA / MOQAE_E_INVAL and nothing else is written

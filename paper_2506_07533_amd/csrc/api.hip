@@ -176,6 +176,7 @@ int moqae_quantize_pack(const moqae_cfg *cfg,
                         void *stream) {
     if (!cfg_ok(cfg) || !layout_ok(cfg) || !K || !V || !expert || !arena || !arena_used || !chunk_off || !status) return MOQAE_E_INVAL;
     if (chunk_begin < 0 || chunk_end < chunk_begin) return MOQAE_E_INVAL;
+    if (chunk_end - chunk_begin > 65535) return MOQAE_E_INVAL;             // grid.y of the pack kernel
     if (expert_stride < chunk_end || off_stride < chunk_end) return MOQAE_E_INVAL;
     if (!strides_ok(cfg, stride_b, stride_h, stride_s) || !aligned(K, 16) || !aligned(V, 16)) return MOQAE_E_INVAL;
     if (!aligned(arena, 256) || !aligned(arena_used, 8) || !aligned(chunk_off, 8) || !aligned(status, 4)) return MOQAE_E_INVAL;

@@ -4,11 +4,12 @@
 //
 //   plan_rows_kernel / plan_kernel  block sizes -> exclusive scan in (b, h, c) order -> offsets and
 //                capacity check: one workgroup per row when the table allows, else one workgroup.
-//   pack_kernel  one workgroup per (chunk, K or V).  16 lanes own one token row (8 dims each),
-//                group min/max by DPP, codes in registers.  K words are assembled in registers
-//                (row-major layout); V codes go through LDS as bytes and are gathered
-//                token-wise into the dimension-major tile layout.  HBM-bound: reads 2*N*D*2 bytes,
-//                writes the block.
+//   pack_kernel  one workgroup per (K or V, chunk, row), one lane per (token row, group): the lane loads its
+//                G dims, takes minimum and maximum with packed fp16 operations, computes scale and
+//                reciprocal once and then four operations per code (no cross-lane step anywhere).
+//                K words are assembled in registers (row-major layout); V codes go through LDS as
+//                bytes and are gathered token-wise into the dimension-major tile layout.
+//                HBM-bound: reads 2*N*D*2 bytes, writes the block.
 #include "moqae_dev.hpp"
 #include "moqae_kernels.hpp"
 
@@ -338,9 +339,9 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     extern __shared__ uint8_t vcodes[];               // [N][kVRow] code bytes (V only); odd dword stride: rows fall on different banks
     if (*a.status != 0) return;
 
-    const int c = a.chunk_begin + (int)blockIdx.x;
-    const int u = (int)blockIdx.y;
-    const int isV = (int)blockIdx.z;
+    const int isV = (int)blockIdx.x;                  // K and V of a chunk side by side in launch order: the lighter K
+    const int c = a.chunk_begin + (int)blockIdx.y;    // workgroups and the V workgroups (LDS phase) share the CUs at all times
+    const int u = (int)blockIdx.z;
     const int tid = (int)threadIdx.x;
     const int N = a.N;
     const int bits = a.bits_of[a.expert[(int64_t)u * a.expert_stride + c]];
@@ -425,7 +426,7 @@ hipError_t launch_pack(const PackArgs &a, hipStream_t s) {
     else         hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)a.n_chunks, (unsigned)a.BH, 2u);
+    dim3 grid(2u, (unsigned)a.n_chunks, (unsigned)a.BH);
     const size_t lds = (size_t)a.N * kVRow;
     if (a.G == 32) hipLaunchKernelGGL(pack_kernel<32>, grid, dim3(kPackThreads), lds, s, a);
     else           hipLaunchKernelGGL(pack_kernel<64>, grid, dim3(kPackThreads), lds, s, a);
