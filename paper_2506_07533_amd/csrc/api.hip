@@ -196,15 +196,15 @@ int moqae_quantize_pack(const moqae_cfg *cfg,
     return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
 }
 
-int moqae_decode_attn(const moqae_cfg *cfg,
-                      const void *q,
-                      const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
-                      int64_t desc_stride, int32_t n_chunks,
-                      const void *K_tail, const void *V_tail, int32_t n_tail,
-                      float softmax_scale,
-                      float *out,
-                      void *workspace, uint64_t workspace_bytes,
-                      void *stream) {
+static int decode_uniform(const moqae_cfg *cfg,
+                          const void *q,
+                          const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                          int64_t desc_stride, int32_t n_chunks,
+                          const void *K_tail, const void *V_tail, int32_t n_tail,
+                          float softmax_scale,
+                          float *out,
+                          void *workspace, uint64_t workspace_bytes,
+                          void *stream, int planned) {
     if (!cfg_ok(cfg) || !layout_ok(cfg) || !q || !out || !workspace) return MOQAE_E_INVAL;
     if (n_chunks < 0 || n_tail < 0 || n_tail >= cfg->chunk || n_chunks + n_tail <= 0) return MOQAE_E_INVAL;
     if (n_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride < n_chunks)) return MOQAE_E_INVAL;
@@ -218,7 +218,7 @@ int moqae_decode_attn(const moqae_cfg *cfg,
     a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
-    a.seq_chunks = nullptr; a.seq_tail = nullptr;
+    a.seq_chunks = nullptr; a.seq_tail = nullptr; a.planned = planned;
     a.counters = static_cast<unsigned int *>(workspace);
     a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, n_chunks)); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;
@@ -230,6 +230,40 @@ int moqae_decode_attn(const moqae_cfg *cfg,
     for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;
     hipError_t e = launch_attn(a, static_cast<hipStream_t>(stream), g_time_begin, g_time_end);
     return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+int moqae_decode_attn(const moqae_cfg *cfg, const void *q,
+                      const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                      int64_t desc_stride, int32_t n_chunks,
+                      const void *K_tail, const void *V_tail, int32_t n_tail,
+                      float softmax_scale, float *out, void *workspace, uint64_t workspace_bytes, void *stream) {
+    return decode_uniform(cfg, q, arena, chunk_off, expert, desc_stride, n_chunks, K_tail, V_tail, n_tail, softmax_scale,
+                          out, workspace, workspace_bytes, stream, 0);
+}
+
+int moqae_decode_attn_planned(const moqae_cfg *cfg, const void *q,
+                              const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                              int64_t desc_stride, int32_t n_chunks,
+                              const void *K_tail, const void *V_tail, int32_t n_tail,
+                              float softmax_scale, float *out, void *workspace, uint64_t workspace_bytes, void *stream) {
+    return decode_uniform(cfg, q, arena, chunk_off, expert, desc_stride, n_chunks, K_tail, V_tail, n_tail, softmax_scale,
+                          out, workspace, workspace_bytes, stream, 1);
+}
+
+int moqae_decode_plan(const moqae_cfg *cfg, const uint8_t *expert, int64_t desc_stride, int32_t n_chunks,
+                      void *workspace, uint64_t workspace_bytes, void *stream) {
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !workspace || n_chunks < 0) return MOQAE_E_INVAL;
+    if (n_chunks > 0 && (!expert || desc_stride < n_chunks)) return MOQAE_E_INVAL;
+    if (!aligned(workspace, 256)) return MOQAE_E_INVAL;
+    if (workspace_bytes < moqae_decode_workspace_bytes(cfg, n_chunks)) return MOQAE_E_WORKSPACE;
+    AttnArgs a = {};
+    a.expert = expert; a.desc_stride = desc_stride;
+    a.counters = static_cast<unsigned int *>(workspace);
+    a.n_chunks = n_chunks; a.n_tail = cfg->chunk / 2;
+    a.N = cfg->chunk; a.G = cfg->group; a.Hkv = cfg->n_kv_heads; a.rep = cfg->n_q_heads / cfg->n_kv_heads;
+    a.BH = cfg->batch * cfg->n_kv_heads;
+    for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;
+    return launch_attn_plan(a, static_cast<hipStream_t>(stream)) == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
 }
 
 int moqae_decode_attn_ragged(const moqae_cfg *cfg,
@@ -256,7 +290,7 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
     a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
-    a.seq_chunks = n_chunks_seq; a.seq_tail = n_tail_seq;
+    a.seq_chunks = n_chunks_seq; a.seq_tail = n_tail_seq; a.planned = 0;
     a.counters = static_cast<unsigned int *>(workspace);
     a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, max_chunks)); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;

@@ -1375,11 +1375,15 @@ size_t attn_counter_bytes(int BH, int n_chunks, int N) {
 constexpr int kMergeGroups = 8;
 __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const float *__restrict__ part,
                                                                        float *__restrict__ out, int rep,
-                                                                       const uint32_t *__restrict__ row_wgs, int max_partials) {
+                                                                       const uint32_t *__restrict__ row_wgs, int max_partials,
+                                                                       unsigned int *zero_counters, int n_seg) {
     __shared__ float numl[kMergeGroups][kD];
     __shared__ float denl[kMergeGroups], ml[kMergeGroups];
     const int row = (int)blockIdx.x, tid = (int)threadIdx.x, d = tid & (kD - 1), grp = tid >> 7;
     const int u = row / rep;
+    // calls that run on a plan (moqae_decode_plan) leave the ticket counters as they found them: zero
+    if (zero_counters && row % rep == 0)
+        for (int i = tid; i < n_seg; i += kD * kMergeGroups) zero_counters[((size_t)u * n_seg + i) * kCounterStride] = 0u;
     const int P = (int)row_wgs[u];
     const float *p0 = part + (int64_t)row * max_partials * (kD + 2);
     // this group's partials, merged on the way (online rescaling)
@@ -1429,9 +1433,11 @@ template <int G, int REP>
 static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     constexpr int NWV = waves_per_wg<REP>();
     const int n_seg = attn_row_segments(a.n_chunks, a.N);
-    hipLaunchKernelGGL(attn_prep_kernel, dim3((unsigned)a.BH), dim3(256), 0, s, a, n_seg);
-    hipError_t e0 = hipGetLastError();
-    if (e0 != hipSuccess) return e0;
+    if (!a.planned) {
+        hipLaunchKernelGGL(attn_prep_kernel, dim3((unsigned)a.BH), dim3(256), 0, s, a, n_seg);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
     if (ev_begin && hipEventRecord(ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
     if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
     else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
@@ -1440,7 +1446,8 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
     if (ev_end && hipEventRecord(ev_end, s) != hipSuccess) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)(a.BH * a.rep)), dim3(kD * kMergeGroups), 0, s,
                        (const float *)a.part, a.out, a.rep,
-                       (const uint32_t *)(a.counters + (size_t)a.BH * n_seg * kCounterStride + a.BH), a.max_partials);
+                       (const uint32_t *)(a.counters + (size_t)a.BH * n_seg * kCounterStride + a.BH), a.max_partials,
+                       a.planned ? a.counters : (unsigned int *)nullptr, n_seg);
     return hipGetLastError();
 }
 
@@ -1453,6 +1460,13 @@ int attn_resident_wgs_per_cu(int G, int rep) {
     return 1;
 }
 int attn_waves_per_wg(int rep) { (void)rep; return 8; }
+
+// The first kernel of a decode call alone: ticket counters zeroed, the rows' costs (with a nominal residual of half
+// a chunk, so that a row with any token has a cost) and zero workgroup counts left in the workspace.
+hipError_t launch_attn_plan(const AttnArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(attn_prep_kernel, dim3((unsigned)a.BH), dim3(256), 0, s, a, attn_row_segments(a.n_chunks, a.N));
+    return hipGetLastError();
+}
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
 #define MOQAE_CASE(GV, RV) if (a.G == GV && a.rep == RV) return launch_gr<GV, RV>(a, s, ev_begin, ev_end);

@@ -33,8 +33,10 @@ struct AttnArgs {
     unsigned int *counters;     // ticket counters, one per (row, row segment), attn_counter_bytes() in all
     float scale_log2;           // softmax_scale * log2(e)
     int n_chunks, n_tail, n_wg, max_partials, N, G, Hkv, rep, BH;
+    int planned;                // the workspace holds a plan: no prep kernel, the merge kernel zeroes the counters again
     int bits_of[8];
 };
+hipError_t launch_attn_plan(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 int attn_resident_wgs_per_cu(int G, int rep);   // occupancy of the split kernel (host query, cached)
 int attn_waves_per_wg(int rep);

@@ -476,3 +476,42 @@ def test_hot_path_replays_from_a_hip_graph(mq, ref):
         # attention: equal up to the order in which the wavefronts drew their units (grouped queries round their
         # weights to fp16 relative to the running maximum of the moment), far inside the 2e-3 bar
         assert np.isfinite(a).all() and np.abs(a - b).max() <= 2e-4 * np.abs(b).max()
+
+
+# ----------------------------------------------------------------------------------------------
+# decode steps on a plan
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,G,C", [(2, 4, 4, 128, 64, 23), (1, 8, 2, 64, 32, 40), (1, 2, 2, 256, 64, 0)])
+def test_attention_on_a_plan(mq, ref, B, Hq, Hkv, N, G, C):
+    """moqae_decode_plan once, then several moqae_decode_attn_planned calls with a growing residual and new queries:
+    each equals the oracle, and an unplanned call in between (which overwrites the plan) needs a new plan."""
+    rng = np.random.default_rng(C + N)
+    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, (2, 4, 8, 16), 1)
+    K, V = _rand_kv(rng, B, Hkv, C * N + N)
+    expert = rng.integers(0, 4, (B * Hkv, max(C, 1))).astype(np.uint8)
+    scale = 1 / math.sqrt(128)
+    if C > 0:
+        (arena, used, off, status), (arena_ref, used_ref, off_ref, st_ref) = _pack_both(mq, ref, cfg, rcfg, K, V, 0, C, expert)
+        ed = _dev(expert)
+    else:
+        arena = off = ed = None; arena_ref = off_ref = None
+    ws = torch.empty(mq.decode_workspace_bytes(cfg, C), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    out = torch.zeros((B, Hq, 128), dtype=torch.float32, device="cuda")
+    mq.decode_plan(cfg, ed, C, ws)
+    for step, T in enumerate([1, 2, 17, N // 2, N - 1]):
+        q = rng.standard_normal((B, Hq, 128), dtype=np.float32).astype(np.float16)
+        Kt = np.zeros((B, Hkv, N, 128), np.float16); Vt = np.zeros_like(Kt)
+        Kt[:, :, :T] = K[:, :, C * N:C * N + T]; Vt[:, :, :T] = V[:, :, C * N:C * N + T]
+        o_ref = ref.decode_attn(rcfg, q, arena_ref, off_ref, expert if C else None, C, Kt, Vt, T, scale)
+        if step == 3:                                             # an ordinary call uses the workspace its own way
+            mq.decode_attn(cfg, _dev(q), arena, off, ed, C, _dev(Kt), _dev(Vt), T, scale, out, ws)
+            mq.decode_plan(cfg, ed, C, ws)
+        out.fill_(float("nan"))
+        mq.decode_attn(cfg, _dev(q), arena, off, ed, C, _dev(Kt), _dev(Vt), T, scale, out, ws, planned=True)
+        torch.cuda.synchronize()
+        o = out.cpu().numpy().astype(np.float64)
+        assert np.isfinite(o).all()
+        err = (np.abs(o - o_ref).max(-1) / np.abs(o_ref).max(-1)).max()
+        assert err <= ATTN_TOL, (step, err)
