@@ -68,3 +68,11 @@ def test_null_pointers_are_rejected_before_any_launch(mq):
     assert mq.decode_workspace_bytes_ragged(mq.Cfg(1, 8, 8), 16) >= mq.decode_workspace_bytes(mq.Cfg(1, 8, 8), 16)
     assert L.moqae_decode_plan(C.byref(cfg), None, 0, 4, None, 0, None) == mq.E_INVAL
     assert L.moqae_decode_attn_planned(C.byref(cfg), None, None, None, None, 0, 0, None, None, 0, 1.0, None, None, 0, None) == mq.E_INVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; `bench.py --gpus N` with N > 1 says so and exits (before touching any GPU)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
