@@ -162,6 +162,16 @@ int moqae_decode_attn(const moqae_cfg *cfg,
                       void *stream);
 
 /*
+ * The residual of Sec. 3.2 during decode: the new token's key and value rows (k_new, v_new: fp16 [B, Hkv, D],
+ * contiguous) are written to row n_tail (0 <= n_tail < N) of the FP16 residual buffers K_tail, V_tail
+ * (fp16 [B, Hkv, N, D], contiguous), which then hold n_tail + 1 valid rows.  All pointers 16-byte aligned.
+ * When the residual reaches N rows the caller routes and packs it as the next chunk (moqae_route_chunks /
+ * moqae_quantize_pack with the residual buffers as K, V) and starts again at row 0.
+ */
+int moqae_append_tail(const moqae_cfg *cfg, const void *k_new, const void *v_new, void *K_tail, void *V_tail,
+                      int32_t n_tail, void *stream);
+
+/*
  * Decode steps that follow one another on unchanged tables (routing decisions are made once when a chunk is
  * compressed and reused by every later decode step, Sec. 3.2 / 3.4): what the first kernel of moqae_decode_attn
  * derives from the tables -- the cost of every row, zeroed ticket counters -- is the same for all of them.

@@ -52,7 +52,7 @@ _lib = None
 EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "moqae_chunk_block_bytes",
            "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version",
            "moqae_debug_time_decode_kernel", "moqae_decode_attn_ragged", "moqae_decode_workspace_bytes_ragged",
-           "moqae_decode_plan", "moqae_decode_attn_planned"]
+           "moqae_decode_plan", "moqae_decode_attn_planned", "moqae_append_tail"]
 
 
 def lib():
@@ -75,6 +75,8 @@ def lib():
         L.moqae_decode_attn_planned.argtypes = L.moqae_decode_attn.argtypes
         L.moqae_decode_plan.restype = C.c_int
         L.moqae_decode_plan.argtypes = [C.POINTER(_Cfg), vp, i64, i32, vp, u64, vp]
+        L.moqae_append_tail.restype = C.c_int
+        L.moqae_append_tail.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i32, vp]
         L.moqae_decode_attn_ragged.restype = C.c_int
         L.moqae_decode_attn_ragged.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i64, vp, i32, vp, vp, vp, C.c_float, vp,
                                                vp, u64, vp]
@@ -234,3 +236,16 @@ def decode_attn_ragged(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor],
                                           float(softmax_scale), _ptr(out), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream()),
            "moqae_decode_attn_ragged")
+
+
+def append_tail(cfg: Cfg, k_new: torch.Tensor, v_new: torch.Tensor, K_tail: torch.Tensor, V_tail: torch.Tensor,
+                n_tail: int) -> None:
+    """k_new, v_new: fp16 [B, Hkv, D] -> row n_tail of K_tail, V_tail (fp16 [B, Hkv, N, D])."""
+    for t in (k_new, v_new):
+        assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous()
+        assert t.shape == (cfg.batch, cfg.n_kv_heads, cfg.head_dim)
+    for t in (K_tail, V_tail):
+        assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous()
+        assert t.shape == (cfg.batch, cfg.n_kv_heads, cfg.chunk, cfg.head_dim)
+    _check(lib().moqae_append_tail(C.byref(cfg.c()), _ptr(k_new), _ptr(v_new), _ptr(K_tail), _ptr(V_tail), n_tail,
+                                   _stream()), "moqae_append_tail")

@@ -81,8 +81,7 @@ class LayerCache:
     def append(self, k_new: torch.Tensor, v_new: torch.Tensor, router=None, leader: "LayerCache" = None) -> bool:
         """k_new, v_new: fp16 [B, Hkv, D], the new token.  Returns True when a chunk was flushed."""
         N = self.cfg.chunk
-        self.K_tail[:, :, self.n_tail].copy_(k_new)
-        self.V_tail[:, :, self.n_tail].copy_(v_new)
+        mq.append_tail(self.cfg, k_new, v_new, self.K_tail, self.V_tail, self.n_tail)
         self.n_tail += 1
         if self.n_tail < N:
             return False

@@ -232,6 +232,16 @@ static int decode_uniform(const moqae_cfg *cfg,
     return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
 }
 
+int moqae_append_tail(const moqae_cfg *cfg, const void *k_new, const void *v_new, void *K_tail, void *V_tail,
+                      int32_t n_tail, void *stream) {
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !k_new || !v_new || !K_tail || !V_tail) return MOQAE_E_INVAL;
+    if (n_tail < 0 || n_tail >= cfg->chunk) return MOQAE_E_INVAL;
+    if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(K_tail, 16) || !aligned(V_tail, 16)) return MOQAE_E_INVAL;
+    hipError_t e = launch_append_tail(k_new, v_new, K_tail, V_tail, cfg->batch * cfg->n_kv_heads, cfg->chunk, n_tail,
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
 int moqae_decode_attn(const moqae_cfg *cfg, const void *q,
                       const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
                       int64_t desc_stride, int32_t n_chunks,

@@ -23,6 +23,8 @@ struct PackArgs {
     int bits_of[8];
 };
 hipError_t launch_pack(const PackArgs &a, hipStream_t s);
+hipError_t launch_append_tail(const void *k_new, const void *v_new, void *K_tail, void *V_tail, int BH, int N, int n_tail,
+                              hipStream_t s);
 
 struct AttnArgs {
     const uint16_t *q; const uint8_t *arena; const uint64_t *chunk_off; const uint8_t *expert;

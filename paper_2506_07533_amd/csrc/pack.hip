@@ -418,6 +418,22 @@ __global__ void arena_end_kernel(PackArgs a) {
     *a.arena_used = a.chunk_off[lu * a.off_stride + lc] + sz;
 }
 
+// The new token's K and V rows (fp16 [B*Hkv, D]) into row n_tail of the FP16 residual buffers ([B*Hkv, N, D]): one
+// kernel for both, one 16-byte piece per thread.
+__global__ __launch_bounds__(32) void append_tail_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new,
+                                                         uint4 *__restrict__ K_tail, uint4 *__restrict__ V_tail, int N, int n_tail) {
+    const int u = (int)blockIdx.x, t = (int)threadIdx.x;   // 16 pieces of K, 16 of V
+    const size_t dst = ((size_t)u * N + n_tail) * (kD / 8) + (t & 15);
+    if (t < 16) K_tail[dst] = k_new[(size_t)u * (kD / 8) + t];
+    else        V_tail[dst] = v_new[(size_t)u * (kD / 8) + (t & 15)];
+}
+hipError_t launch_append_tail(const void *k_new, const void *v_new, void *K_tail, void *V_tail, int BH, int N, int n_tail,
+                              hipStream_t s) {
+    hipLaunchKernelGGL(append_tail_kernel, dim3((unsigned)BH), dim3(32), 0, s, static_cast<const uint4 *>(k_new),
+                       static_cast<const uint4 *>(v_new), static_cast<uint4 *>(K_tail), static_cast<uint4 *>(V_tail), N, n_tail);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack(const PackArgs &a, hipStream_t s) {
     if (a.n_chunks <= 0 || a.BH <= 0) return hipSuccess;
     const bool rows_ok = a.BH <= kPlanRowsMax &&

@@ -66,6 +66,7 @@ def test_null_pointers_are_rejected_before_any_launch(mq):
     assert L.moqae_decode_attn_ragged(C.byref(cfg), None, None, None, None, 0, None, 4, None, None, None, 1.0, None, None, 0,
                                       None) == mq.E_INVAL
     assert mq.decode_workspace_bytes_ragged(mq.Cfg(1, 8, 8), 16) >= mq.decode_workspace_bytes(mq.Cfg(1, 8, 8), 16)
+    assert L.moqae_append_tail(C.byref(cfg), None, None, None, None, 0, None) == mq.E_INVAL
     assert L.moqae_decode_plan(C.byref(cfg), None, 0, 4, None, 0, None) == mq.E_INVAL
     assert L.moqae_decode_attn_planned(C.byref(cfg), None, None, None, None, 0, 0, None, None, 0, 1.0, None, None, 0, None) == mq.E_INVAL
 

@@ -515,3 +515,19 @@ def test_attention_on_a_plan(mq, ref, B, Hq, Hkv, N, G, C):
         assert np.isfinite(o).all()
         err = (np.abs(o - o_ref).max(-1) / np.abs(o_ref).max(-1)).max()
         assert err <= ATTN_TOL, (step, err)
+
+
+def test_append_tail(mq, ref):
+    """The new token's rows land in row n_tail of both residual buffers and nowhere else."""
+    cfg, _ = _cfgs(mq, ref, 3, 8, 4, 128, 64, (2, 4, 8, 16), 1)
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    Kt = torch.randn((3, 4, 128, 128), generator=g, device="cuda").half(); Vt = torch.randn((3, 4, 128, 128), generator=g, device="cuda").half()
+    for n_tail in (0, 77, 127):
+        kn = torch.randn((3, 4, 128), generator=g, device="cuda").half(); vn = torch.randn((3, 4, 128), generator=g, device="cuda").half()
+        Kr, Vr = Kt.clone(), Vt.clone()
+        Kr[:, :, n_tail] = kn; Vr[:, :, n_tail] = vn
+        mq.append_tail(cfg, kn, vn, Kt, Vt, n_tail)
+        torch.cuda.synchronize()
+        assert torch.equal(Kt, Kr) and torch.equal(Vt, Vr)
+    with pytest.raises(mq.MoqaeError):
+        mq.append_tail(cfg, kn, vn, Kt, Vt, 128)
