@@ -6,10 +6,9 @@
  *                        (router MLP Eq. (1), token top-1 + chunk majority vote
  *                        Eq. (2), Sec. 3.2; routing freezing, Sec. 3.4);
  *   moqae_quantize_pack  group-wise quantisation of every chunk at its routed
- *                        bit-width into a packed arena (Sec. 3.1: chunks "are
- *                        quantized using the bit-width configuration just
- *                        determined"; the residual shorter than a chunk stays
- *                        FP16, Sec. 3.2);
+ *                        bit-width into a packed arena (Sec. 3.1: every chunk is
+ *                        quantised at the bit-width its router chose; the
+ *                        residual shorter than a chunk stays FP16, Sec. 3.2);
  *   moqae_decode_attn    single-token decode attention over the mixed-precision
  *                        cache with de-quantisation on the fly and a full-
  *                        precision softmax (Sec. "Limitations").
@@ -48,7 +47,9 @@
  * Quantiser (per token, per group of G consecutive dims): zero = min,
  *   scale = fp16 round-UP of (max-min)/(2^b-1) (1.0 if max == min),
  *   code = clamp(rint((x-zero) * (1/scale)), 0, 2^b-1), all in binary32 with
- *   round-to-nearest-even.
+ *   round-to-nearest-even.  K and V must be finite fp16 values: an Inf or NaN
+ *   in a group gives that group an Inf / NaN scale and undefined codes (the
+ *   paper's method has no rule for them either).
  */
 #ifndef MOQAE_H
 #define MOQAE_H

@@ -257,10 +257,11 @@ int moqae_route_chunks_ref(const moqae_ref_cfg *cfg,
 }
 
 /* ------------------------------------------------------------------ */
-/* Quantiser (the paper only says the chunk "is quantized using the     */
-/* bit-width configuration just determined"; formula = this build's):   */
+/* Quantiser (Sec. 3.1 only says that a chunk is quantised at the       */
+/* bit-width its router chose; the formula is this build's own):        */
 /* per token row, per group of G consecutive head-dim elements,         */
-/* asymmetric uniform, scale and zero kept as fp16.                     */
+/* asymmetric uniform, scale and zero kept as fp16.  Inputs must be     */
+/* finite: Inf / NaN have no defined codes.                             */
 /* ------------------------------------------------------------------ */
 
 /* One group: x[G] fp16 bit patterns in, codes[G] out, *meta = scale | zero<<16. */

@@ -241,7 +241,8 @@ def _read_words():
         if not t or t[0].startswith("#"):
             continue
         if t[0] == "case":
-            cur = cases.setdefault((t[1], int(t[2])), [])
+            shape = tuple(int(v) for v in t[3:6]) if len(t) >= 6 else (64, 64, 64)
+            cur = cases.setdefault((t[1], int(t[2]), shape), [])
         elif t[0] == "word":
             cur.append((t[1], int(t[2]), int(t[3], 16)))
     return cases
@@ -252,14 +253,21 @@ _GEN = {
     "k_dt_v_d5t": (lambda t, d: (d + t) % 16, lambda t, d: (d + 5 * t) % 16),
     "k_7dt_v_3d11t": (lambda t, d: np.where(d == 0, 0, np.where(d == 1, 255, (7 * d + t) % 256)),
                       lambda t, d: np.where(d == 0, 0, np.where(d == 1, 255, (3 * d + 11 * t) % 256))),
+    # N = D = 128: the V code also depends on the token block, so that swapping block and column tile shows
+    "n128_k_dt_v_3dt": (lambda t, d: (d + t) % 4, lambda t, d: (3 * d + t + t // 64) % 4),
+    "n128_g32_zero": (lambda t, d: (d + t) % 16 + d // 32 + 4 * (t % 4),
+                      lambda t, d: (d + 5 * t + t // 32) % 16 + 2 * (d // 32) + t % 2),
+    "n128_k_7dt_v_3d11t": (lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (7 * d + t) % 256)),
+                           lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (3 * d + 11 * t + t // 32) % 256))),
 }
 
 
 def test_pack_words_golden(ref):
     """A wrong bit position, word order, tile stride or area order moves these words."""
-    N = D = G = 64
-    t, d = np.meshgrid(np.arange(N), np.arange(D), indexing="ij")
-    for (name, bits), probes in _read_words().items():
+    cases = _read_words()
+    assert any(shape[1] == 128 for (_, _, shape) in cases), "no case at the head size the library ships"
+    for (name, bits, (N, D, G)), probes in cases.items():
+        t, d = np.meshgrid(np.arange(N), np.arange(D), indexing="ij")
         cfg = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0)
         fk, fv = _GEN[name]
         blk = ref.pack_chunk(cfg, bits, fk(t, d).astype(np.float16), fv(t, d).astype(np.float16))
@@ -267,6 +275,7 @@ def test_pack_words_golden(ref):
         areas = {"kcodes": 0, "kmeta": cb, "vcodes": cb + mb, "vmeta": 2 * cb + mb}
         assert blk.size == 2 * (cb + mb)
         for area, idx, val in probes:
+            assert 4 * idx < (cb if area.endswith("codes") else mb)
             got = int(blk[areas[area] + 4 * idx: areas[area] + 4 * idx + 4].view("<u4")[0])
             assert got == val, (name, area, idx, hex(got), hex(val))
 
