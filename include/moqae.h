@@ -219,6 +219,26 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
                              void *stream);
 uint64_t moqae_decode_workspace_bytes_ragged(const moqae_cfg *cfg, int32_t max_chunks);   /* host; 0 if cfg invalid */
 
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): moqae_decode_attn without the workspace argument.  The workspace is a fixed array of
+ * moqae_static_scratch_bytes() (8 MiB) that lives inside the library, one copy on every GPU the library is used
+ * on, held until the process ends.  Same arguments otherwise, same result.  MOQAE_E_WORKSPACE if
+ * moqae_decode_workspace_bytes(cfg, n_chunks) exceeds that size (e.g. batch * Hq above about 16 000 query rows);
+ * nothing is launched then.  The call allocates nothing and frees nothing.  All calls on one GPU share the
+ * array: calls that may overlap on one GPU (different streams, different threads) race and must be serialised
+ * by the caller; nothing has to be cleared between calls.
+ */
+int moqae_decode_attn_static(const moqae_cfg *cfg,
+                             const void *q,
+                             const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                             int64_t desc_stride, int32_t n_chunks,
+                             const void *K_tail, const void *V_tail, int32_t n_tail,
+                             float softmax_scale,
+                             float *out,
+                             void *stream);
+uint64_t moqae_static_scratch_bytes(void);                                       /* host */
+
 /* Host helpers (no GPU work). */
 uint64_t moqae_chunk_block_bytes(const moqae_cfg *cfg, int32_t bits);            /* K+V block of one chunk; 0 if invalid */
 uint64_t moqae_arena_upper_bound(const moqae_cfg *cfg, int64_t n_chunks_total);  /* all-16-bit worst case + alignment    */

@@ -52,7 +52,8 @@ _lib = None
 EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "moqae_chunk_block_bytes",
            "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version",
            "moqae_debug_time_decode_kernel", "moqae_decode_attn_ragged", "moqae_decode_workspace_bytes_ragged",
-           "moqae_decode_plan", "moqae_decode_attn_planned", "moqae_append_tail"]
+           "moqae_decode_plan", "moqae_decode_attn_planned", "moqae_append_tail",
+           "moqae_decode_attn_static", "moqae_static_scratch_bytes"]
 
 
 def lib():
@@ -73,6 +74,10 @@ def lib():
                                         vp, u64, vp]
         L.moqae_decode_attn_planned.restype = C.c_int
         L.moqae_decode_attn_planned.argtypes = L.moqae_decode_attn.argtypes
+        L.moqae_decode_attn_static.restype = C.c_int
+        L.moqae_decode_attn_static.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i64, i32, vp, vp, i32, C.c_float, vp, vp]
+        L.moqae_static_scratch_bytes.restype = u64
+        L.moqae_static_scratch_bytes.argtypes = []
         L.moqae_decode_plan.restype = C.c_int
         L.moqae_decode_plan.argtypes = [C.POINTER(_Cfg), vp, i64, i32, vp, u64, vp]
         L.moqae_append_tail.restype = C.c_int
@@ -210,6 +215,32 @@ def decode_attn(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_
               n_chunks, _ptr(K_tail), _ptr(V_tail), n_tail, float(softmax_scale), _ptr(out),
               _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "moqae_decode_attn_planned" if planned else "moqae_decode_attn")
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().moqae_static_scratch_bytes())
+
+
+def decode_attn_static(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_off: Optional[torch.Tensor],
+                       expert: Optional[torch.Tensor], n_chunks: int,
+                       K_tail: Optional[torch.Tensor], V_tail: Optional[torch.Tensor], n_tail: int,
+                       softmax_scale: float, out: torch.Tensor) -> None:
+    """decode_attn on the library's own fixed scratch array (moqae_decode_attn_static): no workspace, no allocation."""
+    assert q.is_cuda and q.dtype == torch.float16 and q.is_contiguous()
+    assert q.shape == (cfg.batch, cfg.n_q_heads, cfg.head_dim)
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+    stride = 0
+    if n_chunks > 0:
+        assert expert.dtype == torch.uint8 and chunk_off.dtype == torch.int64
+        assert expert.shape == chunk_off.shape and expert.is_contiguous() and chunk_off.is_contiguous()
+        stride = expert.shape[1]
+    if n_tail > 0:
+        for t in (K_tail, V_tail):
+            assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous()
+            assert t.shape == (cfg.batch, cfg.n_kv_heads, cfg.chunk, cfg.head_dim)
+    _check(lib().moqae_decode_attn_static(C.byref(cfg.c()), _ptr(q), _ptr(arena), _ptr(chunk_off), _ptr(expert), stride,
+                                          n_chunks, _ptr(K_tail), _ptr(V_tail), n_tail, float(softmax_scale), _ptr(out),
+                                          _stream()), "moqae_decode_attn_static")
 
 
 def decode_attn_ragged(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_off: Optional[torch.Tensor],

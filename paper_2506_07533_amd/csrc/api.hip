@@ -4,8 +4,15 @@
 #include "moqae_dev.hpp"
 #include "moqae_kernels.hpp"
 #include <stdlib.h>
+#include <mutex>
 
 using namespace moqae;
+
+// Scratch memory of moqae_decode_attn_static: the decode workspace (ticket counters, row costs, softmax partials) of
+// callers that cannot allocate.  One copy per GPU the library runs on, held until the process ends.  In host code the
+// array's name is only a stand-in for hipGetSymbolAddress; kernels get the address that call returns.
+#define MOQAE_STATIC_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) unsigned char scratch[MOQAE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -95,6 +102,24 @@ uint64_t workspace_bytes_ragged(const moqae_cfg *c, int max_chunks) {
     const int n_wg = choose_wgs(c, max_chunks, c->chunk - 1);
     const uint64_t rows = (uint64_t)c->batch * c->n_q_heads;
     return counters_bytes(c, max_chunks) + rows * (uint64_t)n_wg * (kD + 2) * sizeof(float);
+}
+
+// Device address of `scratch` on every GPU, looked up once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOQAE_E_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MOQAE_E_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOQAE_OK;
 }
 
 thread_local hipEvent_t g_time_begin = nullptr, g_time_end = nullptr;   // measurement aid, see moqae.h
@@ -250,6 +275,22 @@ int moqae_decode_attn(const moqae_cfg *cfg, const void *q,
     return decode_uniform(cfg, q, arena, chunk_off, expert, desc_stride, n_chunks, K_tail, V_tail, n_tail, softmax_scale,
                           out, workspace, workspace_bytes, stream, 0);
 }
+
+int moqae_decode_attn_static(const moqae_cfg *cfg, const void *q,
+                             const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                             int64_t desc_stride, int32_t n_chunks,
+                             const void *K_tail, const void *V_tail, int32_t n_tail,
+                             float softmax_scale, float *out, void *stream) {
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || n_chunks < 0) return MOQAE_E_INVAL;
+    if (workspace_bytes(cfg, n_chunks) > (uint64_t)MOQAE_STATIC_SCRATCH_BYTES) return MOQAE_E_WORKSPACE;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != MOQAE_OK) return rc;
+    return decode_uniform(cfg, q, arena, chunk_off, expert, desc_stride, n_chunks, K_tail, V_tail, n_tail, softmax_scale,
+                          out, ws, MOQAE_STATIC_SCRATCH_BYTES, stream, 0);
+}
+
+uint64_t moqae_static_scratch_bytes(void) { return MOQAE_STATIC_SCRATCH_BYTES; }
 
 int moqae_decode_attn_planned(const moqae_cfg *cfg, const void *q,
                               const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
