@@ -8,8 +8,13 @@ the timed region.  The decode call of step i reads the arena packed in step i-1 
 alternate), so the 256 MB last-level cache cannot hold what it reads.
 
 Prints ONE JSON line: metric = decode-attention HBM GB/s (algorithmic packed bytes / time of
-the whole decode call, made on the plan that was left in its workspace when the cache was packed), `roofline` for its main kernel timed alone, route+pack chunks/s with a
-roofline object each, and the CPU oracle timed on a sample of the same workload.
+the whole decode call, made on the plan that was left in its workspace when the cache was packed),
+`roofline` for its main kernel timed alone (HIP events the library records around it), the same
+call without a plan (`decode_call_unplanned` = moqae_decode_attn), `stream_ceiling` = what a plain
+read-only streaming kernel reaches on the same GPU, route+pack chunks/s with a roofline object
+each, and the CPU oracle timed on the same workload.  The timed steps rotate over three kinds (whole
+planned call / main kernel alone / whole unplanned call), so the default 150 steps give 50 samples
+of each; averages, medians and minima are reported.
 """
 from __future__ import annotations
 
@@ -27,10 +32,23 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 
-# HBM bytes per decode call (attn_split_kernel + attn_merge_kernel, fetched + written) from the rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_<workload>.md; counters cannot be read
-# from inside this process, so a workload without such a run reports null.
-MEASURED_TRAFFIC = {"llama13b_128k": 693653741}
+# What the decode contraction computes in (the `dtype` of the JSON line): one query head per KV head: code bytes
+# times base-128 digits of a 21-bit fixed-point copy of q / of the softmax weights on v_mfma_i32_16x16x64_i8, exact
+# integer sums; grouped queries: fp16 code fields times fp16 weights on v_mfma_f32_16x16x32_f16; softmax and all
+# accumulation in binary32 (no narrower than the FP16 de-quantisation of the paper's "Limitations" section).
+DTYPE = {1: "i8-mfma fixed-point 21b / f32 accumulate", 0: "f16-mfma / f32 accumulate"}
+
+
+def measured_traffic(workload):
+    """HBM bytes per decode call (fetched + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+    profiles/hbm_traffic_<workload>.md (its line `traffic_bytes_per_decode_call: N`); counters cannot be read from
+    inside this process, so a workload without such a summary reports null."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.md")
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_decode_call:"):
+                return int(line.split(":")[1].split()[0])
+    return None
 
 
 def log(*a):
@@ -65,8 +83,8 @@ class HipEvents:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 150 for one layer, 10 for the stack)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 5; 2 for the stack)")
     ap.add_argument("--workload", default="llama13b_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-only", action="store_true",
@@ -102,6 +120,11 @@ def main() -> int:
     from paper_2506_07533_amd import synth
 
     w = synth.WORKLOADS[args.workload]
+    stack_like = w.n_layers > 1 or args.sweep == "share"
+    if args.steps is None:
+        args.steps = 10 if stack_like else 150
+    if args.warmup is None:
+        args.warmup = 2 if stack_like else 5
     if args.sweep == "chunk":
         if w.n_layers > 1:
             print("bench.py: --sweep chunk takes a single-layer workload", file=sys.stderr)
@@ -185,9 +208,11 @@ def bench_layer(args, w):
 
     hev = HipEvents(args.steps)
     L = mq.lib()
+    ws_unplanned = torch.zeros(mq.decode_workspace_bytes(cfg, C), dtype=torch.uint8, device=dev)
 
     def step(i, ev=None, k=None):
         a = i & 1
+        kind = None if k is None else k % 3              # 0: planned call, 1: its main kernel alone, 2: unplanned call
         useds[a].zero_()
         if ev: ev[0].record()
         if not args.decode_only:
@@ -197,10 +222,14 @@ def bench_layer(args, w):
             mq.quantize_pack(cfg, K, V, 0, C, expert, arenas[a], useds[a], offs[a], status)
             mq.decode_plan(cfg, expert, C, wss[a])       # counted with the pack call
         if ev: ev[2].record()
-        if k is not None and (k & 1): L.moqae_debug_time_decode_kernel(*hev.pair(k))   # odd steps: the main kernel alone
-        mq.decode_attn(cfg, q, arenas[a ^ 1], offs[a ^ 1], expert, C, Kt if T else None, Vt if T else None, T,
-                       scale, out, wss[a ^ 1], planned=True)
-        if k is not None and (k & 1): L.moqae_debug_time_decode_kernel(None, None)
+        if kind == 1: L.moqae_bench_time_decode_kernel(*hev.pair(k))
+        if kind == 2:
+            mq.decode_attn(cfg, q, arenas[a ^ 1], offs[a ^ 1], expert, C, Kt if T else None, Vt if T else None, T,
+                           scale, out, ws_unplanned)
+        else:
+            mq.decode_attn(cfg, q, arenas[a ^ 1], offs[a ^ 1], expert, C, Kt if T else None, Vt if T else None, T,
+                           scale, out, wss[a ^ 1], planned=True)
+        if kind == 1: L.moqae_bench_time_decode_kernel(None, None)
         if ev: ev[3].record()
 
     for a in range(2):                                   # both arenas packed before anything is timed
@@ -222,10 +251,11 @@ def bench_layer(args, w):
     assert int(status.item()) == 0, "arena overflow"
     t_route = np.array([e[0].elapsed_time(e[1]) for e in evs])
     t_pack = np.array([e[1].elapsed_time(e[2]) for e in evs])
-    # the whole decode call (three kernels) on the even steps, where nothing else is recorded inside it;
-    # its main kernel alone on the odd steps
-    t_attn = np.array([e[2].elapsed_time(e[3]) for i, e in enumerate(evs) if not (i & 1)])
-    t_split = np.array([hev.elapsed_ms(i) for i in range(args.steps) if i & 1]) if args.steps > 1 else t_attn
+    # the whole planned call (two kernels) on steps 0, 3, ..., where nothing else is recorded inside it; its main
+    # kernel alone on steps 1, 4, ...; the whole unplanned call (three kernels) on steps 2, 5, ...
+    t_attn = np.array([e[2].elapsed_time(e[3]) for i, e in enumerate(evs) if i % 3 == 0])
+    t_split = np.array([hev.elapsed_ms(i) for i in range(args.steps) if i % 3 == 1]) if args.steps > 1 else t_attn
+    t_unpl = np.array([e[2].elapsed_time(e[3]) for i, e in enumerate(evs) if i % 3 == 2]) if args.steps > 2 else t_attn
     ms_per_step = wall_ms / args.steps
 
     n_units = BH * C
@@ -244,7 +274,7 @@ def bench_layer(args, w):
     res = {
         "metric": "decode_attn_hbm_GBps", "value": None, "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": DTYPE[1 if w.n_q_heads == w.n_kv_heads else 0], "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "cached_tokens": w.seq, "chunk": w.chunk, "group": w.group,
                    "expert_bits": list(w.expert_bits), "realised_mix": mix, "chunks": n_units,
@@ -253,11 +283,15 @@ def bench_layer(args, w):
         "roofline": dict(roof(attn_bytes, t_split), kernel="attn_split_kernel"),
         # the decode call as a whole (moqae_decode_attn_planned): attn_split_kernel + attn_merge_kernel and the gap; the
         # plan of the tables is made once per packed cache (with the pack call above), not per decode step
-        "decode_call": roof(attn_bytes, t_attn),
+        "decode_call": dict(roof(attn_bytes, t_attn), entry_point="moqae_decode_attn_planned", samples=int(t_attn.size)),
+        # the same call with the plan made inside it (moqae_decode_attn: attn_prep_kernel + the two kernels above)
+        "decode_call_unplanned": dict(roof(attn_bytes, t_unpl), entry_point="moqae_decode_attn", samples=int(t_unpl.size)),
         "pct_of_hbm_peak": None,
     }
+    res["roofline"]["samples"] = int(t_split.size)
+    res["stream_ceiling"] = stream_ceiling(mq, dev)
     if not args.force_bits:
-        res["roofline"]["traffic"] = MEASURED_TRAFFIC.get(w.name)
+        res["roofline"]["traffic"] = measured_traffic(w.name)
     res["value"] = res["decode_call"]["achieved"]
     res["pct_of_hbm_peak"] = round(100 * res["decode_call"]["frac"], 2)
     if not args.decode_only:
@@ -270,6 +304,32 @@ def bench_layer(args, w):
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, scale)
     return res
+
+
+def stream_ceiling(mq, dev):
+    """What a plain read-only streaming kernel (csrc/stream_probe.hip: 16-byte loads, 2 GiB read once per launch,
+    eight times the 256 MB last-level cache) reaches on this GPU: the practical ceiling of any read-bound kernel."""
+    import ctypes as C
+    import torch
+    L = mq.lib()
+    L.moqae_bench_stream_sink_words.restype = C.c_uint32
+    L.moqae_bench_stream_read.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
+    nbytes = 2 << 30
+    buf = torch.zeros(nbytes // 4, dtype=torch.int32, device=dev)
+    sink = torch.zeros(int(L.moqae_bench_stream_sink_words()), dtype=torch.int32, device=dev)
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    n = 20
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for i in range(3 + n):
+        if i >= 3: ev[i - 3][0].record()
+        assert L.moqae_bench_stream_read(C.c_void_p(buf.data_ptr()), nbytes, C.c_void_p(sink.data_ptr()), st) == 0
+        if i >= 3: ev[i - 3][1].record()
+    torch.cuda.synchronize()
+    t = np.array([a.elapsed_time(b) for a, b in ev])
+    g = nbytes / (np.median(t) * 1e-3) / 1e9
+    return {"achieved": round(float(g), 1), "unit": "GB/s", "frac_of_peak": round(float(g / HBM_PEAK_GBPS), 4),
+            "bytes_per_launch": nbytes, "median_ms": round(float(np.median(t)), 4), "min_ms": round(float(t.min()), 4),
+            "kernel": "stream_read_kernel (read-only, 16-byte loads)", "samples": n}
 
 
 def bench_stack(args, w):
@@ -352,7 +412,7 @@ def bench_stack(args, w):
     res = {
         "metric": "decode_attn_hbm_GBps", "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms / args.steps, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": DTYPE[1 if w.n_q_heads == H else 0], "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "q_heads": w.n_q_heads, "kv_heads": H, "head_dim": D,
                    "cached_tokens": w.seq, "chunk": N, "group": w.group, "layers": w.n_layers,
                    "routing_sharing_group": w.share_group, "chunks": n_units, "packed_bytes": packed,
@@ -428,7 +488,7 @@ def bench_ragged(args):
     g_r = bytes_r / (t_r.mean() * 1e-3) / 1e9; g_u = bytes_u / (t_u.mean() * 1e-3) / 1e9
     return {"metric": "decode_attn_hbm_GBps", "value": round(g_r, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": round(float(t_r.mean()), 4), "higher_is_better": True, "scaling": "weak",
-            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "vs_baseline": None, "dtype": DTYPE[1], "data": "synthetic",
             "config": {"workload": w.name, "batch": B, "q_heads": w.n_q_heads, "kv_heads": H, "head_dim": D, "chunk": N,
                        "group": w.group, "chunks_per_sequence": lens_c, "residual_rows": lens_t, "packed_bytes_read": bytes_r},
             "roofline": {"bound": "hbm", "achieved": round(g_r, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -443,7 +503,9 @@ def cpu_baseline(w, d, scale):
     """The CPU oracle as it stands, timed on the first KV heads of the same workload."""
     from oracle import moqae_ref as R
     threads = R.num_threads()
-    Hs = min(w.batch * w.n_kv_heads if w.batch == 1 else w.n_kv_heads, max(1, 2 * threads))   # two rows per thread
+    # every (sequence 0, KV head) row when that is at most four per thread (about 10 s of CPU work at 128k tokens), else two per thread
+    rows0 = w.batch * w.n_kv_heads if w.batch == 1 else w.n_kv_heads
+    Hs = rows0 if rows0 <= 4 * threads else max(1, 2 * threads)
     rep = w.n_q_heads // w.n_kv_heads
     C, T = w.n_chunks, w.n_tail
     rcfg = R.RefCfg(1, Hs * rep, Hs, w.head_dim, w.chunk, w.group, w.expert_bits, w.freeze_chunks)

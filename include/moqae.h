@@ -239,20 +239,12 @@ int moqae_decode_attn_static(const moqae_cfg *cfg,
                              void *stream);
 uint64_t moqae_static_scratch_bytes(void);                                       /* host */
 
-/* Host helpers (no GPU work). */
+/* Host helpers (no GPU work; moqae_decode_workspace_bytes* read the number of compute units of the current device). */
 uint64_t moqae_chunk_block_bytes(const moqae_cfg *cfg, int32_t bits);            /* K+V block of one chunk; 0 if invalid */
 uint64_t moqae_arena_upper_bound(const moqae_cfg *cfg, int64_t n_chunks_total);  /* all-16-bit worst case + alignment    */
 uint64_t moqae_decode_workspace_bytes(const moqae_cfg *cfg, int32_t n_chunks);   /* 0 if cfg invalid                     */
 const char *moqae_strerror(int code);
 uint32_t moqae_abi_version(void);
-
-/*
- * Measurement aid, not part of the method: the decode calls this host thread makes from now on record
- * the two given events (hipEvent_t passed as void*, owned by the caller, created with timing enabled)
- * on the call's stream right before and right after the main kernel of moqae_decode_attn, so that a
- * benchmark can time that kernel alone, as a profiler does.  Pass NULL, NULL to stop.  Returns MOQAE_OK.
- */
-int moqae_debug_time_decode_kernel(void *event_begin, void *event_end);
 
 #ifdef __cplusplus
 }

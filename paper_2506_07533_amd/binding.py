@@ -51,9 +51,11 @@ class Cfg:
 _lib = None
 EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "moqae_chunk_block_bytes",
            "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version",
-           "moqae_debug_time_decode_kernel", "moqae_decode_attn_ragged", "moqae_decode_workspace_bytes_ragged",
+           "moqae_decode_attn_ragged", "moqae_decode_workspace_bytes_ragged",
            "moqae_decode_plan", "moqae_decode_attn_planned", "moqae_append_tail",
            "moqae_decode_attn_static", "moqae_static_scratch_bytes"]
+# measurement aids of include/moqae_bench.h (bench.py only)
+BENCH_EXPORTS = ["moqae_bench_time_decode_kernel", "moqae_bench_stream_read", "moqae_bench_stream_sink_words"]
 
 
 def lib():

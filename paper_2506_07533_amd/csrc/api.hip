@@ -1,9 +1,9 @@
 // C-ABI entry points of libmoqae: argument validation on the host, then kernel launches on the
 // caller's stream.  No allocation and no synchronisation happen here.
 #include "../../include/moqae.h"
+#include "../../include/moqae_bench.h"
 #include "moqae_dev.hpp"
 #include "moqae_kernels.hpp"
-#include <stdlib.h>
 #include <mutex>
 
 using namespace moqae;
@@ -65,17 +65,12 @@ int cu_count() {
     return cus;
 }
 
-// Persistent workgroups of the decode kernel: one per resident slot of the chip, but never more
-// than there are tickets of 128 tokens to hand to their wavefronts.  MOQAE_DECODE_WGS_PER_CU
-// overrides the occupancy query (tuning aid).
+// Persistent workgroups of the decode kernel: one per compute unit (its eight wavefronts of up to 256
+// registers and its LDS tables fill one), but never more than there are tickets of 128 tokens to hand to
+// their wavefronts.  The only device query is the number of compute units of the current device.
 int choose_wgs(const moqae_cfg *c, int n_chunks, int n_tail) {
-    static int override_wgs = -1;
-    if (override_wgs < 0) {
-        const char *e = getenv("MOQAE_DECODE_WGS_PER_CU");
-        override_wgs = e ? atoi(e) : 0;
-    }
     const int rep = c->n_q_heads / c->n_kv_heads;
-    const int per_cu = override_wgs > 0 ? override_wgs : attn_resident_wgs_per_cu(c->group, rep);
+    const int per_cu = 1;
     const int64_t rows = (int64_t)c->batch * c->n_kv_heads;
     const int64_t tickets = rows * ((int64_t)n_chunks * (c->chunk >= 256 ? c->chunk / 128 : 1) + (n_tail + 127) / 128);
     int64_t n = (int64_t)cu_count() * per_cu;
@@ -122,13 +117,13 @@ int static_scratch(void **out) {
     return MOQAE_OK;
 }
 
-thread_local hipEvent_t g_time_begin = nullptr, g_time_end = nullptr;   // measurement aid, see moqae.h
+thread_local hipEvent_t g_time_begin = nullptr, g_time_end = nullptr;   // measurement aid, see moqae_bench.h
 
 }  // namespace
 
 extern "C" {
 
-int moqae_debug_time_decode_kernel(void *event_begin, void *event_end) {
+int moqae_bench_time_decode_kernel(void *event_begin, void *event_end) {
     g_time_begin = static_cast<hipEvent_t>(event_begin); g_time_end = static_cast<hipEvent_t>(event_end);
     return MOQAE_OK;
 }

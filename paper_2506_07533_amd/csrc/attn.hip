@@ -161,12 +161,15 @@ template <int G> struct VRegs {
 };
 
 // Loads through a scalar base plus a 32-bit per-lane byte offset (no 64-bit vector address
-// arithmetic: the base of every KiB is computed on the scalar unit).
+// arithmetic: the base of every KiB is computed on the scalar unit).  The cache is read exactly once
+// per call, so every load of it is a streaming (nontemporal) load: a plain read-only kernel moves
+// 6.9 TB/s with them on this chip and 6.0 TB/s with ordinary loads.
 __device__ __forceinline__ uint4 ld16(const uint8_t *sbase, uint32_t voff) {
-    return *reinterpret_cast<const uint4 *>(sbase + voff);
+    const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(sbase + voff));
+    return uint4{v[0], v[1], v[2], v[3]};
 }
 __device__ __forceinline__ uint32_t ld4(const uint8_t *sbase, uint32_t voff) {
-    return *reinterpret_cast<const uint32_t *>(sbase + voff);
+    return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(sbase + voff));
 }
 
 // The V side: the 16-byte slots 64*j + l of the unit's V KiBs and its (token, group) meta
@@ -340,7 +343,9 @@ __device__ __forceinline__ v4f mfma16(v4u a, v4u b, v4f c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
 }
 __device__ __forceinline__ uint2 ld8(const uint8_t *sbase, uint32_t voff) {
-    return *reinterpret_cast<const uint2 *>(sbase + voff);
+    typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+    const v2u v = __builtin_nontemporal_load(reinterpret_cast<const v2u *>(sbase + voff));
+    return uint2{v[0], v[1]};
 }
 // the k-th fp16 pair of a code word, left where it lies (scaled by 2^pair_exp(k))
 template <int BITS> __device__ __forceinline__ uint32_t pair_reg(uint32_t w, int k) {
@@ -1417,19 +1422,6 @@ __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const floa
 template <int REP> constexpr int waves_per_wg() { return 8; }
 
 template <int G, int REP>
-static int resident_wgs_per_cu() {
-    static int cached = 0;
-    if (cached == 0) {
-        int n = 0;
-        constexpr int NWV = waves_per_wg<REP>();
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_split_kernel<G, REP, NWV, false>, NWV * 64, 0) != hipSuccess || n < 1)
-            n = 1;
-        cached = n;
-    }
-    return cached;
-}
-
-template <int G, int REP>
 static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     constexpr int NWV = waves_per_wg<REP>();
     const int n_seg = attn_row_segments(a.n_chunks, a.N);
@@ -1453,12 +1445,6 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
 
 #define MOQAE_FOR_EACH_VARIANT(X) X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(32, 1) X(32, 2) X(32, 4)
 
-int attn_resident_wgs_per_cu(int G, int rep) {
-#define MOQAE_CASE(GV, RV) if (G == GV && rep == RV) return resident_wgs_per_cu<GV, RV>();
-    MOQAE_FOR_EACH_VARIANT(MOQAE_CASE)
-#undef MOQAE_CASE
-    return 1;
-}
 int attn_waves_per_wg(int rep) { (void)rep; return 8; }
 
 // The first kernel of a decode call alone: ticket counters zeroed, the rows' costs (with a nominal residual of half

@@ -40,7 +40,6 @@ struct AttnArgs {
 };
 hipError_t launch_attn_plan(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
-int attn_resident_wgs_per_cu(int G, int rep);   // occupancy of the split kernel (host query, cached)
 int attn_waves_per_wg(int rep);
 int attn_max_partials(int n_wg, int BH);        // partial slots per row
 size_t attn_counter_bytes(int BH, int n_chunks, int N); // bytes of the ticket counters at the start of the workspace

@@ -130,12 +130,15 @@ constexpr int kPlanRowsMax = 1024;
 __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(PackArgs a) {
     __shared__ uint32_t rowtot[kPlanRowsMax];         // block bytes of every row, in units of 256 bytes
     __shared__ unsigned long long wsum[kPlanThreads / 64];
-    __shared__ int bad;
+    __shared__ int bad, status_in;
     const int tid = (int)threadIdx.x, u_own = (int)blockIdx.x;
-    if (*a.status != 0) return;                       // sticky error: the call is a no-op
+    // One read of the status word per workgroup: workgroup 0 may set it while a workgroup that starts later is
+    // reading it, and all wavefronts of a workgroup must take the same way out.  (A workgroup that still sees 0
+    // reaches the same verdict as workgroup 0 by itself and writes nothing either.)
+    if (tid == 0) { status_in = *a.status; bad = 0; }
     for (int i = tid; i < a.BH; i += kPlanThreads) rowtot[i] = 0;
-    if (tid == 0) bad = 0;
     __syncthreads();
+    if (status_in != 0) return;                       // sticky error: the call is a no-op
 
     uint32_t size_of[8];
     unsigned long long lut = 0;                       // size_of[e] in 16-bit field e (a block is < 2^16 * 256 bytes)

@@ -19,12 +19,13 @@ def mq():
 
 
 def test_every_declared_symbol_is_exported(mq):
-    header = open(os.path.join(ROOT, "include", "moqae.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = sorted(set(re.findall(r"\b(moqae_[a-z_0-9]+)\s*\(", header)))
-    assert declared == sorted(mq.EXPORTS)
-    for name in declared:
-        assert getattr(mq.lib(), name) is not None
+    for fname, exports in (("moqae.h", mq.EXPORTS), ("moqae_bench.h", mq.BENCH_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", fname)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared = sorted(set(re.findall(r"\b(moqae_[a-z_0-9]+)\s*\(", header)))
+        assert declared == sorted(exports), fname
+        for name in declared:
+            assert getattr(mq.lib(), name) is not None
     assert mq.abi_version() == 1
     assert "arena" in mq.strerror(mq.E_ARENA) and mq.strerror(0) == "ok"
 

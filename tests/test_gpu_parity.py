@@ -212,6 +212,39 @@ def test_pack_subrange_append_and_status(mq, ref):
     assert int(status.item()) == mq.E_INVAL and int(used2.item()) == 0
 
 
+@pytest.mark.parametrize("BH", [700, 1500])           # more rows than workgroups resident at once; above 1024: the one-workgroup plan
+def test_pack_status_with_many_rows(mq, ref, BH):
+    """An undersized arena with many (sequence, KV head) rows: every workgroup of the plan must reach the same
+    verdict, whenever it starts: status -3, no offset, no arena byte, arena_used unchanged; then the same
+    call on a large enough arena equals the oracle."""
+    rng = np.random.default_rng(BH)
+    N, G, C = 64, 64, 17
+    cfg, rcfg = _cfgs(mq, ref, BH, 1, 1, N, G, (2, 4, 8, 16), 0)
+    K = rng.standard_normal((BH, 1, C * N, 128), dtype=np.float32).astype(np.float16)
+    V = rng.standard_normal((BH, 1, C * N, 128), dtype=np.float32).astype(np.float16)
+    expert = rng.integers(0, 4, (BH, C)).astype(np.uint8)
+    need = int(sum(ref.chunk_block_bytes(rcfg, (2, 4, 8, 16)[e]) for e in expert.ravel()))
+    Kd, Vd, ed = _dev(K), _dev(V), _dev(expert)
+    small = torch.zeros(need - 256, dtype=torch.uint8, device="cuda")
+    used = torch.full((1,), 0, dtype=torch.int64, device="cuda"); status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    off = torch.full((BH, C), 77, dtype=torch.int64, device="cuda")
+    for _ in range(3):                                                  # the verdict may not depend on timing
+        status.zero_()
+        mq.quantize_pack(cfg, Kd, Vd, 0, C, ed, small, used, off, status)
+        torch.cuda.synchronize()
+        assert int(status.item()) == mq.E_ARENA and int(used.item()) == 0
+        assert (off == 77).all().item() and not small.any().item()
+    status.zero_()
+    arena = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    mq.quantize_pack(cfg, Kd, Vd, 0, C, ed, arena, used, off, status)
+    torch.cuda.synchronize()
+    arena_ref = np.zeros(need, np.uint8); used_ref = np.zeros(1, np.uint64); off_ref = np.zeros((BH, C), np.uint64)
+    assert ref.quantize_pack(rcfg, K, V, 0, C, expert, arena_ref, used_ref, off_ref) == 0
+    assert int(status.item()) == 0 and int(used.item()) == int(used_ref[0]) == need
+    assert np.array_equal(off.cpu().numpy().astype(np.uint64), off_ref)
+    assert np.array_equal(arena.cpu().numpy(), arena_ref)
+
+
 # ----------------------------------------------------------------------------------------------
 # decode attention
 # ----------------------------------------------------------------------------------------------
