@@ -418,12 +418,23 @@ __device__ __forceinline__ void load_k_mc(const Unit &u, int lane, KRegsMC<G, RE
     const uint32_t lane_off = raw ? (uint32_t)lane * 16u : (((uint32_t)x << rbsh) + ((uint32_t)qd << (rbsh - 2)));
     const int iptsh = raw ? 1 : u.lgb - 1;                // log2(loads per tile); raw: per KiB
     const int tbsh = raw ? 10 : rbsh + 4;                 // log2(bytes per tile); raw: a KiB
-    const int imax = 2 * u.nsub - 1;
+    // A streaming load drops its 128-byte line after use, so every line must be covered by ONE load instruction:
+    // 8-byte pieces only at 2 bits (a quarter row is 8 bytes; the 16 lanes of a quarter cover whole lines together),
+    // 16-byte pieces otherwise (a quarter row is 16 bytes at 4 bits, 32 bytes = two adjacent pieces at 8 bits).
+    if (u.lgb == 1) {
+        const int imax = 2 * u.nsub - 1;
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const int ic = min(i, imax);
-        const uint2 t = ld8(u.kb, u.kc + lane_off + (((uint32_t)(ic >> iptsh) << tbsh) + (uint32_t)(ic & ((1 << iptsh) - 1)) * 8u));
-        if (i & 1) { k.c[i >> 1].z = t.x; k.c[i >> 1].w = t.y; } else { k.c[i >> 1].x = t.x; k.c[i >> 1].y = t.y; }
+        for (int i = 0; i < 8; i++) {
+            const int ic = min(i, imax);
+            const uint2 t = ld8(u.kb, u.kc + lane_off + (((uint32_t)(ic >> iptsh) << tbsh) + (uint32_t)(ic & ((1 << iptsh) - 1)) * 8u));
+            if (i & 1) { k.c[i >> 1].z = t.x; k.c[i >> 1].w = t.y; } else { k.c[i >> 1].x = t.x; k.c[i >> 1].y = t.y; }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const uint32_t jc = (uint32_t)min(j, u.nsub - 1);
+            k.c[j] = ld16(u.kb, u.kc + lane_off + (u.lgb == 3 ? (jc >> 1) * 2048u + (jc & 1u) * 16u : jc * 1024u));
+        }
     }
     const int TU = raw ? 16 : (u.nsub << (6 - u.lgb));    // tokens of the unit
 #pragma unroll

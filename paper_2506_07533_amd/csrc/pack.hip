@@ -277,6 +277,7 @@ __device__ __forceinline__ void pack_item(const uint4 *__restrict__ p, bool isV,
     uint32_t w[NW];
 #pragma unroll
     for (int j = 0; j < G / 8; j++) {                // the whole item is requested at once: its 128-byte line arrives once
+        // (ordinary loads: the lane's eight loads share the line through the cache; streaming loads here fetch it eight times)
         const uint4 t = p[j];
         w[4 * j] = t.x; w[4 * j + 1] = t.y; w[4 * j + 2] = t.z; w[4 * j + 3] = t.w;
     }
