@@ -32,15 +32,17 @@
  *            16*(e%2) + b*(e/2);
  *            K codes: token-major rows of D*b/32 words, dim d -> word d/(32/b),
  *                     in-word index d%(32/b);
- *            V codes: dimension-major 1-KiB tiles of 64 slots x 4 words.  With
- *                     TW = 32/b tokens per word, a slot holds a slice of
+ *            V codes: dimension-major tiles of up to 64 slots x 4 words (1 KiB).
+ *                     With TW = 32/b tokens per word, a slot holds a slice of
  *                     TQ = max(TW, 8) consecutive tokens of one dim (WD = TQ/TW
- *                     words) for CPK = 4/WD dims that lie 16 apart.  Token t:
- *                     block t/(4*TQ), slice qd = (t % (4*TQ))/TQ, word
- *                     w = (t % TQ)/TW, in-word index t % TW.  Dim d = 16*ct + j:
- *                     tile cg = ct/CPK of the block, slot 16*qd + j, word
- *                     n = (ct % CPK)*WD + w; word index in the area =
- *                     ((block*D/(16*CPK) + cg)*64 + 16*qd + j)*4 + n;
+ *                     words) for CPK = 4/WD dims that lie 16 apart.  A token block
+ *                     is TB = min(4*TQ, N) tokens = QD = TB/TQ slices (QD = 4; only
+ *                     32-token chunks at 2 bits have QD = 2: the chunk is one block
+ *                     and a tile has 32 slots).  Token t: block t/TB, slice
+ *                     qd = (t % TB)/TQ, word w = (t % TQ)/TW, in-word index t % TW.
+ *                     Dim d = 16*ct + j: tile cg = ct/CPK of the block, slot
+ *                     16*qd + j, word n = (ct % CPK)*WD + w; word index in the area =
+ *                     ((block*D/(16*CPK) + cg)*16*QD + 16*qd + j)*4 + n;
  *            meta area = one 32-bit word per (token, group), token-major:
  *                     fp16 scale | fp16 zero << 16;  x^ = code*scale + zero.
  *   b = 16 : [K rows | V rows], raw fp16, token-major.
@@ -77,8 +79,9 @@ typedef struct {
                                query head hq reads KV head hq / (Hq/Hkv)                       */
     int32_t n_kv_heads;     /* Hkv                                                             */
     int32_t head_dim;       /* D, must be 128                                                  */
-    int32_t chunk;          /* N tokens per chunk, 32..256: a multiple of 32 for routing, of 64
-                               for pack and decode (a V tile spans 64 tokens)                  */
+    int32_t chunk;          /* N tokens per chunk, 32..256: a multiple of 32 for routing; 32 (the
+                               paper's default, Sec. 4.1) or a multiple of 64 for pack and decode
+                               (the V token blocks span 64 tokens at 2 bits)                    */
     int32_t group;          /* G elements per quantisation group along D: 32 or 64             */
     int32_t n_experts;      /* M, 1..8                                                         */
     int32_t expert_bits[MOQAE_MAX_EXPERTS]; /* B_j in {2,4,8,16}; index order = tie-break order */

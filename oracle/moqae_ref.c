@@ -300,37 +300,40 @@ void moqae_ref_quantize_group(const uint16_t *x, int G, int bits, uint8_t *codes
  *
  * K codes: token-major rows.  Row t holds D*b/32 words; in-row word d / n,
  *          in-word index d % n.
- * V codes: dimension-major inside blocks of tokens, cut into 1-KiB tiles of
- *          64 slots x 4 words.  With TW = 32/b tokens per word, a slot holds
- *          a slice of TQ = max(TW, 8) consecutive tokens of one dimension
- *          (WD = TQ/TW words) for CPK = 4/WD dimensions that lie 16 apart.
- *          A token block is TB = 4*TQ tokens; token t of the chunk sits in
- *          block t / TB, slice qd = (t % TB) / TQ, and inside the slice in
- *          word w = (t % TQ) / TW at in-word index e = t % TW.
- *          Dimension d = 16*ct + j belongs to tile cg = ct / CPK of its
- *          block (D / (16*CPK) tiles per block), slot 16*qd + j, word
+ * V codes: dimension-major inside blocks of tokens, cut into tiles of up to
+ *          64 slots x 4 words (1 KiB).  With TW = 32/b tokens per word, a slot
+ *          holds a slice of TQ = max(TW, 8) consecutive tokens of one
+ *          dimension (WD = TQ/TW words) for CPK = 4/WD dimensions that lie 16
+ *          apart.  A token block is TB = min(4*TQ, N) tokens = QD = TB/TQ
+ *          slices (QD = 4 except for 32-token chunks at 2 bits, where the whole
+ *          chunk is one block of QD = 2 slices and a tile has 32 slots); token t
+ *          of the chunk sits in block t / TB, slice qd = (t % TB) / TQ, and
+ *          inside the slice in word w = (t % TQ) / TW at in-word index
+ *          e = t % TW.  Dimension d = 16*ct + j belongs to tile cg = ct / CPK of
+ *          its block (D / (16*CPK) tiles per block), slot 16*qd + j, word
  *          n = (ct % CPK) * WD + w of the slot:
- *              word index = ((block * D/(16*CPK) + cg) * 64 + 16*qd + j) * 4 + n.
- *          Needs D % 64 == 0 and N % 64 == 0.                              */
+ *              word index = ((block * D/(16*CPK) + cg) * 16*QD + 16*qd + j) * 4 + n.
+ *          Needs D % 64 == 0 and N % 64 == 0 or N == 32.                     */
 static void k_code_pos(int t, int d, int D, int b, uint32_t *word, int *bit)
 {
     int n = 32 / b, e = d % n;
     *word = (uint32_t)t * (uint32_t)(D * b / 32) + (uint32_t)(d / n);
     *bit  = 16 * (e % 2) + b * (e / 2);
 }
-static void v_code_pos(int t, int d, int D, int b, uint32_t *word, int *bit)
+static void v_code_pos(int t, int d, int N, int D, int b, uint32_t *word, int *bit)
 {
-    int TW = 32 / b, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, TB = 4 * TQ;
+    int TW = 32 / b, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD;
+    int TB = 4 * TQ < N ? 4 * TQ : N, QD = TB / TQ;
     int block = t / TB, qd = (t % TB) / TQ, w = (t % TQ) / TW, e = t % TW;
     int ct = d / 16, j = d % 16, cg = ct / CPK, n = (ct % CPK) * WD + w;
-    *word = (uint32_t)(((block * (D / (16 * CPK)) + cg) * 64 + 16 * qd + j) * 4 + n);
+    *word = (uint32_t)(((block * (D / (16 * CPK)) + cg) * (16 * QD) + 16 * qd + j) * 4 + n);
     *bit  = 16 * (e % 2) + b * (e / 2);
 }
 /* The V layout above exists for quantised experts only when it tiles evenly. */
 static int layout_ok(const moqae_ref_cfg *c)
 {
     for (int j = 0; j < c->n_experts; j++)
-        if (c->expert_bits[j] < 16 && (c->head_dim % 64 || c->chunk % 64)) return 0;
+        if (c->expert_bits[j] < 16 && (c->head_dim % 64 || (c->chunk % 64 && c->chunk != 32))) return 0;
     return 1;
 }
 
@@ -374,7 +377,7 @@ void moqae_ref_pack_chunk(const moqae_ref_cfg *cfg, int bits,
             moqae_ref_quantize_group(Vc + t * ss + g * G, G, bits, codes, &meta);
             memcpy(v_meta + 4u * (size_t)(t * NG + g), &meta, 4);
             for (int i = 0; i < G; i++) {
-                v_code_pos(t, g * G + i, D, bits, &word, &bit);
+                v_code_pos(t, g * G + i, N, D, bits, &word, &bit);
                 put_code(v_codes, word, bit, codes[i]);
             }
         }
@@ -405,7 +408,7 @@ void moqae_ref_decode_chunk(const moqae_ref_cfg *cfg, int bits, const uint8_t *b
         k_code_pos(t, d, D, bits, &word, &bit);
         Kh[t * D + d] = (double)get_code(k_codes, word, bit, bits) * (double)H2F((uint16_t)(mk & 0xffffu))
                       + (double)H2F((uint16_t)(mk >> 16));
-        v_code_pos(t, d, D, bits, &word, &bit);
+        v_code_pos(t, d, N, D, bits, &word, &bit);
         Vh[t * D + d] = (double)get_code(v_codes, word, bit, bits) * (double)H2F((uint16_t)(mv & 0xffffu))
                       + (double)H2F((uint16_t)(mv >> 16));
     }

@@ -34,10 +34,11 @@ bool cfg_ok(const moqae_cfg *c) {
     return true;
 }
 
-// The packed layout (pack and decode calls): V tiles span 64 tokens, and the decode kernel's
-// matrix-core path for grouped queries holds (query head, group) pairs in the 16 rows of a tile.
+// The packed layout (pack and decode calls): V token blocks span up to 64 tokens (chunks of 32 tokens
+// have their own tile shape), and the decode kernel's matrix-core path for grouped queries holds
+// (query head, group) pairs in the 16 rows of a tile.
 bool layout_ok(const moqae_cfg *c) {
-    if (c->chunk % 64) return false;
+    if (c->chunk % 64 && c->chunk != 32) return false;
     const int rep = c->n_q_heads / c->n_kv_heads;
     return rep == 1 || rep * (kD / c->group) <= 16;
 }

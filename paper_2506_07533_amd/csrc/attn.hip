@@ -174,12 +174,22 @@ __device__ __forceinline__ uint32_t ld4(const uint8_t *sbase, uint32_t voff) {
 
 // The V side: the 16-byte slots 64*j + l of the unit's V KiBs and its (token, group) meta
 // words 64*jj + l, same conventions.
-template <int G>
+// CH32 (chunks of 32 tokens): at 2 bits the chunk's V codes are two tiles of 32 slots (two token slices of 16);
+// lanes 0..31 take tile cg = 0 into c[0] and tile cg = 1 into c[1] as the lanes of slices 0 and 1 of a 64-token
+// block would, the lanes of the absent slices 2, 3 and the absent second block hold zeros.
+template <int G, bool CH32>
 __device__ __forceinline__ void load_v(const Unit &u, int lane, VRegs<G> &v) {
     constexpr int NG = kD / G;
     const uint32_t vv = u.vc + (uint32_t)lane * 16u, vmo = u.vm + (uint32_t)lane * 4u;
     const int nvm = u.lgb == 4 ? 1 : (u.nsub * NG) >> u.lgb;              // >= 1
-    if (u.nsub == 4) {
+    if (CH32 && u.lgb == 1) {
+        const uint32_t vh = u.vc + (uint32_t)(lane & 31) * 16u;
+        const uint4 t0 = ld16(u.vb, vh), t1 = ld16(u.vb, vh + 512u);
+        const bool lo = lane < 32;
+        v.c[0] = uint4{lo ? t0.x : 0u, lo ? t0.y : 0u, lo ? t0.z : 0u, lo ? t0.w : 0u};
+        v.c[1] = uint4{lo ? t1.x : 0u, lo ? t1.y : 0u, lo ? t1.z : 0u, lo ? t1.w : 0u};
+        v.c[2] = uint4{0u, 0u, 0u, 0u}; v.c[3] = uint4{0u, 0u, 0u, 0u};
+    } else if (u.nsub == 4) {
 #pragma unroll
         for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vb + j * 1024, vv);
     } else {
@@ -735,7 +745,7 @@ __device__ __forceinline__ void iq_scores(const Unit &u, const KRegs<G> &k, int 
             ps = fmaf(half_bits_to_float(k.m[j][0] & 0xffffu), iq_combine(acc), ps);
             ps += __shfl_xor(ps, 16);
             ps += __shfl_xor(ps, 32);
-            s4[j] = ps * sc;
+            s4[j] = (j < u.nsub) ? ps * sc : -INFINITY;    // KiB past a short unit (32-token chunks): ignored
             lmax = fmaxf(lmax, s4[j]);
         }
         rescale<G, 1>(st, 0, wave_max(lmax), lane);
@@ -964,7 +974,8 @@ __host__ __device__ inline int attn_segment_chunks(int N) { return min(kDescCap,
 
 // RAGGED: the sequences of the batch have their own numbers of chunks and residual rows (a.seq_chunks,
 // a.seq_tail, device arrays indexed by sequence); a.n_chunks is then the bound that sizes the segments.
-template <int G, int REP, int NWV, bool RAGGED>
+// CH32: chunks of 32 tokens (a.N == 32), see load_v.
+template <int G, int REP, int NWV, bool RAGGED, bool CH32>
 __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     __shared__ AttnLds<G, REP, NWV> L;
     constexpr int NG = kD / G;
@@ -1235,7 +1246,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             auto load_keys = [&](const Unit &un) {
                 if constexpr (REP == 1) load_k_iq<G>(un, lane, kr); else load_k_mc<G, REP>(un, lane, kr);
             };
-            if (have) { load_keys(cur); load_v<G>(cur, lane, va); }
+            if (have) { load_keys(cur); load_v<G, CH32>(cur, lane, va); }
             if (seg == 0) {                              // the q tables, behind the first units' loads
                 if constexpr (kLateTables) build_q_tables();
                 if constexpr (REP > 1) {
@@ -1256,7 +1267,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
 #pragma unroll
                     for (int mi = 0; mi < 4; mi++) ak[mi] = L.qmc[bi][mi][lane];
                 }
-                load_v<G>(pf, lane, vn);                  // a whole unit ahead
+                load_v<G, CH32>(pf, lane, vn);                  // a whole unit ahead
                 if constexpr (REP == 1) {
                     if (lgb == 1)      iq_scores<2, G, NWV>(cur, kr, lane, wave, L, st);
                     else if (lgb == 2) iq_scores<4, G, NWV>(cur, kr, lane, wave, L, st);
@@ -1442,8 +1453,14 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
         if (e0 != hipSuccess) return e0;
     }
     if (ev_begin && hipEventRecord(ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
-    if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
-    else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false>), dim3((unsigned)a.n_wg), dim3(NWV * 64), 0, s, a);
+    const dim3 grid((unsigned)a.n_wg), block(NWV * 64);
+    if (a.N == 32) {
+        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, true>), grid, block, 0, s, a);
+        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true>), grid, block, 0, s, a);
+    } else {
+        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, false>), grid, block, 0, s, a);
+        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, false>), grid, block, 0, s, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev_end && hipEventRecord(ev_end, s) != hipSuccess) return hipErrorInvalidValue;

@@ -380,15 +380,17 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     if (!isV) return;
 
     __syncthreads();
-    // V: dimension-major 1-KiB tiles of 64 slots x 4 words.  A slot holds TQ = max(TW, 8) consecutive
-    // tokens (TW = 32/bits per word, WD = TQ/TW words) of CPK = 4/WD dimensions that lie 16 apart;
-    // slot 16*qd + j of tile cg of a block of 4*TQ tokens: dims 16*(cg*CPK + n/WD) + j, token slice qd.
+    // V: dimension-major tiles of 16*QD slots x 4 words.  A slot holds TQ = max(TW, 8) consecutive tokens
+    // (TW = 32/bits per word, WD = TQ/TW words) of CPK = 4/WD dimensions that lie 16 apart; a token block is
+    // TB = min(4*TQ, N) tokens = QD slices (QD = 4, i.e. 1-KiB tiles, except for 32-token chunks at 2 bits: QD = 2);
+    // slot 16*qd + j of tile cg of a block: dims 16*(cg*CPK + n/WD) + j, token slice qd.
     const int TW = 32 / bits, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, NCG = kD / (16 * CPK);
+    const int TB = min(4 * TQ, N), QD = TB / TQ;
     const int n_groups = N * kD * bits / 128;         // a thread builds the words of four adjacent dims at a time
     for (int g = tid; g < n_groups; g += kPackThreads) {
-        const int n = g & 3, jq = (g >> 2) & 3, qd = (g >> 4) & 3, kib = g >> 6;
-        const int cg = kib % NCG, block = kib / NCG;
-        const int d0 = 16 * (cg * CPK + n / WD) + 4 * jq, t0 = block * 4 * TQ + qd * TQ + (n % WD) * TW;
+        const int n = g & 3, jq = (g >> 2) & 3, qd = (g >> 4) & (QD - 1), tile = g / (16 * QD);
+        const int cg = tile % NCG, block = tile / NCG;
+        const int d0 = 16 * (cg * CPK + n / WD) + 4 * jq, t0 = block * TB + qd * TQ + (n % WD) * TW;
         uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
         for (int e = 0; e < TW; e++) {
             const uint32_t v4 = *reinterpret_cast<const uint32_t *>(vcodes + (t0 + e) * kVRow + d0);   // codes of dims d0..d0+3
@@ -408,7 +410,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
             const uint32_t r = dpp_u<DPP_XOR2>((n & 2) ? wk[k] : wk[k + 2]);
             if (n & 2) wk[k] = r; else wk[k + 2] = r;
         }
-        nt_store(reinterpret_cast<uint4 *>(codes_w + (kib * 64 + 16 * qd + 4 * jq + n) * 4), uint4{wk[0], wk[1], wk[2], wk[3]});
+        nt_store(reinterpret_cast<uint4 *>(codes_w + (tile * 16 * QD + 16 * qd + 4 * jq + n) * 4), uint4{wk[0], wk[1], wk[2], wk[3]});
     }
 }
 

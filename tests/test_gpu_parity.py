@@ -124,7 +124,8 @@ def _pack_both(mq, ref, cfg, rcfg, K, V, c0, c1, expert, start=0, slack=0):
 
 
 @pytest.mark.parametrize("B,Hkv,N,G,C", [(1, 8, 64, 32, 32), (2, 2, 128, 64, 9), (1, 3, 64, 32, 6),
-                                         (1, 2, 256, 64, 5), (1, 1, 192, 32, 8), (1, 2, 64, 64, 7)])
+                                         (1, 2, 256, 64, 5), (1, 1, 192, 32, 8), (1, 2, 64, 64, 7),
+                                         (2, 3, 32, 64, 21), (1, 2, 32, 32, 10)])     # the paper's default chunk size
 def test_pack_bit_exact(mq, ref, B, Hkv, N, G, C):
     rng = np.random.default_rng(N + G + C)
     cfg, rcfg = _cfgs(mq, ref, B, Hkv, Hkv, N, G, (2, 4, 8, 16), 1)
@@ -291,6 +292,11 @@ def _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, bits, seed, scale=None, expert=N
     (2, 2, 2, 64, 64, 3, 0),
     (1, 2, 2, 192, 64, 11, 50),
     (1, 1, 1, 128, 64, 600, 5),      # more chunks than splits*64: several descriptor batches
+    (1, 4, 4, 32, 64, 70, 19),       # chunks of 32 tokens (the paper's default): half tiles at 2 bits, short units at 4 bits
+    (2, 2, 2, 32, 32, 33, 0),
+    (1, 8, 2, 32, 64, 50, 31),       # ... with grouped queries x4
+    (1, 4, 2, 32, 32, 9, 5),
+    (1, 2, 2, 32, 64, 2500, 3),      # ... and several row segments (more than 1024 chunks per row)
 ])
 def test_attention_mixed_bits(mq, ref, B, Hq, Hkv, N, G, C, T):
     err = _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, (2, 4, 8, 16), seed=C * 7 + T)
@@ -298,7 +304,7 @@ def test_attention_mixed_bits(mq, ref, B, Hq, Hkv, N, G, C, T):
 
 
 @pytest.mark.parametrize("bits", [(2,), (4,), (8,), (16,)])
-@pytest.mark.parametrize("N,G,rep", [(128, 64, 1), (64, 32, 4), (192, 32, 1), (256, 64, 2)])
+@pytest.mark.parametrize("N,G,rep", [(128, 64, 1), (64, 32, 4), (192, 32, 1), (256, 64, 2), (32, 64, 1), (32, 64, 8), (32, 32, 2)])
 def test_attention_single_bit_width(mq, ref, bits, N, G, rep):
     err = _attn_case(mq, ref, 1, 2 * rep, 2, N, G, 12, 17, bits, seed=bits[0] + N, freeze=0)
     assert err <= ATTN_TOL, err
@@ -415,6 +421,7 @@ def _ragged_case(mq, ref, Hq, Hkv, N, G, lens, bits=(2, 4, 8, 16), seed=0):
     (2, 2, 256, 64, [256 * 9 + 255, 256, 255, 256 * 4]),
     (2, 1, 64, 64, [64 * 300, 64 * 2 + 1, 5]),                              # grouped queries x2, one row much longer than the rest
     (3, 3, 128, 64, [0, 0, 77]),                                            # almost everything empty
+    (4, 2, 32, 64, [32 * 50 + 7, 31, 32 * 3, 0]),                           # chunks of 32 tokens, grouped queries x2
 ])
 def test_attention_ragged_batch(mq, ref, Hq, Hkv, N, G, lens):
     err = _ragged_case(mq, ref, Hq, Hkv, N, G, lens, seed=len(lens) * 31 + N)

@@ -257,6 +257,9 @@ _GEN = {
     "n128_k_dt_v_3dt": (lambda t, d: (d + t) % 4, lambda t, d: (3 * d + t + t // 64) % 4),
     "n128_g32_zero": (lambda t, d: (d + t) % 16 + d // 32 + 4 * (t % 4),
                       lambda t, d: (d + 5 * t + t // 32) % 16 + 2 * (d // 32) + t % 2),
+    "n32_k_dt_v_3dt": (lambda t, d: (d + t) % 4, lambda t, d: (3 * d + t + t // 16) % 4),
+    "n32_g32_zero": (lambda t, d: (d + t) % 16 + d // 32 + 4 * (t % 4),
+                     lambda t, d: (d + 5 * t + t // 8) % 16 + 2 * (d // 32) + t % 2),
     "n128_k_7dt_v_3d11t": (lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (7 * d + t) % 256)),
                            lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (3 * d + 11 * t + t // 32) % 256))),
 }
@@ -283,7 +286,11 @@ def test_pack_words_golden(ref):
 @pytest.mark.parametrize("bits", [2, 4, 8])
 def test_pack_bit_coverage_is_a_bijection(ref, bits):
     """Every element owns b bits of the code area and no two elements share a bit."""
-    N, D, G = 64, 128, 32
+    for N, D, G in ((64, 128, 32), (32, 128, 64)):
+        _bijection(ref, bits, N, D, G)
+
+
+def _bijection(ref, bits, N, D, G):
     cfg = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0)
     cb, mb = N * D * bits // 8, N * (D // G) * 4
     tot_k = np.zeros(cb, np.uint8); tot_v = np.zeros(cb, np.uint8)
@@ -298,12 +305,13 @@ def test_pack_bit_coverage_is_a_bijection(ref, bits):
     assert (tot_k == 0xFF).all() and (tot_v == 0xFF).all()
 
 
-@pytest.mark.parametrize("bits,G", [(2, 64), (4, 64), (8, 64), (2, 32), (4, 32), (16, 64)])
-def test_pack_decode_roundtrip_bound(ref, bits, G):
+@pytest.mark.parametrize("bits,G,N", [(2, 64, 64), (4, 64, 64), (8, 64, 64), (2, 32, 64), (4, 32, 64), (16, 64, 64),
+                                      (2, 64, 32), (4, 32, 32), (8, 64, 32), (16, 64, 32)])
+def test_pack_decode_roundtrip_bound(ref, bits, G, N):
     """decode(pack(x)) stays within scale/2 of x for every element of K and V:
     the decoder reads each code, scale and zero from where the packer put it."""
     rng = np.random.default_rng(10 + bits)
-    N, D = 64, 128
+    D = 128
     cfg = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0)
     Kc = rng.standard_normal((N, D)).astype(np.float32); Kc[:, [3, 50, 77, 120]] *= 10
     Kc = Kc.astype(np.float16); Vc = rng.standard_normal((N, D)).astype(np.float16)
