@@ -41,6 +41,11 @@
  *   decode attention   : 16-bit experts == unquantised attention (torch fp64
  *                        scaled_dot_product_attention), S = 1, uniform keys,
  *                        score-shift invariance
+ *   paged store        : pool sizes and bases by closed form; a set model of the
+ *                        allocator written in the test (pages handed out in ring
+ *                        order, given-back pages reused first-in first-out, no
+ *                        page twice, exhaustion status); every page holds the
+ *                        block the (pinned) chunk packer makes for its chunk
  */
 #include <math.h>
 #include <stdint.h>
@@ -464,6 +469,128 @@ int moqae_quantize_pack_ref(const moqae_ref_cfg *cfg,
         const int bits = cfg->expert_bits[expert[u * expert_stride_bh + c]];
         const int64_t base = b * stride_b + h * stride_h + (int64_t)c * N * stride_s;
         moqae_ref_pack_chunk(cfg, bits, K + base, V + base, stride_s, arena + chunk_off[u * off_stride_bh + c]);
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Paged store: one pool of fixed-size pages per expert instead of the  */
+/* ordered arena, so that a chunk can be routed (Eq. (1)-(2), Sec. 3.2) */
+/* and quantised in one pass -- its place no longer depends on the      */
+/* decisions of the chunks before it -- and so that chunks can be given */
+/* back (a finished sequence, a sliding window).  Not in the paper: it  */
+/* stores the same blocks as above, only somewhere else.                */
+/*                                                                      */
+/* Pool j serves expert j: n_pages[j] pages of                          */
+/* round_up_256(chunk_block_bytes(B_j)) bytes, pool after pool in the   */
+/* arena.  State (uint32 words): head[8], tail[8], then the free rings  */
+/* of the pools one after another (n_pages[j] entries).  The free pages */
+/* of pool j are ring[head % n] .. ring[(tail-1) % n]; a page is taken  */
+/* at head, given back at tail.                                         */
+/* ------------------------------------------------------------------ */
+typedef struct { int32_t n_pages[8]; } moqae_ref_pool_cfg;
+
+static int pool_ok(const moqae_ref_cfg *c, const moqae_ref_pool_cfg *pc)
+{
+    if (!pc) return 0;
+    for (int j = 0; j < c->n_experts; j++) if (pc->n_pages[j] < 0) return 0;
+    return 1;
+}
+uint64_t moqae_ref_pool_page_bytes(const moqae_ref_cfg *c, int32_t j)
+{
+    return round_up_256(moqae_ref_chunk_block_bytes(c, c->expert_bits[j]));
+}
+uint64_t moqae_ref_pool_base(const moqae_ref_cfg *c, const moqae_ref_pool_cfg *pc, int32_t j)
+{
+    uint64_t off = 0;
+    for (int i = 0; i < j; i++) off += (uint64_t)pc->n_pages[i] * moqae_ref_pool_page_bytes(c, i);
+    return off;
+}
+uint64_t moqae_ref_pool_arena_bytes(const moqae_ref_cfg *c, const moqae_ref_pool_cfg *pc)
+{
+    return moqae_ref_pool_base(c, pc, c->n_experts);
+}
+static uint32_t ring_start(const moqae_ref_cfg *c, const moqae_ref_pool_cfg *pc, int j)
+{
+    uint32_t w = 16;
+    (void)c;
+    for (int i = 0; i < j; i++) w += (uint32_t)pc->n_pages[i];
+    return w;
+}
+uint64_t moqae_ref_pool_state_bytes(const moqae_ref_cfg *c, const moqae_ref_pool_cfg *pc)
+{
+    return 4u * (uint64_t)ring_start(c, pc, c->n_experts);
+}
+int moqae_pool_init_ref(const moqae_ref_cfg *cfg, const moqae_ref_pool_cfg *pc, uint32_t *state)
+{
+    if (!cfg_ok(cfg) || !pool_ok(cfg, pc) || !state) return REF_E_INVAL;
+    for (int j = 0; j < 8; j++) { state[j] = 0; state[8 + j] = j < cfg->n_experts ? (uint32_t)pc->n_pages[j] : 0u; }
+    for (int j = 0; j < cfg->n_experts; j++)
+        for (int i = 0; i < pc->n_pages[j]; i++) state[ring_start(cfg, pc, j) + (uint32_t)i] = (uint32_t)i;
+    return REF_OK;
+}
+
+/* Route (W1 != NULL; else `expert` is an input: the decisions of a routing-sharing leader, Sec. 3.4), take a page of
+ * the routed expert's pool and pack, for chunks [chunk_begin, chunk_end) of every (b, h), in (b, h, c) order.
+ * chunk_off receives the page's byte offset in the arena.  A chunk whose pool is empty gets offset ~0, is not
+ * packed, and *status becomes REF_E_ARENA; an expert index >= M (given decisions) likewise with REF_E_INVAL.
+ * *status != 0 on entry: nothing is done.                                                                    */
+int moqae_route_pack_paged_ref(const moqae_ref_cfg *cfg, const moqae_ref_pool_cfg *pc,
+                               const uint16_t *K, const uint16_t *V,
+                               int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                               int32_t chunk_begin, int32_t chunk_end,
+                               const uint16_t *W1, const uint16_t *W2, const uint16_t *W3, const float *logit_bias,
+                               uint8_t *expert, int64_t expert_stride_bh, int32_t *votes,
+                               uint8_t *arena, uint32_t *state,
+                               uint64_t *chunk_off, int64_t off_stride_bh, int32_t *status)
+{
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !pool_ok(cfg, pc) || !K || !V || !expert || !arena || !state || !chunk_off || !status)
+        return REF_E_INVAL;
+    if (chunk_begin < 0 || chunk_end < chunk_begin || expert_stride_bh < chunk_end || off_stride_bh < chunk_end) return REF_E_INVAL;
+    if (W1 && (!W2 || !W3)) return REF_E_INVAL;
+    if (*status != 0) return REF_OK;
+    if (W1) {
+        int rc = moqae_route_chunks_ref(cfg, K, stride_b, stride_h, stride_s, chunk_begin, chunk_end, W1, W2, W3, logit_bias,
+                                        expert, expert_stride_bh, votes);
+        if (rc != REF_OK) return rc;
+    }
+    const int N = cfg->chunk;
+    const int64_t units = (int64_t)cfg->batch * cfg->n_kv_heads;
+    for (int64_t u = 0; u < units; u++) for (int c = chunk_begin; c < chunk_end; c++) {
+        const int64_t b = u / cfg->n_kv_heads, h = u % cfg->n_kv_heads;
+        const int e = expert[u * expert_stride_bh + c];
+        chunk_off[u * off_stride_bh + c] = ~(uint64_t)0;
+        if (e >= cfg->n_experts) { *status = REF_E_INVAL; continue; }
+        uint32_t *head = &state[e], *tail = &state[8 + e];
+        if (*head == *tail) { if (*status == 0) *status = REF_E_ARENA; continue; }
+        const uint32_t page = state[ring_start(cfg, pc, e) + *head % (uint32_t)pc->n_pages[e]];
+        *head += 1;
+        const uint64_t off = moqae_ref_pool_base(cfg, pc, e) + (uint64_t)page * moqae_ref_pool_page_bytes(cfg, e);
+        chunk_off[u * off_stride_bh + c] = off;
+        const int64_t base = b * stride_b + h * stride_h + (int64_t)c * N * stride_s;
+        moqae_ref_pack_chunk(cfg, cfg->expert_bits[e], K + base, V + base, stride_s, arena + off);
+    }
+    return REF_OK;
+}
+
+/* Gives the pages of chunks [chunk_begin, chunk_end) of rows [row_begin, row_end) back to their pools, in (row, c)
+ * order, and sets their offsets to ~0.  Chunks without a page (offset ~0) are skipped.                          */
+int moqae_pool_release_ref(const moqae_ref_cfg *cfg, const moqae_ref_pool_cfg *pc,
+                           const uint8_t *expert, int64_t expert_stride_bh,
+                           uint64_t *chunk_off, int64_t off_stride_bh,
+                           int32_t row_begin, int32_t row_end, int32_t chunk_begin, int32_t chunk_end, uint32_t *state)
+{
+    if (!cfg_ok(cfg) || !pool_ok(cfg, pc) || !expert || !chunk_off || !state) return REF_E_INVAL;
+    if (row_begin < 0 || row_end < row_begin || row_end > cfg->batch * cfg->n_kv_heads) return REF_E_INVAL;
+    if (chunk_begin < 0 || chunk_end < chunk_begin || expert_stride_bh < chunk_end || off_stride_bh < chunk_end) return REF_E_INVAL;
+    for (int64_t u = row_begin; u < row_end; u++) for (int c = chunk_begin; c < chunk_end; c++) {
+        const uint64_t off = chunk_off[u * off_stride_bh + c];
+        const int e = expert[u * expert_stride_bh + c];
+        if (off == ~(uint64_t)0 || e >= cfg->n_experts) continue;
+        const uint32_t page = (uint32_t)((off - moqae_ref_pool_base(cfg, pc, e)) / moqae_ref_pool_page_bytes(cfg, e));
+        state[ring_start(cfg, pc, e) + state[8 + e] % (uint32_t)pc->n_pages[e]] = page;
+        state[8 + e] += 1;
+        chunk_off[u * off_stride_bh + c] = ~(uint64_t)0;
     }
     return REF_OK;
 }

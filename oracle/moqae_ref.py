@@ -212,6 +212,76 @@ def quantize_pack(cfg: RefCfg, K: np.ndarray, V: np.ndarray, chunk_begin: int, c
     return int(status[0])
 
 
+class _PoolCfg(C.Structure):
+    _fields_ = [("n_pages", C.c_int32 * 8)]
+
+
+def _pc(n_pages: Sequence[int]) -> _PoolCfg:
+    return _PoolCfg((C.c_int32 * 8)(*(list(n_pages) + [0] * (8 - len(n_pages)))))
+
+
+def pool_page_bytes(cfg: RefCfg, j: int) -> int:
+    lib().moqae_ref_pool_page_bytes.restype = C.c_uint64
+    return int(lib().moqae_ref_pool_page_bytes(C.byref(cfg.c()), C.c_int32(j)))
+
+
+def pool_base(cfg: RefCfg, n_pages: Sequence[int], j: int) -> int:
+    lib().moqae_ref_pool_base.restype = C.c_uint64
+    return int(lib().moqae_ref_pool_base(C.byref(cfg.c()), C.byref(_pc(n_pages)), C.c_int32(j)))
+
+
+def pool_arena_bytes(cfg: RefCfg, n_pages: Sequence[int]) -> int:
+    lib().moqae_ref_pool_arena_bytes.restype = C.c_uint64
+    return int(lib().moqae_ref_pool_arena_bytes(C.byref(cfg.c()), C.byref(_pc(n_pages))))
+
+
+def pool_init(cfg: RefCfg, n_pages: Sequence[int]) -> np.ndarray:
+    """Returns the pool state (uint32 words: head[8], tail[8], free rings)."""
+    lib().moqae_ref_pool_state_bytes.restype = C.c_uint64
+    nb = int(lib().moqae_ref_pool_state_bytes(C.byref(cfg.c()), C.byref(_pc(n_pages))))
+    state = np.zeros(nb // 4, np.uint32)
+    rc = lib().moqae_pool_init_ref(C.byref(cfg.c()), C.byref(_pc(n_pages)), _p(state))
+    if rc != 0:
+        raise ValueError(f"moqae_pool_init_ref -> {rc}")
+    return state
+
+
+def route_pack_paged(cfg: RefCfg, n_pages: Sequence[int], K: np.ndarray, V: np.ndarray, chunk_begin: int, chunk_end: int,
+                     router, expert: np.ndarray, votes: Optional[np.ndarray], arena: np.ndarray, state: np.ndarray,
+                     chunk_off: np.ndarray, status: Optional[np.ndarray] = None) -> int:
+    """router: (W1, W2, W3, bias or None) or None (then `expert` holds the decisions to use).  Returns the status."""
+    K = _h(K); V = _h(V)
+    sb, sh, ss = _kv_strides(K, cfg)
+    assert _kv_strides(V, cfg) == (sb, sh, ss) and K.shape[2] >= chunk_end * cfg.chunk
+    assert expert.dtype == np.uint8 and expert.ndim == 2 and expert.flags.c_contiguous
+    assert chunk_off.dtype == np.uint64 and chunk_off.ndim == 2 and chunk_off.flags.c_contiguous
+    assert arena.dtype == np.uint8 and state.dtype == np.uint32
+    if votes is not None:
+        assert votes.dtype == np.int32 and votes.flags.c_contiguous
+    if status is None:
+        status = np.zeros(1, np.int32)
+    W = [None, None, None, None]
+    if router is not None:
+        W = [_h(router[0]), _h(router[1]), _h(router[2]), None if router[3] is None else np.ascontiguousarray(router[3], np.float32)]
+    pp = lambda a: None if a is None else _p(a)
+    rc = lib().moqae_route_pack_paged_ref(C.byref(cfg.c()), C.byref(_pc(n_pages)), _p(K), _p(V), C.c_int64(sb), C.c_int64(sh),
+                                          C.c_int64(ss), C.c_int32(chunk_begin), C.c_int32(chunk_end), pp(W[0]), pp(W[1]), pp(W[2]),
+                                          pp(W[3]), _p(expert), C.c_int64(expert.shape[1]), pp(votes), _p(arena), _p(state),
+                                          _p(chunk_off), C.c_int64(chunk_off.shape[1]), _p(status))
+    if rc != 0:
+        raise ValueError(f"moqae_route_pack_paged_ref -> {rc}")
+    return int(status[0])
+
+
+def pool_release(cfg: RefCfg, n_pages: Sequence[int], expert: np.ndarray, chunk_off: np.ndarray, row_begin: int, row_end: int,
+                 chunk_begin: int, chunk_end: int, state: np.ndarray) -> None:
+    rc = lib().moqae_pool_release_ref(C.byref(cfg.c()), C.byref(_pc(n_pages)), _p(expert), C.c_int64(expert.shape[1]),
+                                      _p(chunk_off), C.c_int64(chunk_off.shape[1]), C.c_int32(row_begin), C.c_int32(row_end),
+                                      C.c_int32(chunk_begin), C.c_int32(chunk_end), _p(state))
+    if rc != 0:
+        raise ValueError(f"moqae_pool_release_ref -> {rc}")
+
+
 def decode_attn(cfg: RefCfg, q: np.ndarray, arena: Optional[np.ndarray], chunk_off: Optional[np.ndarray],
                 expert: Optional[np.ndarray], n_chunks: int,
                 K_tail: Optional[np.ndarray], V_tail: Optional[np.ndarray], n_tail: int,
