@@ -301,6 +301,30 @@ def bench_layer(args, w):
         res["route_chunks_per_s"] = round(n_units / (t_route.mean() * 1e-3), 1)
         res["pack_chunks_per_s"] = round(n_units / (t_pack.mean() * 1e-3), 1)
 
+    if not args.decode_only:
+        # the same compression in ONE kernel on the paged store (moqae_route_pack_paged: router, page, quantiser per chunk;
+        # K is read from HBM once), timed beside the two-call path above
+        pages = tuple(int((bits_of == b).sum()) + 8 for b in w.expert_bits)
+        p_arena = torch.zeros(mq.pool_arena_bytes(cfg, pages), dtype=torch.uint8, device=dev)
+        p_state = torch.zeros(mq.pool_state_bytes(cfg, pages) // 4, dtype=torch.int32, device=dev)
+        p_off = torch.zeros((BH, C), dtype=torch.int64, device=dev)
+        p_expert = torch.zeros((BH, C), dtype=torch.uint8, device=dev)
+        n_f = max(10, args.steps // 3)
+        fev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_f)]
+        for i in range(3 + n_f):
+            mq.pool_init(cfg, pages, p_state)
+            if i >= 3: fev[i - 3][0].record()
+            mq.route_pack_paged(cfg, pages, K, V, 0, C, (W1, W2, W3, None), p_expert, votes, p_arena, p_state, p_off, status)
+            if i >= 3: fev[i - 3][1].record()
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0 and torch.equal(p_expert, expert), "paged path"
+        t_f = np.array([a.elapsed_time(b) for a, b in fev])
+        fused_bytes = 2 * kv_bytes + packed_bytes + n_units * (9 + 1 + 4 * M)
+        res["roofline_route_pack_paged"] = dict(roof(fused_bytes, t_f), kernel="route_pack_kernel (router + page + quantiser, one pass)",
+                                                samples=n_f)
+        res["route_pack_paged_chunks_per_s"] = round(n_units / (t_f.mean() * 1e-3), 1)
+        del p_arena
+
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, scale)
     return res

@@ -223,6 +223,51 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
 uint64_t moqae_decode_workspace_bytes_ragged(const moqae_cfg *cfg, int32_t max_chunks);   /* host; 0 if cfg invalid */
 
 /*
+ * Paged store.  The ordered arena of moqae_quantize_pack puts a chunk's block where the blocks of all earlier
+ * chunks end, so nothing can be packed before every chunk of the call is routed, and nothing can ever be given
+ * back.  Here every expert has a pool of equal pages instead: pool j = n_pages[j] pages of
+ * moqae_pool_page_bytes(cfg, j) bytes (the expert's chunk block rounded up to 256), pool after pool in `arena`
+ * (moqae_pool_base; moqae_pool_arena_bytes in all, 256-byte aligned).  The router (Eq. (1)-(2), Sec. 3.2),
+ * the choice of a page and the quantiser then run in ONE pass over a chunk, which reads K from HBM once; the
+ * blocks are the ones moqae_quantize_pack writes, and moqae_decode_attn* read them through `chunk_off` as before.
+ * `state` (device, moqae_pool_state_bytes, 4-byte aligned) holds the free pages of every pool; its layout is the
+ * library's own (the pages of a pool are spread over several rings, so that the atomic steps of a call do not
+ * all meet on one address).  moqae_pool_init fills it (every page free); moqae_pool_free_pages writes the
+ * number of free pages of every pool to counts[0..7] (device uint32).
+ *
+ * moqae_route_pack_paged, for chunks [chunk_begin, chunk_end) of every (b, h): W1 != NULL: routes the chunk as
+ * moqae_route_chunks does (expert and votes are outputs; frozen chunks take the first 16-bit expert); W1 == NULL:
+ * `expert` is an input (the decisions of a routing-sharing leader, Sec. 3.4) and votes is not touched.  Then a
+ * page is taken from the expert's pool, chunk_off receives its byte offset and K, V are quantised into it.
+ * Which page a chunk gets is not specified (any free page of the right pool).  *status (device int32) != 0 on
+ * entry: nothing is done.  A chunk whose pool is empty gets chunk_off = ~0, is not packed, and *status becomes
+ * MOQAE_E_ARENA (an expert index >= M given as input: MOQAE_E_INVAL); the other chunks of the call are still
+ * served, and the caller must treat the call as failed.  At most 65535 chunks per (b, h) and call.
+ *
+ * moqae_pool_release gives the pages of chunks [chunk_begin, chunk_end) of rows [row_begin, row_end) (row =
+ * b*Hkv + h) back to their pools and sets their chunk_off to ~0 (a finished sequence, the oldest chunks of a
+ * sliding window); entries that are ~0 already are skipped.  Calls on one pool state must not overlap.
+ */
+typedef struct { int32_t n_pages[MOQAE_MAX_EXPERTS]; } moqae_pool_cfg;            /* pages of pool j = expert j */
+uint64_t moqae_pool_page_bytes(const moqae_cfg *cfg, int32_t expert);                              /* host */
+uint64_t moqae_pool_base(const moqae_cfg *cfg, const moqae_pool_cfg *pool, int32_t expert);       /* host */
+uint64_t moqae_pool_arena_bytes(const moqae_cfg *cfg, const moqae_pool_cfg *pool);                /* host */
+uint64_t moqae_pool_state_bytes(const moqae_cfg *cfg, const moqae_pool_cfg *pool);                /* host */
+int moqae_pool_init(const moqae_cfg *cfg, const moqae_pool_cfg *pool, void *state, void *stream);
+int moqae_pool_free_pages(const moqae_cfg *cfg, const moqae_pool_cfg *pool, const void *state, uint32_t *counts, void *stream);
+int moqae_route_pack_paged(const moqae_cfg *cfg, const moqae_pool_cfg *pool,
+                           const void *K, const void *V, int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                           int32_t chunk_begin, int32_t chunk_end,
+                           const void *W1, const void *W2, const void *W3, const float *logit_bias,
+                           uint8_t *expert, int64_t expert_stride, int32_t *votes,
+                           void *arena, void *state, uint64_t *chunk_off, int64_t off_stride, int32_t *status,
+                           void *stream);
+int moqae_pool_release(const moqae_cfg *cfg, const moqae_pool_cfg *pool,
+                       const uint8_t *expert, int64_t expert_stride, uint64_t *chunk_off, int64_t off_stride,
+                       int32_t row_begin, int32_t row_end, int32_t chunk_begin, int32_t chunk_end,
+                       void *state, void *stream);
+
+/*
  * For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc): moqae_decode_attn without the workspace argument.  The workspace is a fixed array of
  * moqae_static_scratch_bytes() (8 MiB) that lives inside the library, one copy on every GPU the library is used

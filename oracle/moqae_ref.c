@@ -483,8 +483,9 @@ int moqae_quantize_pack_ref(const moqae_ref_cfg *cfg,
 /*                                                                      */
 /* Pool j serves expert j: n_pages[j] pages of                          */
 /* round_up_256(chunk_block_bytes(B_j)) bytes, pool after pool in the   */
-/* arena.  State (uint32 words): head[8], tail[8], then the free rings  */
-/* of the pools one after another (n_pages[j] entries).  The free pages */
+/* arena.  State (uint32 words): head[8], tail[8], 16 reserved words,    */
+/* then the free rings of the pools one after another (n_pages[j]       */
+/* entries each, the first at word 32).  The free pages                 */
 /* of pool j are ring[head % n] .. ring[(tail-1) % n]; a page is taken  */
 /* at head, given back at tail.                                         */
 /* ------------------------------------------------------------------ */
@@ -512,7 +513,7 @@ uint64_t moqae_ref_pool_arena_bytes(const moqae_ref_cfg *c, const moqae_ref_pool
 }
 static uint32_t ring_start(const moqae_ref_cfg *c, const moqae_ref_pool_cfg *pc, int j)
 {
-    uint32_t w = 16;
+    uint32_t w = 32;
     (void)c;
     for (int i = 0; i < j; i++) w += (uint32_t)pc->n_pages[i];
     return w;
@@ -525,6 +526,7 @@ int moqae_pool_init_ref(const moqae_ref_cfg *cfg, const moqae_ref_pool_cfg *pc, 
 {
     if (!cfg_ok(cfg) || !pool_ok(cfg, pc) || !state) return REF_E_INVAL;
     for (int j = 0; j < 8; j++) { state[j] = 0; state[8 + j] = j < cfg->n_experts ? (uint32_t)pc->n_pages[j] : 0u; }
+    for (int j = 16; j < 32; j++) state[j] = 0;
     for (int j = 0; j < cfg->n_experts; j++)
         for (int i = 0; i < pc->n_pages[j]; i++) state[ring_start(cfg, pc, j) + (uint32_t)i] = (uint32_t)i;
     return REF_OK;

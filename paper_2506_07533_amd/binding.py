@@ -48,12 +48,22 @@ class Cfg:
                     self.group, len(self.expert_bits), (C.c_int32 * 8)(*bits), self.freeze_chunks)
 
 
+class _PoolCfg(C.Structure):
+    _fields_ = [("n_pages", C.c_int32 * 8)]
+
+
+def _pc(n_pages: Sequence[int]) -> _PoolCfg:
+    return _PoolCfg((C.c_int32 * 8)(*(list(n_pages) + [0] * (8 - len(n_pages)))))
+
+
 _lib = None
 EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "moqae_chunk_block_bytes",
            "moqae_arena_upper_bound", "moqae_decode_workspace_bytes", "moqae_strerror", "moqae_abi_version",
            "moqae_decode_attn_ragged", "moqae_decode_workspace_bytes_ragged",
            "moqae_decode_plan", "moqae_decode_attn_planned", "moqae_append_tail",
-           "moqae_decode_attn_static", "moqae_static_scratch_bytes"]
+           "moqae_decode_attn_static", "moqae_static_scratch_bytes",
+           "moqae_pool_page_bytes", "moqae_pool_base", "moqae_pool_arena_bytes", "moqae_pool_state_bytes",
+           "moqae_pool_init", "moqae_route_pack_paged", "moqae_pool_release", "moqae_pool_free_pages"]
 # measurement aids of include/moqae_bench.h (bench.py only)
 BENCH_EXPORTS = ["moqae_bench_time_decode_kernel", "moqae_bench_stream_read", "moqae_bench_stream_sink_words"]
 
@@ -80,6 +90,24 @@ def lib():
         L.moqae_decode_attn_static.argtypes = [C.POINTER(_Cfg), vp, vp, vp, vp, i64, i32, vp, vp, i32, C.c_float, vp, vp]
         L.moqae_static_scratch_bytes.restype = u64
         L.moqae_static_scratch_bytes.argtypes = []
+        pcp = C.POINTER(_PoolCfg)
+        L.moqae_pool_page_bytes.restype = u64
+        L.moqae_pool_page_bytes.argtypes = [C.POINTER(_Cfg), i32]
+        L.moqae_pool_base.restype = u64
+        L.moqae_pool_base.argtypes = [C.POINTER(_Cfg), pcp, i32]
+        L.moqae_pool_arena_bytes.restype = u64
+        L.moqae_pool_arena_bytes.argtypes = [C.POINTER(_Cfg), pcp]
+        L.moqae_pool_state_bytes.restype = u64
+        L.moqae_pool_state_bytes.argtypes = [C.POINTER(_Cfg), pcp]
+        L.moqae_pool_init.restype = C.c_int
+        L.moqae_pool_init.argtypes = [C.POINTER(_Cfg), pcp, vp, vp]
+        L.moqae_route_pack_paged.restype = C.c_int
+        L.moqae_route_pack_paged.argtypes = [C.POINTER(_Cfg), pcp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, i64, vp,
+                                             vp, vp, vp, i64, vp, vp]
+        L.moqae_pool_free_pages.restype = C.c_int
+        L.moqae_pool_free_pages.argtypes = [C.POINTER(_Cfg), pcp, vp, vp, vp]
+        L.moqae_pool_release.restype = C.c_int
+        L.moqae_pool_release.argtypes = [C.POINTER(_Cfg), pcp, vp, i64, vp, i64, i32, i32, i32, i32, vp, vp]
         L.moqae_decode_plan.restype = C.c_int
         L.moqae_decode_plan.argtypes = [C.POINTER(_Cfg), vp, i64, i32, vp, u64, vp]
         L.moqae_append_tail.restype = C.c_int
@@ -182,6 +210,73 @@ def quantize_pack(cfg: Cfg, K: torch.Tensor, V: torch.Tensor, chunk_begin: int, 
                                      sb, sh, ss, chunk_begin, chunk_end, _ptr(expert), expert.shape[1],
                                      _ptr(arena), arena.numel(), _ptr(arena_used), _ptr(chunk_off), chunk_off.shape[1],
                                      _ptr(status), _stream()), "moqae_quantize_pack")
+
+
+def pool_page_bytes(cfg: Cfg, expert: int) -> int:
+    return int(lib().moqae_pool_page_bytes(C.byref(cfg.c()), expert))
+
+
+def pool_base(cfg: Cfg, n_pages: Sequence[int], expert: int) -> int:
+    return int(lib().moqae_pool_base(C.byref(cfg.c()), C.byref(_pc(n_pages)), expert))
+
+
+def pool_arena_bytes(cfg: Cfg, n_pages: Sequence[int]) -> int:
+    return int(lib().moqae_pool_arena_bytes(C.byref(cfg.c()), C.byref(_pc(n_pages))))
+
+
+def pool_state_bytes(cfg: Cfg, n_pages: Sequence[int]) -> int:
+    return int(lib().moqae_pool_state_bytes(C.byref(cfg.c()), C.byref(_pc(n_pages))))
+
+
+def pool_init(cfg: Cfg, n_pages: Sequence[int], state: torch.Tensor) -> None:
+    """state: int32 / uint8 device tensor of pool_state_bytes() bytes."""
+    assert state.is_cuda and state.is_contiguous() and state.numel() * state.element_size() >= pool_state_bytes(cfg, n_pages)
+    _check(lib().moqae_pool_init(C.byref(cfg.c()), C.byref(_pc(n_pages)), _ptr(state), _stream()), "moqae_pool_init")
+
+
+def pool_free_pages(cfg: Cfg, n_pages: Sequence[int], state: torch.Tensor) -> list:
+    """Free pages of every pool (synchronises: a test / monitoring aid)."""
+    counts = torch.zeros(8, dtype=torch.int32, device=state.device)
+    _check(lib().moqae_pool_free_pages(C.byref(cfg.c()), C.byref(_pc(n_pages)), _ptr(state), _ptr(counts), _stream()),
+           "moqae_pool_free_pages")
+    return [int(v) for v in counts.cpu().tolist()][:len(cfg.expert_bits)]
+
+
+def route_pack_paged(cfg: Cfg, n_pages: Sequence[int], K: torch.Tensor, V: torch.Tensor, chunk_begin: int, chunk_end: int,
+                     router, expert: torch.Tensor, votes: Optional[torch.Tensor], arena: torch.Tensor, state: torch.Tensor,
+                     chunk_off: torch.Tensor, status: torch.Tensor, token0: int = 0) -> None:
+    """router: (W1, W2, W3, bias or None), or None: `expert` then holds the decisions to use (routing sharing).
+    arena: uint8 [pool_arena_bytes]; state: pool state; chunk_off: int64 [B*Hkv, Ccap]; status: int32 [1]."""
+    sb, sh, ss = _kv_strides(K, cfg)
+    assert _kv_strides(V, cfg) == (sb, sh, ss)
+    assert K.shape[2] + token0 >= chunk_end * cfg.chunk and chunk_begin * cfg.chunk >= token0
+    assert expert.dtype == torch.uint8 and expert.dim() == 2 and expert.is_contiguous() and expert.is_cuda
+    assert chunk_off.dtype == torch.int64 and chunk_off.dim() == 2 and chunk_off.is_contiguous()
+    assert arena.dtype == torch.uint8 and arena.numel() >= pool_arena_bytes(cfg, n_pages) and status.dtype == torch.int32
+    assert state.numel() * state.element_size() >= pool_state_bytes(cfg, n_pages)
+    W = (None, None, None, None)
+    if router is not None:
+        W = router
+        for w in W[:3]:
+            assert w.is_cuda and w.dtype == torch.float16 and w.is_contiguous()
+        if W[3] is not None:
+            assert W[3].is_cuda and W[3].dtype == torch.float32
+    if votes is not None:
+        assert votes.dtype == torch.int32 and votes.is_contiguous() and votes.shape[:2] == expert.shape
+    shift = token0 * ss * 2
+    _check(lib().moqae_route_pack_paged(C.byref(cfg.c()), C.byref(_pc(n_pages)), C.c_void_p(K.data_ptr() - shift),
+                                        C.c_void_p(V.data_ptr() - shift), sb, sh, ss, chunk_begin, chunk_end,
+                                        _ptr(W[0]), _ptr(W[1]), _ptr(W[2]), _ptr(W[3]), _ptr(expert), expert.shape[1], _ptr(votes),
+                                        _ptr(arena), _ptr(state), _ptr(chunk_off), chunk_off.shape[1], _ptr(status), _stream()),
+           "moqae_route_pack_paged")
+
+
+def pool_release(cfg: Cfg, n_pages: Sequence[int], expert: torch.Tensor, chunk_off: torch.Tensor, row_begin: int, row_end: int,
+                 chunk_begin: int, chunk_end: int, state: torch.Tensor) -> None:
+    assert expert.dtype == torch.uint8 and expert.is_contiguous() and chunk_off.dtype == torch.int64 and chunk_off.is_contiguous()
+    _check(lib().moqae_pool_release(C.byref(cfg.c()), C.byref(_pc(n_pages)), _ptr(expert), expert.shape[1], _ptr(chunk_off),
+                                    chunk_off.shape[1], row_begin, row_end, chunk_begin, chunk_end, _ptr(state), _stream()),
+           "moqae_pool_release")
 
 
 def decode_plan(cfg: Cfg, expert: Optional[torch.Tensor], n_chunks: int, workspace: torch.Tensor) -> None:

@@ -118,6 +118,28 @@ int static_scratch(void **out) {
     return MOQAE_OK;
 }
 
+// Geometry of the paged store from the configuration: page sizes, pool bases, ring positions.
+bool pool_cfg_ok(const moqae_cfg *c, const moqae_pool_cfg *pc) {
+    if (!pc) return false;
+    uint64_t pages = 0;
+    for (int j = 0; j < c->n_experts; j++) { if (pc->n_pages[j] < 0) return false; pages += (uint64_t)pc->n_pages[j]; }
+    return pages < (1ull << 30);
+}
+uint64_t page_bytes_of(const moqae_cfg *c, int j) { return (block_bytes(c->chunk, c->group, c->expert_bits[j]) + 255u) & ~255ull; }
+void fill_pool_geometry(const moqae_cfg *c, const moqae_pool_cfg *pc, PagedArgs &a) {
+    uint64_t base = 0; uint32_t ring = 16 + 8 * 2 * kPoolShards;
+    for (int j = 0; j < 8; j++) {
+        const bool on = j < c->n_experts;
+        a.n_pages[j] = on ? (uint32_t)pc->n_pages[j] : 0u;
+        a.page_bytes[j] = on ? (uint32_t)page_bytes_of(c, j) : 0u;
+        a.pool_base[j] = base; a.ring_start[j] = ring;
+        a.ring_cap[j] = (a.n_pages[j] + kPoolShards - 1) / kPoolShards; if (a.ring_cap[j] == 0) a.ring_cap[j] = 1;
+        a.bits_of[j] = on ? c->expert_bits[j] : 16;
+        base += (uint64_t)a.n_pages[j] * a.page_bytes[j]; ring += on ? a.ring_cap[j] * kPoolShards : 0u;
+    }
+    a.M = c->n_experts; a.N = c->chunk; a.G = c->group; a.Hkv = c->n_kv_heads; a.BH = c->batch * c->n_kv_heads;
+}
+
 thread_local hipEvent_t g_time_begin = nullptr, g_time_end = nullptr;   // measurement aid, see moqae_bench.h
 
 }  // namespace
@@ -287,6 +309,81 @@ int moqae_decode_attn_static(const moqae_cfg *cfg, const void *q,
 }
 
 uint64_t moqae_static_scratch_bytes(void) { return MOQAE_STATIC_SCRATCH_BYTES; }
+
+uint64_t moqae_pool_page_bytes(const moqae_cfg *cfg, int32_t expert) {
+    if (!cfg_ok(cfg) || expert < 0 || expert >= cfg->n_experts) return 0;
+    return page_bytes_of(cfg, expert);
+}
+uint64_t moqae_pool_base(const moqae_cfg *cfg, const moqae_pool_cfg *pool, int32_t expert) {
+    if (!cfg_ok(cfg) || !pool_cfg_ok(cfg, pool) || expert < 0 || expert > cfg->n_experts) return 0;
+    PagedArgs a = {}; fill_pool_geometry(cfg, pool, a);
+    return expert == cfg->n_experts ? a.pool_base[expert - 1] + (uint64_t)a.n_pages[expert - 1] * a.page_bytes[expert - 1]
+                                    : a.pool_base[expert];
+}
+uint64_t moqae_pool_arena_bytes(const moqae_cfg *cfg, const moqae_pool_cfg *pool) { return moqae_pool_base(cfg, pool, cfg ? cfg->n_experts : 0); }
+uint64_t moqae_pool_state_bytes(const moqae_cfg *cfg, const moqae_pool_cfg *pool) {
+    if (!cfg_ok(cfg) || !pool_cfg_ok(cfg, pool)) return 0;
+    PagedArgs a = {}; fill_pool_geometry(cfg, pool, a);
+    const int last = cfg->n_experts - 1;
+    return 4ull * (a.ring_start[last] + (uint64_t)a.ring_cap[last] * kPoolShards);
+}
+
+int moqae_pool_free_pages(const moqae_cfg *cfg, const moqae_pool_cfg *pool, const void *state, uint32_t *counts, void *stream) {
+    if (!cfg_ok(cfg) || !pool_cfg_ok(cfg, pool) || !state || !counts || !aligned(state, 4) || !aligned(counts, 4)) return MOQAE_E_INVAL;
+    PagedArgs a = {}; fill_pool_geometry(cfg, pool, a);
+    a.state = static_cast<uint32_t *>(const_cast<void *>(state));
+    return launch_pool_free_pages(a, counts, static_cast<hipStream_t>(stream)) == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+int moqae_pool_init(const moqae_cfg *cfg, const moqae_pool_cfg *pool, void *state, void *stream) {
+    if (!cfg_ok(cfg) || !pool_cfg_ok(cfg, pool) || !state || !aligned(state, 4)) return MOQAE_E_INVAL;
+    PagedArgs a = {}; fill_pool_geometry(cfg, pool, a);
+    a.state = static_cast<uint32_t *>(state);
+    return launch_pool_init(a, static_cast<hipStream_t>(stream)) == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+int moqae_route_pack_paged(const moqae_cfg *cfg, const moqae_pool_cfg *pool,
+                           const void *K, const void *V, int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                           int32_t chunk_begin, int32_t chunk_end,
+                           const void *W1, const void *W2, const void *W3, const float *logit_bias,
+                           uint8_t *expert, int64_t expert_stride, int32_t *votes,
+                           void *arena, void *state, uint64_t *chunk_off, int64_t off_stride, int32_t *status, void *stream) {
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || !pool_cfg_ok(cfg, pool) || !K || !V || !expert || !arena || !state || !chunk_off || !status)
+        return MOQAE_E_INVAL;
+    if (chunk_begin < 0 || chunk_end < chunk_begin || chunk_end - chunk_begin > 65535) return MOQAE_E_INVAL;
+    if (expert_stride < chunk_end || off_stride < chunk_end) return MOQAE_E_INVAL;
+    if (!strides_ok(cfg, stride_b, stride_h, stride_s) || !aligned(K, 16) || !aligned(V, 16)) return MOQAE_E_INVAL;
+    if (!aligned(arena, 256) || !aligned(state, 4) || !aligned(chunk_off, 8) || !aligned(status, 4)) return MOQAE_E_INVAL;
+    if (W1 && (!W2 || !W3 || !aligned(W1, 4) || !aligned(W2, 4) || !aligned(W3, 2))) return MOQAE_E_INVAL;
+    const int e16 = first_16bit(cfg);
+    if (W1 && cfg->freeze_chunks > 0 && e16 < 0) return MOQAE_E_INVAL;
+    if (chunk_end == chunk_begin) return MOQAE_OK;
+    PagedArgs a = {}; fill_pool_geometry(cfg, pool, a);
+    a.K = static_cast<const uint16_t *>(K); a.V = static_cast<const uint16_t *>(V);
+    a.stride_b = stride_b; a.stride_h = stride_h; a.stride_s = stride_s;
+    a.W1 = static_cast<const uint16_t *>(W1); a.W2 = static_cast<const uint16_t *>(W2); a.W3 = static_cast<const uint16_t *>(W3);
+    a.bias = logit_bias; a.expert = expert; a.expert_stride = expert_stride; a.votes = votes;
+    a.arena = static_cast<uint8_t *>(arena); a.state = static_cast<uint32_t *>(state);
+    a.chunk_off = reinterpret_cast<unsigned long long *>(chunk_off); a.off_stride = off_stride; a.status = status;
+    a.chunk_begin = chunk_begin; a.n_chunks = chunk_end - chunk_begin;
+    a.freeze_chunks = cfg->freeze_chunks; a.e16 = e16 < 0 ? 0 : e16;
+    return launch_route_pack_paged(a, static_cast<hipStream_t>(stream)) == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
+int moqae_pool_release(const moqae_cfg *cfg, const moqae_pool_cfg *pool,
+                       const uint8_t *expert, int64_t expert_stride, uint64_t *chunk_off, int64_t off_stride,
+                       int32_t row_begin, int32_t row_end, int32_t chunk_begin, int32_t chunk_end, void *state, void *stream) {
+    if (!cfg_ok(cfg) || !pool_cfg_ok(cfg, pool) || !expert || !chunk_off || !state) return MOQAE_E_INVAL;
+    if (row_begin < 0 || row_end < row_begin || row_end > cfg->batch * cfg->n_kv_heads) return MOQAE_E_INVAL;
+    if (chunk_begin < 0 || chunk_end < chunk_begin || expert_stride < chunk_end || off_stride < chunk_end) return MOQAE_E_INVAL;
+    if (!aligned(state, 4) || !aligned(chunk_off, 8)) return MOQAE_E_INVAL;
+    PagedArgs a = {}; fill_pool_geometry(cfg, pool, a);
+    a.expert = const_cast<uint8_t *>(expert); a.expert_stride = expert_stride;
+    a.chunk_off = reinterpret_cast<unsigned long long *>(chunk_off); a.off_stride = off_stride;
+    a.state = static_cast<uint32_t *>(state);
+    a.chunk_begin = chunk_begin; a.n_chunks = chunk_end - chunk_begin;
+    return launch_pool_release(a, row_begin, row_end - row_begin, static_cast<hipStream_t>(stream)) == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
 
 int moqae_decode_attn_planned(const moqae_cfg *cfg, const void *q,
                               const void *arena, const uint64_t *chunk_off, const uint8_t *expert,

@@ -26,6 +26,27 @@ hipError_t launch_pack(const PackArgs &a, hipStream_t s);
 hipError_t launch_append_tail(const void *k_new, const void *v_new, void *K_tail, void *V_tail, int BH, int N, int n_tail,
                               hipStream_t s);
 
+// Paged store: pool j (expert j) = n_pages[j] pages of page_bytes[j] bytes from pool_base[j].  Its free pages sit in
+// kPoolShards rings (page p lives in ring p % kPoolShards, which holds ring_cap[j] entries), so that the atomic steps of
+// a call spread over many addresses.  State words: [0] the status word as it was when the running call began, [1..15]
+// reserved; from word 16 pool j's shard heads then shard tails (2 * kPoolShards words per pool); rings from ring_start[j].
+constexpr int kPoolShards = 256;
+struct PagedArgs {
+    const uint16_t *K, *V; int64_t stride_b, stride_h, stride_s;
+    const uint16_t *W1, *W2, *W3; const float *bias;      // W1 == null: `expert` holds the decisions to use
+    uint8_t *expert; int64_t expert_stride; int32_t *votes;
+    uint8_t *arena; uint32_t *state;
+    unsigned long long *chunk_off; int64_t off_stride; int32_t *status;
+    int chunk_begin, n_chunks, BH, N, G, Hkv, M, freeze_chunks, e16;
+    int bits_of[8];
+    uint32_t n_pages[8], ring_start[8], ring_cap[8], page_bytes[8];
+    unsigned long long pool_base[8];
+};
+hipError_t launch_route_pack_paged(const PagedArgs &a, hipStream_t s);
+hipError_t launch_pool_init(const PagedArgs &a, hipStream_t s);
+hipError_t launch_pool_release(const PagedArgs &a, int row_begin, int n_rows, hipStream_t s);
+hipError_t launch_pool_free_pages(const PagedArgs &a, uint32_t *counts, hipStream_t s);
+
 struct AttnArgs {
     const uint16_t *q; const uint8_t *arena; const uint64_t *chunk_off; const uint8_t *expert;
     int64_t desc_stride;

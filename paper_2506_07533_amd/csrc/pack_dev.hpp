@@ -1,0 +1,201 @@
+// Device code of the quantiser / packer shared by pack_kernel and the fused route + pack kernel.
+#pragma once
+#include "moqae_dev.hpp"
+
+namespace moqae {
+
+// The packed cache is written once and read much later by another kernel: streaming stores keep it
+// from displacing (and later being written back from under) what the caches hold.
+template <typename T> __device__ __forceinline__ void nt_store(T *p, T v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void nt_store(uint4 *p, uint4 v) {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(u4{v.x, v.y, v.z, v.w}, reinterpret_cast<u4 *>(p));
+}
+__device__ __forceinline__ void nt_store(uint2 *p, uint2 v) {
+    typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+    __builtin_nontemporal_store(u2{v.x, v.y}, reinterpret_cast<u2 *>(p));
+}
+
+__device__ __forceinline__ uint4 nt_load(const uint4 *p) {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    const u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(p));
+    return uint4{v[0], v[1], v[2], v[3]};
+}
+
+constexpr int kPackThreads = 256;
+constexpr int kVRow = kD + 4;                        // bytes per token row of the V staging buffer
+
+// Position of the code with in-word index e (b bits): even e in the low half-word, odd e high.
+__device__ __forceinline__ constexpr int code_shift(int e, int b) { return 16 * (e & 1) + b * (e >> 1); }
+
+// Element-wise minimum / maximum of two fp16 pairs (finite inputs).
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t x, uint32_t y) {
+    uint32_t r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t x, uint32_t y) {
+    uint32_t r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+// binary32 sum of one fp16 half of w and c, rounded once: the conversion of the half is exact and rides
+// along in the mixed-precision multiply-add (x * 1 + c), so this is the binary32 subtraction x - (-c).
+__device__ __forceinline__ float add_lo_f16(uint32_t w, float c) {
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float add_hi_f16(uint32_t w, float c) {
+    float r;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(c));
+    return r;
+}
+
+// rint(t) for 0 <= t < 2^22 without a conversion: t + 1.5 * 2^23 is rounded to an integer by the addition
+// itself (ties to even), and the integer sits in the low mantissa bits: bits(result) = kMagicBits + rint(t).
+constexpr float kMagic = 12582912.0f;
+constexpr uint32_t kMagicBits = 0x4B400000u;
+
+// One (token row, group) item of a quantised chunk: G consecutive dims, all in one lane.  No lane ever
+// needs another lane's data: minimum and maximum come from packed fp16 operations on the words as
+// loaded, scale and reciprocal are computed once per group, and a code costs four operations: x - min
+// (with the conversion folded in), * 1/scale, + magic (the rounding), shift-and-add into its word.  The
+// words are sums of bits(t + magic) << shift, i.e. of the codes plus a constant that is taken off at
+// the end; no code is ever masked.  No clamp is needed: the scale is rounded up, so that
+// (x - min) * (1/scale) <= qmax * (1 + 2e-7) and rounds to at most qmax, and x >= min.
+template <int G, int BITS>
+__device__ __forceinline__ void pack_item(const uint4 *__restrict__ p, bool isV, uint32_t *__restrict__ meta_dst,
+                                          uint32_t *__restrict__ k_dst, uint32_t *__restrict__ v_lds) {
+    constexpr int NW = G / 2;                        // input words (fp16 pairs) of the item
+    static_assert(NW >= 16, "G >= 32");
+    uint32_t w[NW];
+#pragma unroll
+    for (int j = 0; j < G / 8; j++) {                // the whole item is requested at once: its 128-byte line arrives once
+        // (ordinary loads: the lane's eight loads share the line through the cache; streaming loads here fetch it eight times)
+        const uint4 t = p[j];
+        w[4 * j] = t.x; w[4 * j + 1] = t.y; w[4 * j + 2] = t.z; w[4 * j + 3] = t.w;
+    }
+    uint32_t mn4[4], mx4[4];                          // four independent chains, folded at the end
+#pragma unroll
+    for (int k = 0; k < 4; k++) { mn4[k] = pk_min_f16(w[k], w[k + 4]); mx4[k] = pk_max_f16(w[k], w[k + 4]); }
+#pragma unroll
+    for (int k = 8; k < NW; k++) { mn4[k & 3] = pk_min_f16(mn4[k & 3], w[k]); mx4[k & 3] = pk_max_f16(mx4[k & 3], w[k]); }
+    const uint32_t mnp = pk_min_f16(pk_min_f16(mn4[0], mn4[1]), pk_min_f16(mn4[2], mn4[3]));
+    const uint32_t mxp = pk_max_f16(pk_max_f16(mx4[0], mx4[1]), pk_max_f16(mx4[2], mx4[3]));
+    float mn = fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16));
+    float mx = fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16));
+    if (mn == 0.0f) mn = 0.0f;                        // -0 is stored as +0
+    if (mx == 0.0f) mx = 0.0f;
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    const float R = __fsub_rn(mx, mn);
+    const float s32 = __fdiv_rn(R, qmax);
+    uint32_t s16 = float_to_half_bits(s32);
+    if (half_bits_to_float(s16) < s32) s16 += 1;      // the scale is rounded up
+    if (s16 == 0) s16 = 0x3C00u;                      // constant group: scale 1
+    const float inv = __fdiv_rn(1.0f, half_bits_to_float(s16));
+    nt_store(meta_dst, s16 | (float_to_half_bits(mn) << 16));
+    const float nmn = -mn;
+    auto ubits = [&](int d) -> uint32_t {             // kMagicBits + code of dim d of the item
+        const float diff = (d & 1) ? add_hi_f16(w[d >> 1], nmn) : add_lo_f16(w[d >> 1], nmn);
+        return __builtin_bit_cast(uint32_t, __fadd_rn(__fmul_rn(diff, inv), kMagic));
+    };
+    if (isV) {                                        // one code per byte into the staging rows
+        constexpr uint32_t KC = kMagicBits * 0x01010101u;
+#pragma unroll
+        for (int k = 0; k < G / 4; k++) {
+            uint32_t acc = ubits(4 * k);
+            acc += ubits(4 * k + 1) << 8; acc += ubits(4 * k + 2) << 16; acc += ubits(4 * k + 3) << 24;
+            v_lds[k] = acc - KC;
+        }
+    } else {                                          // the words of the token-major K layout
+        constexpr int CPW = 32 / BITS, WPL = G / CPW;
+        uint32_t ksum = 0;
+#pragma unroll
+        for (int e = 0; e < CPW; e++) ksum += 1u << code_shift(e, BITS);
+        const uint32_t KC = kMagicBits * ksum;        // constant folded (wraps like the sums do)
+        uint32_t out[WPL];
+#pragma unroll
+        for (int k = 0; k < WPL; k++) {
+            uint32_t acc = ubits(k * CPW);
+#pragma unroll
+            for (int e = 1; e < CPW; e++) acc += ubits(k * CPW + e) << code_shift(e, BITS);
+            out[k] = acc - KC;
+        }
+        if constexpr (WPL >= 4) {
+#pragma unroll
+            for (int k = 0; k < WPL; k += 4)
+                nt_store(reinterpret_cast<uint4 *>(k_dst + k), uint4{out[k], out[k + 1], out[k + 2], out[k + 3]});
+        } else {
+            static_assert(WPL == 2, "G = 32 at 2 bits");
+            nt_store(reinterpret_cast<uint2 *>(k_dst), uint2{out[0], out[1]});
+        }
+    }
+}
+
+// K (isV = 0) or V (isV = 1) of one chunk -> its block `blk` at bit-width `bits`, by one workgroup of NT threads
+// (a multiple of 64).  src: the chunk's first row (row stride stride_s elements); vcodes: N * kVRow bytes of LDS (V only).
+template <int G>
+__device__ __forceinline__ void pack_side(const uint16_t *src, int64_t stride_s, int N, int bits, int isV, uint8_t *blk,
+                                          uint8_t *vcodes, int tid, int NT = kPackThreads) {
+    if (bits == 16) {                                 // FP16 expert: rows copied verbatim
+        const int lane16 = tid & 15, rsub = tid >> 4;
+        uint4 *dst = reinterpret_cast<uint4 *>(blk + (isV ? (size_t)N * kD * 2 : 0));
+        for (int row = rsub; row < N; row += NT / 16)
+            nt_store(&dst[row * 16 + lane16], nt_load(reinterpret_cast<const uint4 *>(src + (int64_t)row * stride_s + lane16 * 8)));
+        return;
+    }
+
+    constexpr int NG = kD / G;                        // groups per row
+    const size_t code_bytes = (size_t)N * kD * bits / 8, meta_bytes = (size_t)N * NG * 4;
+    uint8_t *area = blk + (isV ? code_bytes + meta_bytes : 0);
+    uint32_t *codes_w = reinterpret_cast<uint32_t *>(area);
+    uint32_t *meta_w = reinterpret_cast<uint32_t *>(area + code_bytes);
+
+    // item = (token row, group): consecutive lanes take consecutive 2G-byte pieces of the chunk
+    for (int item = tid; item < N * NG; item += NT) {
+        const int row = item / NG, g = item % NG;
+        const uint4 *p = reinterpret_cast<const uint4 *>(src + (int64_t)row * stride_s + g * G);
+        uint32_t *vl = reinterpret_cast<uint32_t *>(vcodes + row * kVRow + g * G);
+        if (bits == 2)      pack_item<G, 2>(p, isV, &meta_w[item], codes_w + item * (G / 16), vl);
+        else if (bits == 4) pack_item<G, 4>(p, isV, &meta_w[item], codes_w + item * (G / 8), vl);
+        else                pack_item<G, 8>(p, isV, &meta_w[item], codes_w + item * (G / 4), vl);
+    }
+    if (!isV) return;
+
+    __syncthreads();
+    // V: dimension-major tiles of 16*QD slots x 4 words.  A slot holds TQ = max(TW, 8) consecutive tokens
+    // (TW = 32/bits per word, WD = TQ/TW words) of CPK = 4/WD dimensions that lie 16 apart; a token block is
+    // TB = min(4*TQ, N) tokens = QD slices (QD = 4, i.e. 1-KiB tiles, except for 32-token chunks at 2 bits: QD = 2);
+    // slot 16*qd + j of tile cg of a block: dims 16*(cg*CPK + n/WD) + j, token slice qd.
+    const int TW = 32 / bits, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, NCG = kD / (16 * CPK);
+    const int TB = min(4 * TQ, N), QD = TB / TQ;
+    const int n_groups = N * kD * bits / 128;         // a thread builds the words of four adjacent dims at a time
+    for (int g = tid; g < n_groups; g += NT) {
+        const int n = g & 3, jq = (g >> 2) & 3, qd = (g >> 4) & (QD - 1), tile = g / (16 * QD);
+        const int cg = tile % NCG, block = tile / NCG;
+        const int d0 = 16 * (cg * CPK + n / WD) + 4 * jq, t0 = block * TB + qd * TQ + (n % WD) * TW;
+        uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+        for (int e = 0; e < TW; e++) {
+            const uint32_t v4 = *reinterpret_cast<const uint32_t *>(vcodes + (t0 + e) * kVRow + d0);   // codes of dims d0..d0+3
+            const int sh = code_shift(e, bits);
+            w0 |= (v4 & 0xffu) << sh; w1 |= ((v4 >> 8) & 0xffu) << sh; w2 |= ((v4 >> 16) & 0xffu) << sh; w3 |= (v4 >> 24) << sh;
+        }
+        // thread n = 0..3 of a quad holds word n of the slots 16*qd + 4*jq + k, k = 0..3: a 4 x 4 transpose inside
+        // the quad leaves every thread with one whole slot, stored with one 16-byte store
+        uint32_t wk[4] = {w0, w1, w2, w3};
+#pragma unroll
+        for (int k = 0; k < 4; k += 2) {
+            const uint32_t r = dpp_u<DPP_XOR1>((n & 1) ? wk[k] : wk[k + 1]);
+            if (n & 1) wk[k] = r; else wk[k + 1] = r;
+        }
+#pragma unroll
+        for (int k = 0; k < 2; k++) {
+            const uint32_t r = dpp_u<DPP_XOR2>((n & 2) ? wk[k] : wk[k + 2]);
+            if (n & 2) wk[k] = r; else wk[k + 2] = r;
+        }
+        nt_store(reinterpret_cast<uint4 *>(codes_w + (tile * 16 * QD + 16 * qd + 4 * jq + n) * 4), uint4{wk[0], wk[1], wk[2], wk[3]});
+    }
+}
+
+}  // namespace moqae

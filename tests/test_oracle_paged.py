@@ -25,9 +25,9 @@ def test_pool_geometry_closed_form(ref):
     assert [ref.pool_base(cfg, pages, j) for j in range(4)] == [0, 51200, 51200 + 55296, 51200 + 55296 + 69632]
     assert ref.pool_arena_bytes(cfg, pages) == 51200 + 55296 + 69632 + 7 * 65536
     st = ref.pool_init(cfg, pages)
-    assert st.size == 16 + sum(pages)
+    assert st.size == 32 + sum(pages)
     assert list(st[:8]) == [0] * 8 and list(st[8:16]) == [5, 3, 2, 7, 0, 0, 0, 0]
-    assert list(st[16:]) == [0, 1, 2, 3, 4, 0, 1, 2, 0, 1, 0, 1, 2, 3, 4, 5, 6]
+    assert list(st[32:]) == [0, 1, 2, 3, 4, 0, 1, 2, 0, 1, 0, 1, 2, 3, 4, 5, 6]
 
 
 def test_pages_follow_the_ring_model_and_hold_the_chunk_blocks(ref):
