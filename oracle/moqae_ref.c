@@ -41,6 +41,9 @@
  *   decode attention   : 16-bit experts == unquantised attention (torch fp64
  *                        scaled_dot_product_attention), S = 1, uniform keys,
  *                        score-shift invariance
+ *   router loss (3)-(5): gradient against central finite differences of the loss
+ *                        in binary64, one expert (p = 1: constant loss, zero
+ *                        gradient), lambda = 0 / 1 limits, linearity in L_nll
  *   paged store        : pool sizes and bases by closed form; a set model of the
  *                        allocator written in the test (pages handed out in ring
  *                        order, given-back pages reused first-in first-out, no
@@ -659,6 +662,90 @@ int moqae_decode_attn_ref(const moqae_ref_cfg *cfg,
         free(Kh); free(Vh); free(sc);
     }
     return bad ? REF_E_INVAL : REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Router fine-tuning loss (Sec. 3.3, Eq. (3)-(5)) and its gradient.    */
+/*   L_model = (1/T) sum_i [argmax_k p^i_k = j] p^i_j L_nll / B_j       */
+/*   L_mem   = (1/T) sum_i [argmax_k p^i_k = j] 16 p^i_j / B_j          */
+/*   L       = lambda L_model + (1 - lambda) L_mem                      */
+/* Readings: i runs over the router's outputs, one per cached key row   */
+/* (Eq. (1) gives one row of P per token), T of them in all; p^i is the */
+/* softmax of the token's logits (the text calls them probabilities,    */
+/* Eq. (1) has no softmax); the indicator picks the token's own top-1   */
+/* expert j, so a token contributes p^i_j times the penalty of j; L_nll */
+/* is the frozen model's loss of the token's sequence (an input here:   */
+/* one value per sequence); the two penalty vectors are inputs          */
+/* (1/B_j and 16/B_j as printed; the text under Eq. (4) describes the   */
+/* second as inverted, which B_j/16 would be).  The top-1 index is      */
+/* taken from the router's binary32 logits exactly as in routing; given */
+/* it, loss and gradient are evaluated in binary64.                     */
+/* Gradient: dL/dlogit_k = w_j p_j (delta_jk - p_k) / T with            */
+/* w_j = lambda L_nll pen_model_j + (1-lambda) pen_mem_j, then back     */
+/* through logit = h W3 + bias, h = SiLU(z), z = (x W1) * (x W2).       */
+/* ------------------------------------------------------------------ */
+int moqae_router_loss_grad_ref(const moqae_ref_cfg *cfg,
+                               const uint16_t *K, int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                               int32_t token_begin, int32_t token_end,
+                               const uint16_t *W1, const uint16_t *W2, const uint16_t *W3, const float *logit_bias,
+                               const float *nll, const float *pen_model, const float *pen_mem, double lambda,
+                               double *loss3, double *dW1, double *dW2, double *dW3, double *dbias)
+{
+    if (!cfg_ok(cfg) || !K || !W1 || !W2 || !W3 || !nll || !pen_model || !pen_mem || !loss3 || !dW1 || !dW2 || !dW3) return REF_E_INVAL;
+    if (token_begin < 0 || token_end <= token_begin) return REF_E_INVAL;
+    const int D = cfg->head_dim, M = cfg->n_experts;
+    float *w1 = malloc(sizeof(float) * D * M), *w2 = malloc(sizeof(float) * D * M), w3[64];
+    float *x = malloc(sizeof(float) * D);
+    for (int i = 0; i < D * M; i++) { w1[i] = H2F(W1[i]); w2[i] = H2F(W2[i]); }
+    for (int i = 0; i < M * M; i++) w3[i] = H2F(W3[i]);
+    const double T = (double)cfg->batch * cfg->n_kv_heads * (double)(token_end - token_begin);
+    loss3[0] = loss3[1] = loss3[2] = 0.0;
+    for (int i = 0; i < D * M; i++) { dW1[i] = 0.0; dW2[i] = 0.0; }
+    for (int i = 0; i < M * M; i++) dW3[i] = 0.0;
+    if (dbias) for (int k = 0; k < M; k++) dbias[k] = 0.0;
+    for (int64_t b = 0; b < cfg->batch; b++) for (int64_t h = 0; h < cfg->n_kv_heads; h++)
+    for (int64_t t = token_begin; t < token_end; t++) {
+        const uint16_t *row = K + b * stride_b + h * stride_h + t * stride_s;
+        for (int d = 0; d < D; d++) x[d] = H2F(row[d]);
+        float p32[8];
+        router_token_logits(x, D, M, w1, w2, w3, logit_bias, p32);     /* the routing arithmetic decides the expert */
+        int j = 0;
+        for (int k = 1; k < M; k++) if (p32[k] > p32[j]) j = k;
+        /* forward in binary64 */
+        double a[8], bb[8], z[8], sg[8], hh[8], lg[8], p[8];
+        for (int m = 0; m < M; m++) {
+            a[m] = 0.0; bb[m] = 0.0;
+            for (int d = 0; d < D; d++) { a[m] += (double)x[d] * w1[d * M + m]; bb[m] += (double)x[d] * w2[d * M + m]; }
+            z[m] = a[m] * bb[m]; sg[m] = 1.0 / (1.0 + exp(-z[m])); hh[m] = z[m] * sg[m];
+        }
+        double mx = -INFINITY, den = 0.0;
+        for (int k = 0; k < M; k++) {
+            lg[k] = logit_bias ? (double)logit_bias[k] : 0.0;
+            for (int m = 0; m < M; m++) lg[k] += hh[m] * w3[m * M + k];
+            if (lg[k] > mx) mx = lg[k];
+        }
+        for (int k = 0; k < M; k++) { p[k] = exp(lg[k] - mx); den += p[k]; }
+        for (int k = 0; k < M; k++) p[k] /= den;
+        const double lm = p[j] * (double)nll[b] * (double)pen_model[j], le = p[j] * (double)pen_mem[j];
+        loss3[1] += lm / T; loss3[2] += le / T;
+        /* backward */
+        const double w = lambda * (double)nll[b] * (double)pen_model[j] + (1.0 - lambda) * (double)pen_mem[j];
+        double dl[8], dh[8];
+        for (int k = 0; k < M; k++) dl[k] = w * p[j] * ((k == j ? 1.0 : 0.0) - p[k]) / T;
+        for (int m = 0; m < M; m++) {
+            dh[m] = 0.0;
+            for (int k = 0; k < M; k++) { dh[m] += dl[k] * w3[m * M + k]; dW3[m * M + k] += hh[m] * dl[k]; }
+        }
+        if (dbias) for (int k = 0; k < M; k++) dbias[k] += dl[k];
+        for (int m = 0; m < M; m++) {
+            const double dz = dh[m] * (sg[m] * (1.0 + z[m] * (1.0 - sg[m])));    /* d SiLU(z) / dz */
+            const double da = dz * bb[m], db = dz * a[m];
+            for (int d = 0; d < D; d++) { dW1[d * M + m] += (double)x[d] * da; dW2[d * M + m] += (double)x[d] * db; }
+        }
+    }
+    loss3[0] = lambda * loss3[1] + (1.0 - lambda) * loss3[2];
+    free(w1); free(w2); free(x);
+    return REF_OK;
 }
 
 int moqae_ref_num_threads(void)

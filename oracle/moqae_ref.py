@@ -282,6 +282,27 @@ def pool_release(cfg: RefCfg, n_pages: Sequence[int], expert: np.ndarray, chunk_
         raise ValueError(f"moqae_pool_release_ref -> {rc}")
 
 
+def router_loss_grad(cfg: RefCfg, K: np.ndarray, token_begin: int, token_end: int, W1, W2, W3, bias, nll: np.ndarray,
+                     pen_model: np.ndarray, pen_mem: np.ndarray, lam: float):
+    """Eq. (3)-(5) over tokens [token_begin, token_end) of every (b, h).  Returns (loss[3] = L, L_model, L_mem,
+    dW1 [D, M], dW2 [D, M], dW3 [M, M], dbias [M]) in float64."""
+    K = _h(K); W1 = _h(W1); W2 = _h(W2); W3 = _h(W3)
+    sb, sh, ss = _kv_strides(K, cfg)
+    M, D = len(cfg.expert_bits), cfg.head_dim
+    nll = np.ascontiguousarray(nll, np.float32); pen_model = np.ascontiguousarray(pen_model, np.float32)
+    pen_mem = np.ascontiguousarray(pen_mem, np.float32)
+    assert nll.shape == (cfg.batch,) and pen_model.shape == (M,) and pen_mem.shape == (M,)
+    b = None if bias is None else np.ascontiguousarray(bias, np.float32)
+    loss = np.zeros(3); dW1 = np.zeros((D, M)); dW2 = np.zeros((D, M)); dW3 = np.zeros((M, M)); db = np.zeros(M)
+    rc = lib().moqae_router_loss_grad_ref(C.byref(cfg.c()), _p(K), C.c_int64(sb), C.c_int64(sh), C.c_int64(ss),
+                                          C.c_int32(token_begin), C.c_int32(token_end), _p(W1), _p(W2), _p(W3), _p(b),
+                                          _p(nll), _p(pen_model), _p(pen_mem), C.c_double(lam),
+                                          _p(loss), _p(dW1), _p(dW2), _p(dW3), _p(db))
+    if rc != 0:
+        raise ValueError(f"moqae_router_loss_grad_ref -> {rc}")
+    return loss, dW1, dW2, dW3, db
+
+
 def decode_attn(cfg: RefCfg, q: np.ndarray, arena: Optional[np.ndarray], chunk_off: Optional[np.ndarray],
                 expert: Optional[np.ndarray], n_chunks: int,
                 K_tail: Optional[np.ndarray], V_tail: Optional[np.ndarray], n_tail: int,
