@@ -325,6 +325,27 @@ def bench_layer(args, w):
         res["route_pack_paged_chunks_per_s"] = round(n_units / (t_f.mean() * 1e-3), 1)
         del p_arena
 
+    if not args.decode_only:
+        # router fine-tuning (Sec. 3.3): loss and gradient over every cached key row of the layer, synthetic L_nll
+        nll = torch.full((w.batch,), 2.0, dtype=torch.float32, device=dev)
+        loss = torch.zeros(3, dtype=torch.float32, device=dev)
+        g1 = torch.zeros((w.head_dim, M), dtype=torch.float32, device=dev); g2 = torch.zeros_like(g1)
+        g3 = torch.zeros((M, M), dtype=torch.float32, device=dev); gb = torch.zeros(M, dtype=torch.float32, device=dev)
+        tev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for i in range(12):
+            if i >= 2: tev[i - 2][0].record()
+            mq.router_loss_grad(cfg, K, 0, C * w.chunk, W1, W2, W3, None, nll, None, None, 0.5, loss, g1, g2, g3, gb)
+            if i >= 2: tev[i - 2][1].record()
+        torch.cuda.synchronize()
+        t_t = np.array([a.elapsed_time(b) for a, b in tev])
+        rows = BH * C * w.chunk
+        flop = rows * (8 * M * w.head_dim)               # 2*M*D multiply-adds forward and as many for dW1, dW2
+        tf = flop / (t_t.mean() * 1e-3) / 1e12
+        res["router_train"] = {"bound": "alu", "achieved": round(tf, 2), "peak": 157.3, "unit": "TFLOP/s", "frac": round(tf / 157.3, 4),
+                               "rows": rows, "flop_per_row": 8 * M * w.head_dim, "avg_ms": round(float(t_t.mean()), 4),
+                               "min_ms": round(float(t_t.min()), 4), "rows_per_s": round(rows / (t_t.mean() * 1e-3), 1),
+                               "kernel": "router_train_kernel (Eq. (3)-(5): loss + gradient, binary32)", "loss": [round(float(v), 6) for v in loss.cpu()]}
+
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, scale)
     return res

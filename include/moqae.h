@@ -223,6 +223,27 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
 uint64_t moqae_decode_workspace_bytes_ragged(const moqae_cfg *cfg, int32_t max_chunks);   /* host; 0 if cfg invalid */
 
 /*
+ * Router fine-tuning, Sec. 3.3: the loss of Eq. (3)-(5) and its gradient with respect to the router weights, over
+ * the cached key rows [token_begin, token_end) of every (b, h) (T rows in all), with the language model frozen:
+ *   L_model = (1/T) sum_i p^i_j * L_nll * penalty_model[j],   L_mem = (1/T) sum_i p^i_j * penalty_mem[j],
+ *   L = lambda * L_model + (1 - lambda) * L_mem,
+ * where p^i = softmax of the logits of row i (Eq. (1)), j = its top-1 expert (the routing decision, taken in the
+ * same binary32 arithmetic as moqae_route_chunks), and L_nll = nll[b], the frozen model's loss of the row's
+ * sequence (device fp32 [B]; an input, here synthetic).  penalty_model, penalty_mem: HOST fp32 [M], or NULL for
+ * the values Eq. (3) and Eq. (4) print, 1/B_j and 16/B_j (the text under Eq. (4) describes its penalty as the
+ * inverse of Eq. (3)'s, which B_j/16 would be: pass it explicitly if that is wanted).
+ * Out (device fp32, overwritten): loss[3] = L, L_model, L_mem; dW1, dW2 [D, M]; dW3 [M, M]; dbias [M] or NULL.
+ * Evaluated in binary32; sums over rows are added in no fixed order (results agree to rounding, not bit for bit).
+ */
+int moqae_router_loss_grad(const moqae_cfg *cfg,
+                           const void *K, int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                           int32_t token_begin, int32_t token_end,
+                           const void *W1, const void *W2, const void *W3, const float *logit_bias,
+                           const float *nll, const float *penalty_model, const float *penalty_mem, float lambda,
+                           float *loss, float *dW1, float *dW2, float *dW3, float *dbias,
+                           void *stream);
+
+/*
  * Paged store.  The ordered arena of moqae_quantize_pack puts a chunk's block where the blocks of all earlier
  * chunks end, so nothing can be packed before every chunk of the call is routed, and nothing can ever be given
  * back.  Here every expert has a pool of equal pages instead: pool j = n_pages[j] pages of

@@ -63,7 +63,8 @@ EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "mo
            "moqae_decode_plan", "moqae_decode_attn_planned", "moqae_append_tail",
            "moqae_decode_attn_static", "moqae_static_scratch_bytes",
            "moqae_pool_page_bytes", "moqae_pool_base", "moqae_pool_arena_bytes", "moqae_pool_state_bytes",
-           "moqae_pool_init", "moqae_route_pack_paged", "moqae_pool_release", "moqae_pool_free_pages"]
+           "moqae_pool_init", "moqae_route_pack_paged", "moqae_pool_release", "moqae_pool_free_pages",
+           "moqae_router_loss_grad"]
 # measurement aids of include/moqae_bench.h (bench.py only)
 BENCH_EXPORTS = ["moqae_bench_time_decode_kernel", "moqae_bench_stream_read", "moqae_bench_stream_sink_words"]
 
@@ -104,6 +105,9 @@ def lib():
         L.moqae_route_pack_paged.restype = C.c_int
         L.moqae_route_pack_paged.argtypes = [C.POINTER(_Cfg), pcp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, i64, vp,
                                              vp, vp, vp, i64, vp, vp]
+        L.moqae_router_loss_grad.restype = C.c_int
+        L.moqae_router_loss_grad.argtypes = [C.POINTER(_Cfg), vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp,
+                                             C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_float, vp, vp, vp, vp, vp, vp]
         L.moqae_pool_free_pages.restype = C.c_int
         L.moqae_pool_free_pages.argtypes = [C.POINTER(_Cfg), pcp, vp, vp, vp]
         L.moqae_pool_release.restype = C.c_int
@@ -210,6 +214,30 @@ def quantize_pack(cfg: Cfg, K: torch.Tensor, V: torch.Tensor, chunk_begin: int, 
                                      sb, sh, ss, chunk_begin, chunk_end, _ptr(expert), expert.shape[1],
                                      _ptr(arena), arena.numel(), _ptr(arena_used), _ptr(chunk_off), chunk_off.shape[1],
                                      _ptr(status), _stream()), "moqae_quantize_pack")
+
+
+def router_loss_grad(cfg: Cfg, K: torch.Tensor, token_begin: int, token_end: int, W1: torch.Tensor, W2: torch.Tensor,
+                     W3: torch.Tensor, bias: Optional[torch.Tensor], nll: torch.Tensor,
+                     penalty_model: Optional[Sequence[float]], penalty_mem: Optional[Sequence[float]], lam: float,
+                     loss: torch.Tensor, dW1: torch.Tensor, dW2: torch.Tensor, dW3: torch.Tensor,
+                     dbias: Optional[torch.Tensor]) -> None:
+    """Eq. (3)-(5) and their gradient (moqae_router_loss_grad).  nll: fp32 [B]; loss: fp32 [3]; dW1, dW2: fp32 [D, M];
+    dW3: fp32 [M, M]; dbias: fp32 [M] or None; penalties: host sequences of M floats or None (the printed ones)."""
+    sb, sh, ss = _kv_strides(K, cfg)
+    M = len(cfg.expert_bits)
+    assert 0 <= token_begin < token_end <= K.shape[2]
+    for w in (W1, W2, W3):
+        assert w.is_cuda and w.dtype == torch.float16 and w.is_contiguous()
+    assert nll.is_cuda and nll.dtype == torch.float32 and nll.shape == (cfg.batch,)
+    for t, shape in ((loss, (3,)), (dW1, (cfg.head_dim, M)), (dW2, (cfg.head_dim, M)), (dW3, (M, M))):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape
+    if dbias is not None:
+        assert dbias.is_cuda and dbias.dtype == torch.float32 and tuple(dbias.shape) == (M,)
+    arr = lambda p: None if p is None else (C.c_float * M)(*[float(v) for v in p])
+    _check(lib().moqae_router_loss_grad(C.byref(cfg.c()), _ptr(K), sb, sh, ss, token_begin, token_end, _ptr(W1), _ptr(W2), _ptr(W3),
+                                        _ptr(bias), _ptr(nll), arr(penalty_model), arr(penalty_mem), float(lam),
+                                        _ptr(loss), _ptr(dW1), _ptr(dW2), _ptr(dW3), _ptr(dbias), _stream()),
+           "moqae_router_loss_grad")
 
 
 def pool_page_bytes(cfg: Cfg, expert: int) -> int:

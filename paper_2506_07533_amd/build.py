@@ -7,7 +7,7 @@ import subprocess
 _PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_PKG, "csrc")
 LIB = os.path.join(_PKG, "libmoqae.so")
-SOURCES = ["route.hip", "pack.hip", "attn.hip", "api.hip", "stream_probe.hip", "fused.hip"]
+SOURCES = ["route.hip", "pack.hip", "attn.hip", "api.hip", "stream_probe.hip", "fused.hip", "train.hip"]
 # -ffp-contract=off: routing and packing are specified with one rounding per operation;
 # fused multiply-adds are written explicitly where they are wanted.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off", "-fPIC", "-shared",

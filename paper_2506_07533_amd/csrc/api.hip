@@ -385,6 +385,34 @@ int moqae_pool_release(const moqae_cfg *cfg, const moqae_pool_cfg *pool,
     return launch_pool_release(a, row_begin, row_end - row_begin, static_cast<hipStream_t>(stream)) == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
 }
 
+int moqae_router_loss_grad(const moqae_cfg *cfg,
+                           const void *K, int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                           int32_t token_begin, int32_t token_end,
+                           const void *W1, const void *W2, const void *W3, const float *logit_bias,
+                           const float *nll, const float *penalty_model, const float *penalty_mem, float lambda,
+                           float *loss, float *dW1, float *dW2, float *dW3, float *dbias, void *stream) {
+    if (!cfg_ok(cfg) || !K || !W1 || !W2 || !W3 || !nll || !loss || !dW1 || !dW2 || !dW3) return MOQAE_E_INVAL;
+    if (token_begin < 0 || token_end <= token_begin) return MOQAE_E_INVAL;
+    if (!strides_ok(cfg, stride_b, stride_h, stride_s) || !aligned(K, 16)) return MOQAE_E_INVAL;
+    if (!aligned(W1, 4) || !aligned(W2, 4) || !aligned(W3, 2) || !aligned(nll, 4) || !aligned(loss, 4)) return MOQAE_E_INVAL;
+    if (!aligned(dW1, 4) || !aligned(dW2, 4) || !aligned(dW3, 4) || !aligned(dbias, 4)) return MOQAE_E_INVAL;
+    TrainArgs a = {};
+    a.K = static_cast<const uint16_t *>(K); a.stride_b = stride_b; a.stride_h = stride_h; a.stride_s = stride_s;
+    a.W1 = static_cast<const uint16_t *>(W1); a.W2 = static_cast<const uint16_t *>(W2); a.W3 = static_cast<const uint16_t *>(W3);
+    a.bias = logit_bias; a.nll = nll;
+    for (int j = 0; j < 8; j++) {                         // defaults: the penalties as Eq. (3) and Eq. (4) print them
+        const float bj = j < cfg->n_experts ? (float)cfg->expert_bits[j] : 16.0f;
+        a.pen_model[j] = (penalty_model && j < cfg->n_experts) ? penalty_model[j] : 1.0f / bj;
+        a.pen_mem[j] = (penalty_mem && j < cfg->n_experts) ? penalty_mem[j] : 16.0f / bj;
+    }
+    a.lambda = lambda;
+    a.token_begin = token_begin; a.n_tok = token_end - token_begin;
+    a.BH = cfg->batch * cfg->n_kv_heads; a.Hkv = cfg->n_kv_heads; a.M = cfg->n_experts;
+    a.inv_T = (float)(1.0 / ((double)a.BH * (double)a.n_tok));
+    a.loss3 = loss; a.dW1 = dW1; a.dW2 = dW2; a.dW3 = dW3; a.dbias = dbias;
+    return launch_router_train(a, cu_count(), static_cast<hipStream_t>(stream)) == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
+}
+
 int moqae_decode_attn_planned(const moqae_cfg *cfg, const void *q,
                               const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
                               int64_t desc_stride, int32_t n_chunks,

@@ -47,6 +47,15 @@ hipError_t launch_pool_init(const PagedArgs &a, hipStream_t s);
 hipError_t launch_pool_release(const PagedArgs &a, int row_begin, int n_rows, hipStream_t s);
 hipError_t launch_pool_free_pages(const PagedArgs &a, uint32_t *counts, hipStream_t s);
 
+struct TrainArgs {
+    const uint16_t *K; int64_t stride_b, stride_h, stride_s;
+    const uint16_t *W1, *W2, *W3; const float *bias; const float *nll;
+    float pen_model[8], pen_mem[8]; float lambda, inv_T;
+    int token_begin, n_tok, BH, Hkv, M;
+    float *loss3, *dW1, *dW2, *dW3, *dbias;
+};
+hipError_t launch_router_train(const TrainArgs &a, int n_cu, hipStream_t s);
+
 struct AttnArgs {
     const uint16_t *q; const uint8_t *arena; const uint64_t *chunk_off; const uint8_t *expert;
     int64_t desc_stride;
