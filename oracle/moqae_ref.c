@@ -62,6 +62,8 @@ typedef struct {
     int32_t n_experts;      /* M                                                   */
     int32_t expert_bits[8]; /* bit-width B_j of expert j, each in {2,4,8,16}       */
     int32_t freeze_chunks;  /* RF: chunks c < freeze_chunks are FP16, never routed */
+    int32_t k_per_channel;  /* 0: K groups = G consecutive dims of a token (as V);    */
+                            /* 1: K groups = G consecutive tokens of one dim          */
 } moqae_ref_cfg;
 
 enum { REF_OK = 0, REF_E_INVAL = -1, REF_E_ARENA = -3 };
@@ -154,6 +156,8 @@ static int cfg_ok(const moqae_ref_cfg *c)
     if (c->n_experts < 1 || c->n_experts > 8) return 0;
     for (int j = 0; j < c->n_experts; j++) if (!bits_ok(c->expert_bits[j])) return 0;
     if (c->freeze_chunks < 0) return 0;
+    if (c->k_per_channel != 0 && c->k_per_channel != 1) return 0;
+    if (c->k_per_channel && c->chunk % c->group) return 0;        /* token groups must tile the chunk */
     return 1;
 }
 
@@ -269,7 +273,9 @@ int moqae_route_chunks_ref(const moqae_ref_cfg *cfg,
 /* bit-width its router chose; the formula is this build's own):        */
 /* per token row, per group of G consecutive head-dim elements,         */
 /* asymmetric uniform, scale and zero kept as fp16.  Inputs must be     */
-/* finite: Inf / NaN have no defined codes.                             */
+/* finite: Inf / NaN have no defined codes.  With k_per_channel the     */
+/* keys' groups run along tokens instead (G tokens of one dim), the     */
+/* values' groups stay as they are.                                     */
 /* ------------------------------------------------------------------ */
 
 /* One group: x[G] fp16 bit patterns in, codes[G] out, *meta = scale | zero<<16. */
@@ -373,14 +379,33 @@ void moqae_ref_pack_chunk(const moqae_ref_cfg *cfg, int bits,
     uint8_t *v_codes = k_meta + meta_bytes, *v_meta = v_codes + code_bytes;
     memset(blk, 0, 2 * (code_bytes + meta_bytes));
     uint8_t *codes = malloc((size_t)G);
+    /* Keys quantised per channel (the outlier channels of key caches that Sec. 2.2 quotes from KIVI make a group
+     * of dims share one huge range; along tokens a channel is homogeneous): a group is G consecutive tokens of one
+     * dim, its meta word sits at [token group][dim]; the codes keep their token-major places.                     */
+    if (cfg->k_per_channel) {
+        uint16_t *col = malloc(sizeof(uint16_t) * (size_t)G);
+        for (int tg = 0; tg < N / G; tg++) for (int d = 0; d < D; d++) {
+            uint32_t meta, word; int bit;
+            for (int i = 0; i < G; i++) col[i] = Kc[(int64_t)(tg * G + i) * ss + d];
+            moqae_ref_quantize_group(col, G, bits, codes, &meta);
+            memcpy(k_meta + 4u * (size_t)(tg * D + d), &meta, 4);
+            for (int i = 0; i < G; i++) {
+                k_code_pos(tg * G + i, d, D, bits, &word, &bit);
+                put_code(k_codes, word, bit, codes[i]);
+            }
+        }
+        free(col);
+    }
     for (int t = 0; t < N; t++) {
         for (int g = 0; g < NG; g++) {
             uint32_t meta, word; int bit;
-            moqae_ref_quantize_group(Kc + t * ss + g * G, G, bits, codes, &meta);
-            memcpy(k_meta + 4u * (size_t)(t * NG + g), &meta, 4);
-            for (int i = 0; i < G; i++) {
-                k_code_pos(t, g * G + i, D, bits, &word, &bit);
-                put_code(k_codes, word, bit, codes[i]);
+            if (!cfg->k_per_channel) {
+                moqae_ref_quantize_group(Kc + t * ss + g * G, G, bits, codes, &meta);
+                memcpy(k_meta + 4u * (size_t)(t * NG + g), &meta, 4);
+                for (int i = 0; i < G; i++) {
+                    k_code_pos(t, g * G + i, D, bits, &word, &bit);
+                    put_code(k_codes, word, bit, codes[i]);
+                }
             }
             moqae_ref_quantize_group(Vc + t * ss + g * G, G, bits, codes, &meta);
             memcpy(v_meta + 4u * (size_t)(t * NG + g), &meta, 4);
@@ -411,7 +436,7 @@ void moqae_ref_decode_chunk(const moqae_ref_cfg *cfg, int bits, const uint8_t *b
     const uint8_t *v_codes = k_meta + meta_bytes, *v_meta = v_codes + code_bytes;
     for (int t = 0; t < N; t++) for (int d = 0; d < D; d++) {
         uint32_t mk, mv, word; int bit;
-        memcpy(&mk, k_meta + 4u * (size_t)(t * NG + d / G), 4);
+        memcpy(&mk, k_meta + 4u * (size_t)(cfg->k_per_channel ? (t / G) * D + d : t * NG + d / G), 4);
         memcpy(&mv, v_meta + 4u * (size_t)(t * NG + d / G), 4);
         k_code_pos(t, d, D, bits, &word, &bit);
         Kh[t * D + d] = (double)get_code(k_codes, word, bit, bits) * (double)H2F((uint16_t)(mk & 0xffffu))

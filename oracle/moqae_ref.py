@@ -37,7 +37,7 @@ class _Cfg(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("chunk", C.c_int32), ("group", C.c_int32),
                 ("n_experts", C.c_int32), ("expert_bits", C.c_int32 * 8),
-                ("freeze_chunks", C.c_int32)]
+                ("freeze_chunks", C.c_int32), ("k_per_channel", C.c_int32)]
 
 
 @dataclass
@@ -50,11 +50,12 @@ class RefCfg:
     group: int = 64
     expert_bits: Sequence[int] = field(default_factory=lambda: (2, 4, 8, 16))
     freeze_chunks: int = 1
+    k_per_channel: int = 0
 
     def c(self) -> _Cfg:
         bits = list(self.expert_bits) + [0] * (8 - len(self.expert_bits))
         return _Cfg(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.chunk,
-                    self.group, len(self.expert_bits), (C.c_int32 * 8)(*bits), self.freeze_chunks)
+                    self.group, len(self.expert_bits), (C.c_int32 * 8)(*bits), self.freeze_chunks, self.k_per_channel)
 
 
 _lib = None

@@ -242,6 +242,7 @@ def _read_words():
             continue
         if t[0] == "case":
             shape = tuple(int(v) for v in t[3:6]) if len(t) >= 6 else (64, 64, 64)
+            shape += (1 if t[-1] == "kpc" else 0,)
             cur = cases.setdefault((t[1], int(t[2]), shape), [])
         elif t[0] == "word":
             cur.append((t[1], int(t[2]), int(t[3], 16)))
@@ -260,6 +261,7 @@ _GEN = {
     "n32_k_dt_v_3dt": (lambda t, d: (d + t) % 4, lambda t, d: (3 * d + t + t // 16) % 4),
     "n32_g32_zero": (lambda t, d: (d + t) % 16 + d // 32 + 4 * (t % 4),
                      lambda t, d: (d + 5 * t + t // 8) % 16 + 2 * (d // 32) + t % 2),
+    "n128_kpc": (lambda t, d: (t + d) % 4 + d % 4 + 4 * (t // 64), lambda t, d: (3 * d + t + t // 64) % 4),
     "n128_k_7dt_v_3d11t": (lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (7 * d + t) % 256)),
                            lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (3 * d + 11 * t + t // 32) % 256))),
 }
@@ -269,9 +271,10 @@ def test_pack_words_golden(ref):
     """A wrong bit position, word order, tile stride or area order moves these words."""
     cases = _read_words()
     assert any(shape[1] == 128 for (_, _, shape) in cases), "no case at the head size the library ships"
-    for (name, bits, (N, D, G)), probes in cases.items():
+    assert any(shape[3] for (_, _, shape) in cases), "no per-channel case"
+    for (name, bits, (N, D, G, kpc)), probes in cases.items():
         t, d = np.meshgrid(np.arange(N), np.arange(D), indexing="ij")
-        cfg = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0)
+        cfg = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0, kpc)
         fk, fv = _GEN[name]
         blk = ref.pack_chunk(cfg, bits, fk(t, d).astype(np.float16), fv(t, d).astype(np.float16))
         cb, mb = N * D * bits // 8, N * (D // G) * 4
@@ -481,3 +484,69 @@ def test_attention_special_cases(ref):
     for hq in range(2):
         best = (Kh @ q[0, hq].astype(np.float64)).argmax()
         assert np.allclose(outb[0, hq], Vh[best], atol=1e-6)
+
+
+# ----------------------------------------------------------------------------
+# keys quantised per channel (k_per_channel)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits,G,N", [(2, 64, 128), (4, 32, 64), (8, 64, 64), (2, 32, 32)])
+def test_per_channel_keys_roundtrip_and_meta(ref, bits, G, N):
+    """Groups run along tokens: zero = minimum of the G tokens of a dim, |x - x^| <= scale/2, meta at [token group][dim];
+    the values and the places of the key codes are untouched by the flag."""
+    rng = np.random.default_rng(bits + N)
+    D = 128
+    cfg = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0, 1)
+    cfg0 = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0, 0)
+    Kc = rng.standard_normal((N, D)).astype(np.float32); Kc[:, [3, 50, 77, 120]] *= 10
+    Kc = Kc.astype(np.float16); Vc = rng.standard_normal((N, D)).astype(np.float16)
+    blk = ref.pack_chunk(cfg, bits, Kc, Vc); blk0 = ref.pack_chunk(cfg0, bits, Kc, Vc)
+    cb, mb = N * D * bits // 8, N * (D // G) * 4
+    assert blk.size == blk0.size == 2 * (cb + mb)
+    assert np.array_equal(blk[cb + mb:], blk0[cb + mb:])                 # the V half does not depend on the flag
+    Kh, Vh = ref.decode_chunk(cfg, bits, blk)
+    meta = blk[cb:cb + mb].view("<u4").reshape(N // G, D)
+    s = (meta & 0xffff).astype(np.uint16).view(np.float16).astype(np.float64)
+    z = (meta >> 16).astype(np.uint16).view(np.float16).astype(np.float64)
+    xg = Kc.astype(np.float64).reshape(N // G, G, D)
+    assert np.array_equal(z, xg.min(1))
+    rng_ = xg.max(1) - xg.min(1)
+    assert np.all(s >= rng_ / ((1 << bits) - 1) * (1 - 1e-7)) and np.all(s <= rng_ / ((1 << bits) - 1) * (1 + 2.0 ** -10) + 2.0 ** -24)
+    err = np.abs(Kh.reshape(N // G, G, D) - xg)
+    assert (err <= 0.5001 * s[:, None, :]).all()
+    # every group is what the (pinned) group quantiser makes of the G tokens of the dim; codes sit where the per-token layout puts them
+    for tg, d in [(0, 0), (N // G - 1, 50), (0, 127)]:
+        codes, m = ref.quantize_group(np.ascontiguousarray(Kc[tg * G:(tg + 1) * G, d]), bits)
+        assert int(meta[tg, d]) == m
+        k = np.round((Kh[tg * G:(tg + 1) * G, d] - z[tg, d]) / s[tg, d]).astype(np.int64)
+        assert np.array_equal(k, codes.astype(np.int64))
+    # the outlier channels no longer blow up the error of their neighbours: per channel beats per token on this K
+    Kh0, _ = ref.decode_chunk(cfg0, bits, blk0)
+    if N >= 64:
+        assert np.abs(Kh - Kc).mean() < np.abs(Kh0 - Kc).mean()
+
+
+def test_per_channel_attention_is_attention_over_the_decoded_cache(ref):
+    rng = np.random.default_rng(21)
+    B, Hq, Hkv, N, G, C, T = 1, 2, 2, 64, 64, 5, 9
+    cfg = ref.RefCfg(B, Hq, Hkv, 128, N, G, (2, 4, 8, 16), 0, 1)
+    S = C * N + T
+    K = rng.standard_normal((B, Hkv, S, 128)).astype(np.float16); V = rng.standard_normal((B, Hkv, S, 128)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, 128)).astype(np.float16)
+    expert = rng.integers(0, 4, (B * Hkv, C)).astype(np.uint8)
+    cap = C * B * Hkv * 32768 + 4096
+    arena = np.zeros(cap, np.uint8); used = np.zeros(1, np.uint64); off = np.zeros((B * Hkv, C), np.uint64)
+    assert ref.quantize_pack(cfg, K, V, 0, C, expert, arena, used, off) == 0
+    Kt = np.zeros((B, Hkv, N, 128), np.float16); Vt = np.zeros_like(Kt)
+    Kt[:, :, :T] = K[:, :, C * N:]; Vt[:, :, :T] = V[:, :, C * N:]
+    o = ref.decode_attn(cfg, q, arena, off, expert, C, Kt, Vt, T, 0.1)
+    for u in range(B * Hkv):
+        Kh = np.zeros((S, 128)); Vh = np.zeros((S, 128))
+        for c in range(C):
+            bits = (2, 4, 8, 16)[expert[u, c]]
+            nb = ref.chunk_block_bytes(cfg, bits)
+            kk, vv = ref.decode_chunk(cfg, bits, arena[int(off[u, c]):int(off[u, c]) + nb])
+            Kh[c * N:(c + 1) * N] = kk; Vh[c * N:(c + 1) * N] = vv
+        Kh[C * N:] = Kt[0, u, :T]; Vh[C * N:] = Vt[0, u, :T]
+        sc = 0.1 * (Kh @ q[0, u].astype(np.float64)); p = np.exp(sc - sc.max()); p /= p.sum()
+        assert np.allclose(o[0, u], p @ Vh, rtol=1e-10, atol=1e-12)
