@@ -62,7 +62,7 @@
 extern "C" {
 #endif
 
-#define MOQAE_ABI_VERSION 1u
+#define MOQAE_ABI_VERSION 2u
 #define MOQAE_MAX_EXPERTS 8
 
 enum {
@@ -87,6 +87,12 @@ typedef struct {
     int32_t expert_bits[MOQAE_MAX_EXPERTS]; /* B_j in {2,4,8,16}; index order = tie-break order */
     int32_t freeze_chunks;  /* routing freezing (Sec. 3.4): chunks c < freeze_chunks are never
                                routed and take the first 16-bit expert; the paper uses 1       */
+    int32_t k_per_channel;  /* 0: the keys' quantisation groups are G consecutive dims of a token
+                               (as the values'); 1: G consecutive tokens of one dim (the outlier
+                               channels of key caches, Sec. 2.2): needs N % G == 0; the K meta
+                               area is then indexed [token group][dim], the codes keep their
+                               places; decode attention: one query head per KV head and the
+                               uniform calls only                                              */
 } moqae_cfg;
 
 /*

@@ -31,6 +31,8 @@ bool cfg_ok(const moqae_cfg *c) {
     if (c->n_experts < 1 || c->n_experts > MOQAE_MAX_EXPERTS) return false;
     for (int j = 0; j < c->n_experts; j++) if (!bits_ok(c->expert_bits[j])) return false;
     if (c->freeze_chunks < 0) return false;
+    if (c->k_per_channel != 0 && c->k_per_channel != 1) return false;
+    if (c->k_per_channel && c->chunk % c->group) return false;            // token groups must tile the chunk
     return true;
 }
 
@@ -42,6 +44,8 @@ bool layout_ok(const moqae_cfg *c) {
     const int rep = c->n_q_heads / c->n_kv_heads;
     return rep == 1 || rep * (kD / c->group) <= 16;
 }
+// Decode calls: keys quantised per channel are read by the single-head kernel only.
+bool decode_ok(const moqae_cfg *c) { return layout_ok(c) && (!c->k_per_channel || c->n_q_heads == c->n_kv_heads); }
 
 int first_16bit(const moqae_cfg *c) {
     for (int j = 0; j < c->n_experts; j++) if (c->expert_bits[j] == 16) return j;
@@ -138,6 +142,7 @@ void fill_pool_geometry(const moqae_cfg *c, const moqae_pool_cfg *pc, PagedArgs 
         base += (uint64_t)a.n_pages[j] * a.page_bytes[j]; ring += on ? a.ring_cap[j] * kPoolShards : 0u;
     }
     a.M = c->n_experts; a.N = c->chunk; a.G = c->group; a.Hkv = c->n_kv_heads; a.BH = c->batch * c->n_kv_heads;
+    a.kpc = c->k_per_channel;
 }
 
 thread_local hipEvent_t g_time_begin = nullptr, g_time_end = nullptr;   // measurement aid, see moqae_bench.h
@@ -233,7 +238,7 @@ int moqae_quantize_pack(const moqae_cfg *cfg,
     a.chunk_off = chunk_off; a.off_stride = off_stride; a.status = status;
     a.chunk_begin = chunk_begin; a.n_chunks = chunk_end - chunk_begin;
     a.BH = cfg->batch * cfg->n_kv_heads; a.N = cfg->chunk; a.G = cfg->group; a.Hkv = cfg->n_kv_heads;
-    a.M = cfg->n_experts;
+    a.M = cfg->n_experts; a.kpc = cfg->k_per_channel;
     for (int j = 0; j < 8; j++) a.bits_of[j] = j < cfg->n_experts ? cfg->expert_bits[j] : 16;
     hipError_t e = launch_pack(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
@@ -248,7 +253,7 @@ static int decode_uniform(const moqae_cfg *cfg,
                           float *out,
                           void *workspace, uint64_t workspace_bytes,
                           void *stream, int planned) {
-    if (!cfg_ok(cfg) || !layout_ok(cfg) || !q || !out || !workspace) return MOQAE_E_INVAL;
+    if (!cfg_ok(cfg) || !decode_ok(cfg) || !q || !out || !workspace) return MOQAE_E_INVAL;
     if (n_chunks < 0 || n_tail < 0 || n_tail >= cfg->chunk || n_chunks + n_tail <= 0) return MOQAE_E_INVAL;
     if (n_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride < n_chunks)) return MOQAE_E_INVAL;
     if (n_tail > 0 && (!K_tail || !V_tail)) return MOQAE_E_INVAL;
@@ -261,7 +266,7 @@ static int decode_uniform(const moqae_cfg *cfg,
     a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
-    a.seq_chunks = nullptr; a.seq_tail = nullptr; a.planned = planned;
+    a.seq_chunks = nullptr; a.seq_tail = nullptr; a.planned = planned; a.kpc = cfg->k_per_channel;
     a.counters = static_cast<unsigned int *>(workspace);
     a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, n_chunks)); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;
@@ -448,7 +453,7 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
                              float *out,
                              void *workspace, uint64_t workspace_bytes,
                              void *stream) {
-    if (!cfg_ok(cfg) || !layout_ok(cfg) || !q || !out || !workspace || !n_chunks_seq || !n_tail_seq) return MOQAE_E_INVAL;
+    if (!cfg_ok(cfg) || !layout_ok(cfg) || cfg->k_per_channel || !q || !out || !workspace || !n_chunks_seq || !n_tail_seq) return MOQAE_E_INVAL;
     if (max_chunks < 0) return MOQAE_E_INVAL;
     if (max_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride < max_chunks)) return MOQAE_E_INVAL;
     if (!K_tail || !V_tail) return MOQAE_E_INVAL;
@@ -462,7 +467,7 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
     a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
-    a.seq_chunks = n_chunks_seq; a.seq_tail = n_tail_seq; a.planned = 0;
+    a.seq_chunks = n_chunks_seq; a.seq_tail = n_tail_seq; a.planned = 0; a.kpc = 0;
     a.counters = static_cast<unsigned int *>(workspace);
     a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, max_chunks)); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;

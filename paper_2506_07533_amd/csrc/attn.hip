@@ -65,6 +65,7 @@ template <int G, int REP, int NWV> struct alignas(16) AttnLds {
     uint32_t wpos[REP == 1 ? 3 : 1][8][64];
     alignas(16) float vf[REP < 4 ? NWV : 1][512];                  // raw fp16 units: the value sums of the four row groups on their way to the lanes that own the dims
     uint4 kx[REP == 1 ? NWV : 1][4 * 72];                // per wavefront: the K codes of a unit on their way to the lanes that use them
+    alignas(16) float pcq[REP == 1 ? NWV : 1][4][kD];    // keys quantised per channel: q * scale of up to four token groups of a unit
     int iq[kD];
     int iqs16[8];
     float iqpart[3][8][2];
@@ -150,7 +151,7 @@ struct Unit {
 };
 
 template <int G> struct KRegs {
-    static constexpr int GSMAX = (G == 32) ? 2 : 1;      // a 2-bit slot of 64 codes spans two groups of 32
+    static constexpr int GSMAX = 2;                      // a 2-bit slot of 64 codes spans two groups of 32; per-channel keys: two dims
     uint4 c[4];
     uint32_t m[4][GSMAX];
 };
@@ -629,7 +630,9 @@ __device__ __forceinline__ uint32_t word_of(const uint4 &c, int i) {
 //   4 bits: token 16j + c, quarter row xq (32 dims);
 //   8 bits: token 16*(j/2) + c, eighth of a row 4*(j%2) + xq (16 dims);
 // raw fp16 units keep the slot order and have no meta.
-template <int G>
+// KPC (keys quantised per channel): the meta words are [token group][dim]; lane l takes the words of dims 2l, 2l+1 of
+// the (up to four) token groups the unit's tokens lie in.
+template <int G, bool KPC>
 __device__ __forceinline__ void load_k_iq(const Unit &u, int lane, KRegs<G> &k) {
     constexpr int NG = kD / G;
     const uint32_t xq = (uint32_t)lane >> 4, c = (uint32_t)lane & 15u;
@@ -640,6 +643,18 @@ __device__ __forceinline__ void load_k_iq(const Unit &u, int lane, KRegs<G> &k) 
     } else {                                              // short unit: the last KiB is read again (ignored)
 #pragma unroll
         for (int j = 0; j < 4; j++) k.c[j] = ld16(u.kb, vk + (uint32_t)min(j, u.nsub - 1) * 1024u);
+    }
+    if constexpr (KPC) {
+        if (u.lgb < 4) {
+            const int t0 = (int)(u.kc >> (4 + u.lgb)), TU = u.nsub << (6 - u.lgb);
+            const int ngu = (t0 % G + TU + G - 1) / G;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const uint2 mm = ld8(u.kb, u.km + (uint32_t)min(j, ngu - 1) * (kD * 4u) + (uint32_t)lane * 8u);
+                k.m[j][0] = mm.x; k.m[j][1] = mm.y;
+            }
+        }
+        return;
     }
     if (u.lgb == 1) {
         const uint32_t tok = 16u * (xq >> 1) + c, part = xq & 1u;
@@ -776,6 +791,71 @@ __device__ __forceinline__ void iq_scores(const Unit &u, const KRegs<G> &k, int 
         }
         rescale<G, 1>(st, 0, wave_max(lmax), lane);
         if (xq == 0) { L.sc[wave][0][c] = s2[0]; L.sc[wave][0][16 + c] = s2[1]; }
+    }
+    wave_sync();
+}
+
+// Scores of a quantised unit whose keys are quantised per channel (a group = G consecutive tokens of one dim):
+//   q . k^_t = sum_d (q_d * scale_{g,d}) * code_{t,d} + sum_d q_d * zero_{g,d},   g = the token group of t,
+// so the scale folds into a copy of q per token group (built here from the unit's meta words and kept in LDS)
+// and the zero-points into one number per group.  The codes stay in the slots as loaded (lane l holds slot 64j + l
+// of KiB j = part l % SPR of a token's row); the dot products run on the vector ALU, one multiply-add per code,
+// and the SPR lanes of a token are summed by DPP.  Result as iq_scores: L.sc (log2 domain), running maximum updated.
+template <int BITS, int G, int NWV>
+__device__ __forceinline__ void pc_scores(const Unit &u, const KRegs<G> &k, int lane, int wave, float scale_log2,
+                                          AttnLds<G, 1, NWV> &L, WaveState<1> &st) {
+    constexpr int E = 128 / BITS, SPR = BITS, CPW = 32 / BITS;
+    constexpr int NGU = (256 / BITS) / G > 0 ? (256 / BITS) / G : 1;     // token groups a full unit spans
+    const uint32_t qq = L.qraw[lane];
+    const float q0 = half_bits_to_float(qq & 0xffffu), q1 = half_bits_to_float(qq >> 16);
+    float bias[NGU];
+#pragma unroll
+    for (int j = 0; j < NGU; j++) {
+        const uint32_t m0 = k.m[j][0], m1 = k.m[j][1];
+        float2 qs;
+        qs.x = q0 * half_bits_to_float(m0 & 0xffffu); qs.y = q1 * half_bits_to_float(m1 & 0xffffu);
+        *reinterpret_cast<float2 *>(&L.pcq[wave][j][2 * lane]) = qs;
+        float bz = fmaf(q0, half_bits_to_float(m0 >> 16), q1 * half_bits_to_float(m1 >> 16));
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) bz += __shfl_xor(bz, o);
+        bias[j] = bz;
+    }
+    wave_sync();
+    const int part = lane % SPR;
+    const int goff = (int)(u.kc >> (4 + u.lgb)) % G;      // tokens of the unit's first token group that lie before the unit
+    float s4[4], lmax = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        const int tk = (64 * j + lane) / SPR;             // token of the slot, counted inside the unit
+        const int gj = NGU > 1 ? (goff + tk) / G : 0;
+        const float *qp = &L.pcq[wave][gj][E * part];
+        float dot = 0.0f;
+#pragma unroll
+        for (int wd = 0; wd < 4; wd++) {
+            const uint32_t w = word_of(k.c[j], wd);
+#pragma unroll
+            for (int e4 = 0; e4 < CPW / 4; e4++) {
+                const float4 qv = *reinterpret_cast<const float4 *>(qp + wd * CPW + 4 * e4);
+                const float qa[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int e = 4 * e4 + i;
+                    const uint32_t code = (w >> (16 * (e & 1) + BITS * (e >> 1))) & ((1u << BITS) - 1u);
+                    dot = fmaf((float)code, qa[i], dot);
+                }
+            }
+        }
+        dot = group_sum<SPR>(dot);
+        float bz = bias[0];
+#pragma unroll
+        for (int g = 1; g < NGU; g++) bz = (gj == g) ? bias[g] : bz;
+        s4[j] = (j < u.nsub) ? (dot + bz) * scale_log2 : -INFINITY;      // KiB past a short unit: ignored
+        lmax = fmaxf(lmax, s4[j]);
+    }
+    rescale<G, 1>(st, 0, wave_max(lmax), lane);
+    if (part == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) L.sc[wave][0][(64 * j + lane) / SPR] = s4[j];
     }
     wave_sync();
 }
@@ -974,9 +1054,10 @@ __host__ __device__ inline int attn_segment_chunks(int N) { return min(kDescCap,
 
 // RAGGED: the sequences of the batch have their own numbers of chunks and residual rows (a.seq_chunks,
 // a.seq_tail, device arrays indexed by sequence); a.n_chunks is then the bound that sizes the segments.
-// CH32: chunks of 32 tokens (a.N == 32), see load_v.
-template <int G, int REP, int NWV, bool RAGGED, bool CH32>
+// CH32: chunks of 32 tokens (a.N == 32), see load_v.  KPC: keys quantised per channel (REP == 1 only), see pc_scores.
+template <int G, int REP, int NWV, bool RAGGED, bool CH32, bool KPC>
 __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
+    static_assert(!KPC || REP == 1, "per-channel keys: one query head per KV head");
     __shared__ AttnLds<G, REP, NWV> L;
     constexpr int NG = kD / G;
     constexpr int NT = NWV * 64;
@@ -1222,9 +1303,9 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     } else {
                         const uint32_t cb = (uint32_t)N << (4 + lgb), mb = (uint32_t)N * NG * 4;
                         un.kc = (uint32_t)t0 << (4 + lgb);
-                        un.km = cb + (uint32_t)t0 * NG * 4;
+                        un.km = KPC ? cb + (uint32_t)(t0 / G) * (kD * 4u) : cb + (uint32_t)t0 * NG * 4;
                         un.vc = un.kc + cb + mb;
-                        un.vm = un.km + cb + mb;
+                        un.vm = 2u * cb + mb + (uint32_t)t0 * NG * 4;
                     }
                 } else {                                 // 16 rows of the FP16 residual
                     const int row0 = (int)(tk - n_chunk_units) * 16;
@@ -1244,7 +1325,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             VRegs<G> va, vb;
             bool have = next_unit(cur);
             auto load_keys = [&](const Unit &un) {
-                if constexpr (REP == 1) load_k_iq<G>(un, lane, kr); else load_k_mc<G, REP>(un, lane, kr);
+                if constexpr (REP == 1) load_k_iq<G, KPC>(un, lane, kr); else load_k_mc<G, REP>(un, lane, kr);
             };
             if (have) { load_keys(cur); load_v<G, CH32>(cur, lane, va); }
             if (seg == 0) {                              // the q tables, behind the first units' loads
@@ -1268,7 +1349,17 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     for (int mi = 0; mi < 4; mi++) ak[mi] = L.qmc[bi][mi][lane];
                 }
                 load_v<G, CH32>(pf, lane, vn);                  // a whole unit ahead
-                if constexpr (REP == 1) {
+                if constexpr (REP == 1 && KPC) {
+                    if (lgb == 1)      pc_scores<2, G, NWV>(cur, kr, lane, wave, a.scale_log2, L, st);
+                    else if (lgb == 2) pc_scores<4, G, NWV>(cur, kr, lane, wave, a.scale_log2, L, st);
+                    else if (lgb == 3) pc_scores<8, G, NWV>(cur, kr, lane, wave, a.scale_log2, L, st);
+                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
+                    load_keys(pf);                        // half a unit ahead
+                    if (lgb == 1)      iq_values<2, G, NWV>(vc, lane, wave, iq_weights<2, G, NWV>(vc, lane, wave, L, st), L, st);
+                    else if (lgb == 2) iq_values<4, G, NWV>(vc, lane, wave, iq_weights<4, G, NWV>(vc, lane, wave, L, st), L, st);
+                    else if (lgb == 3) iq_values<8, G, NWV>(vc, lane, wave, iq_weights<8, G, NWV>(vc, lane, wave, L, st), L, st);
+                    else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
+                } else if constexpr (REP == 1) {
                     if (lgb == 1)      iq_scores<2, G, NWV>(cur, kr, lane, wave, L, st);
                     else if (lgb == 2) iq_scores<4, G, NWV>(cur, kr, lane, wave, L, st);
                     else if (lgb == 3) iq_scores<8, G, NWV>(cur, kr, lane, wave, L, st);
@@ -1454,12 +1545,26 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
     }
     if (ev_begin && hipEventRecord(ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
     const dim3 grid((unsigned)a.n_wg), block(NWV * 64);
+    if constexpr (REP == 1) {
+        if (a.kpc) {                                      // uniform calls only (checked by the caller)
+            if (a.N == 32) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true, true>), grid, block, 0, s, a);
+            else           hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, false, true>), grid, block, 0, s, a);
+            hipError_t ek = hipGetLastError();
+            if (ek != hipSuccess) return ek;
+            if (ev_end && hipEventRecord(ev_end, s) != hipSuccess) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)(a.BH * a.rep)), dim3(kD * kMergeGroups), 0, s,
+                               (const float *)a.part, a.out, a.rep,
+                               (const uint32_t *)(a.counters + (size_t)a.BH * n_seg * kCounterStride + a.BH), a.max_partials,
+                               a.planned ? a.counters : (unsigned int *)nullptr, n_seg);
+            return hipGetLastError();
+        }
+    }
     if (a.N == 32) {
-        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, true>), grid, block, 0, s, a);
-        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true>), grid, block, 0, s, a);
+        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, true, false>), grid, block, 0, s, a);
+        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true, false>), grid, block, 0, s, a);
     } else {
-        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, false>), grid, block, 0, s, a);
-        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, false>), grid, block, 0, s, a);
+        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, false, false>), grid, block, 0, s, a);
+        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, false, false>), grid, block, 0, s, a);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -21,7 +21,7 @@
 
 namespace moqae {
 
-template <int M, int G>
+template <int M, int G, bool KPC>
 __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
     extern __shared__ uint8_t vcodes[];               // V staging rows of pack_side
     __shared__ float w3f[72];
@@ -99,8 +99,8 @@ __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
     // ---- (3) quantise and pack K, then V, into the page
     const int bits = a.bits_of[expert_s];
     uint8_t *blk = a.arena + page_off;
-    pack_side<G>(a.K + base, a.stride_s, N, bits, 0, blk, vcodes, tid, NT);
-    pack_side<G>(a.V + base, a.stride_s, N, bits, 1, blk, vcodes, tid, NT);
+    pack_side<G, KPC>(a.K + base, a.stride_s, N, bits, 0, blk, vcodes, tid, NT);
+    pack_side<G, KPC>(a.V + base, a.stride_s, N, bits, 1, blk, vcodes, tid, NT);
 }
 
 // Before every call: the status word is latched for the call's workgroups, and heads that ran past their tails on
@@ -161,8 +161,13 @@ template <int M>
 static hipError_t launch_rp(const PagedArgs &a, dim3 grid, size_t lds, hipStream_t s) {
     // as many wavefronts as the chunk has passes of 64 tokens: all of them route, then all of them pack
     const dim3 block((unsigned)(a.N <= 64 ? 64 : (a.N >= 256 ? 256 : (a.N + 63) / 64 * 64)));
-    if (a.G == 32) hipLaunchKernelGGL((route_pack_kernel<M, 32>), grid, block, lds, s, a);
-    else           hipLaunchKernelGGL((route_pack_kernel<M, 64>), grid, block, lds, s, a);
+    if (a.kpc) {
+        if (a.G == 32) hipLaunchKernelGGL((route_pack_kernel<M, 32, true>), grid, block, lds, s, a);
+        else           hipLaunchKernelGGL((route_pack_kernel<M, 64, true>), grid, block, lds, s, a);
+    } else {
+        if (a.G == 32) hipLaunchKernelGGL((route_pack_kernel<M, 32, false>), grid, block, lds, s, a);
+        else           hipLaunchKernelGGL((route_pack_kernel<M, 64, false>), grid, block, lds, s, a);
+    }
     return hipGetLastError();
 }
 

@@ -20,6 +20,7 @@ struct PackArgs {
     uint8_t *arena; uint64_t capacity; uint64_t *arena_used;
     uint64_t *chunk_off; int64_t off_stride; int32_t *status;
     int chunk_begin, n_chunks, BH, N, G, Hkv, M;
+    int kpc;                    // keys quantised per channel (groups of G tokens of one dim)
     int bits_of[8];
 };
 hipError_t launch_pack(const PackArgs &a, hipStream_t s);
@@ -37,7 +38,7 @@ struct PagedArgs {
     uint8_t *expert; int64_t expert_stride; int32_t *votes;
     uint8_t *arena; uint32_t *state;
     unsigned long long *chunk_off; int64_t off_stride; int32_t *status;
-    int chunk_begin, n_chunks, BH, N, G, Hkv, M, freeze_chunks, e16;
+    int chunk_begin, n_chunks, BH, N, G, Hkv, M, freeze_chunks, e16, kpc;
     int bits_of[8];
     uint32_t n_pages[8], ring_start[8], ring_cap[8], page_bytes[8];
     unsigned long long pool_base[8];
@@ -65,6 +66,7 @@ struct AttnArgs {
     unsigned int *counters;     // ticket counters, one per (row, row segment), attn_counter_bytes() in all
     float scale_log2;           // softmax_scale * log2(e)
     int n_chunks, n_tail, n_wg, max_partials, N, G, Hkv, rep, BH;
+    int kpc;                    // keys quantised per channel
     int planned;                // the workspace holds a plan: no prep kernel, the merge kernel zeroes the counters again
     int bits_of[8];
 };

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(PackArgs a) {
     }
 }
 
-template <int G>
+template <int G, bool KPC>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     extern __shared__ uint8_t vcodes[];               // [N][kVRow] code bytes (V only); odd dword stride: rows fall on different banks
     if (*a.status != 0) return;
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     const uint16_t *src = (isV ? a.V : a.K) + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h
                         + (int64_t)c * N * a.stride_s;
 
-    pack_side<G>(src, a.stride_s, N, bits, isV, blk, vcodes, tid);
+    pack_side<G, KPC>(src, a.stride_s, N, bits, isV, blk, vcodes, tid, kPackThreads);
 }
 
 // The new end of the arena = the end of the last block in (b, h, c) order.  A kernel of its own, after
@@ -265,8 +265,13 @@ hipError_t launch_pack(const PackArgs &a, hipStream_t s) {
     if (e != hipSuccess) return e;
     dim3 grid(2u, (unsigned)a.n_chunks, (unsigned)a.BH);
     const size_t lds = (size_t)a.N * kVRow;
-    if (a.G == 32) hipLaunchKernelGGL(pack_kernel<32>, grid, dim3(kPackThreads), lds, s, a);
-    else           hipLaunchKernelGGL(pack_kernel<64>, grid, dim3(kPackThreads), lds, s, a);
+    if (a.kpc) {
+        if (a.G == 32) hipLaunchKernelGGL((pack_kernel<32, true>), grid, dim3(kPackThreads), lds, s, a);
+        else           hipLaunchKernelGGL((pack_kernel<64, true>), grid, dim3(kPackThreads), lds, s, a);
+    } else {
+        if (a.G == 32) hipLaunchKernelGGL((pack_kernel<32, false>), grid, dim3(kPackThreads), lds, s, a);
+        else           hipLaunchKernelGGL((pack_kernel<64, false>), grid, dim3(kPackThreads), lds, s, a);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(arena_end_kernel, dim3(1), dim3(1), 0, s, a);

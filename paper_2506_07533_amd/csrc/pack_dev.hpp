@@ -133,9 +133,63 @@ __device__ __forceinline__ void pack_item(const uint4 *__restrict__ p, bool isV,
     }
 }
 
+// Keys quantised per channel: a group is G consecutive tokens of one dim.  One wavefront per token group, lane l owns
+// dims 2l, 2l+1 (one 32-bit column of fp16 pairs): it reads the G rows' words (a row is one coalesced 256-byte piece per
+// wavefront), takes the packed minimum / maximum over the tokens, computes scale and reciprocal of both dims as
+// pack_item does (the same binary32 operations, so the same bits), then per token its two codes, which the n/2
+// lanes of a code word OR together (DPP) before one of them stores the word at its token-major place.
+template <int G, int BITS>
+__device__ __forceinline__ void pack_k_channel_group(const uint16_t *src, int64_t stride_s, int tg, uint32_t *codes_w,
+                                                     uint32_t *meta_w, int lane) {
+    const uint32_t *col = reinterpret_cast<const uint32_t *>(src + (int64_t)tg * G * stride_s) + lane;
+    const int64_t rw = stride_s / 2;                  // row stride in words
+    uint32_t w[G];
+#pragma unroll
+    for (int i = 0; i < G; i++) w[i] = col[i * rw];
+    uint32_t mn4[4], mx4[4];
+#pragma unroll
+    for (int k = 0; k < 4; k++) { mn4[k] = pk_min_f16(w[k], w[k + 4]); mx4[k] = pk_max_f16(w[k], w[k + 4]); }
+#pragma unroll
+    for (int k = 8; k < G; k++) { mn4[k & 3] = pk_min_f16(mn4[k & 3], w[k]); mx4[k & 3] = pk_max_f16(mx4[k & 3], w[k]); }
+    const uint32_t mnp = pk_min_f16(pk_min_f16(mn4[0], mn4[1]), pk_min_f16(mn4[2], mn4[3]));
+    const uint32_t mxp = pk_max_f16(pk_max_f16(mx4[0], mx4[1]), pk_max_f16(mx4[2], mx4[3]));
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    float nmn[2], inv[2];
+    uint32_t metaw[2];
+#pragma unroll
+    for (int e = 0; e < 2; e++) {
+        float mn = half_bits_to_float((mnp >> (16 * e)) & 0xffffu), mx = half_bits_to_float((mxp >> (16 * e)) & 0xffffu);
+        if (mn == 0.0f) mn = 0.0f;                    // -0 is stored as +0
+        if (mx == 0.0f) mx = 0.0f;
+        const float s32 = __fdiv_rn(__fsub_rn(mx, mn), qmax);
+        uint32_t s16 = float_to_half_bits(s32);
+        if (half_bits_to_float(s16) < s32) s16 += 1;  // the scale is rounded up
+        if (s16 == 0) s16 = 0x3C00u;                  // constant group: scale 1
+        inv[e] = __fdiv_rn(1.0f, half_bits_to_float(s16));
+        nmn[e] = -mn;
+        metaw[e] = s16 | (float_to_half_bits(mn) << 16);
+    }
+    nt_store(reinterpret_cast<uint2 *>(meta_w + (size_t)tg * kD + 2 * lane), uint2{metaw[0], metaw[1]});
+    constexpr int CPW = 32 / BITS, LPW = CPW / 2;     // codes per word, lanes per word
+    const int pi = lane % LPW;                        // this lane's pair inside its word
+    uint32_t *dst = codes_w + (size_t)tg * G * (kD / CPW) + lane / LPW;
+#pragma unroll
+    for (int i = 0; i < G; i++) {
+        const uint32_t c0 = __builtin_bit_cast(uint32_t, __fadd_rn(__fmul_rn(add_lo_f16(w[i], nmn[0]), inv[0]), kMagic)) - kMagicBits;
+        const uint32_t c1 = __builtin_bit_cast(uint32_t, __fadd_rn(__fmul_rn(add_hi_f16(w[i], nmn[1]), inv[1]), kMagic)) - kMagicBits;
+        uint32_t x = (c0 << (BITS * pi)) | (c1 << (16 + BITS * pi));
+        x |= dpp_u<DPP_XOR1>(x);
+        if constexpr (LPW >= 4) x |= dpp_u<DPP_XOR2>(x);
+        if constexpr (LPW >= 8) x |= dpp_u<DPP_HALF_MIRROR>(x);
+        if (pi == 0) nt_store(dst + (size_t)i * (kD / CPW), x);
+    }
+}
+
 // K (isV = 0) or V (isV = 1) of one chunk -> its block `blk` at bit-width `bits`, by one workgroup of NT threads
 // (a multiple of 64).  src: the chunk's first row (row stride stride_s elements); vcodes: N * kVRow bytes of LDS (V only).
-template <int G>
+// KPC: the keys' groups run along tokens (pack_k_channel_group); a template flag so that its G registers per lane stay out
+// of the ordinary kernels.
+template <int G, bool KPC>
 __device__ __forceinline__ void pack_side(const uint16_t *src, int64_t stride_s, int N, int bits, int isV, uint8_t *blk,
                                           uint8_t *vcodes, int tid, int NT = kPackThreads) {
     if (bits == 16) {                                 // FP16 expert: rows copied verbatim
@@ -152,6 +206,14 @@ __device__ __forceinline__ void pack_side(const uint16_t *src, int64_t stride_s,
     uint32_t *codes_w = reinterpret_cast<uint32_t *>(area);
     uint32_t *meta_w = reinterpret_cast<uint32_t *>(area + code_bytes);
 
+    if (KPC && !isV) {                               // keys quantised per channel: one wavefront per group of G tokens
+        for (int tg = tid >> 6; tg < N / G; tg += NT >> 6) {
+            if (bits == 2)      pack_k_channel_group<G, 2>(src, stride_s, tg, codes_w, meta_w, tid & 63);
+            else if (bits == 4) pack_k_channel_group<G, 4>(src, stride_s, tg, codes_w, meta_w, tid & 63);
+            else                pack_k_channel_group<G, 8>(src, stride_s, tg, codes_w, meta_w, tid & 63);
+        }
+        return;
+    }
     // item = (token row, group): consecutive lanes take consecutive 2G-byte pieces of the chunk
     for (int item = tid; item < N * NG; item += NT) {
         const int row = item / NG, g = item % NG;

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(mq):
         assert declared == sorted(exports), fname
         for name in declared:
             assert getattr(mq.lib(), name) is not None
-    assert mq.abi_version() == 1
+    assert mq.abi_version() == 2
     assert "arena" in mq.strerror(mq.E_ARENA) and mq.strerror(0) == "ok"
 
 

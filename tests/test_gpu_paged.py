@@ -43,11 +43,12 @@ def _check_pages(mq, ref, cfg, rcfg, pages, K, V, expert_h, off_h, arena_h, c0, 
     return seen
 
 
-@pytest.mark.parametrize("B,Hkv,N,G,C,freeze", [(1, 8, 64, 32, 12, 1), (2, 3, 128, 64, 9, 1), (1, 2, 256, 64, 5, 0),
-                                               (2, 2, 32, 64, 21, 2), (1, 3, 192, 32, 4, 1)])
-def test_route_pack_paged(mq, ref, B, Hkv, N, G, C, freeze):
+@pytest.mark.parametrize("B,Hkv,N,G,C,freeze,kpc", [(1, 8, 64, 32, 12, 1, 0), (2, 3, 128, 64, 9, 1, 0), (1, 2, 256, 64, 5, 0, 0),
+                                                   (2, 2, 32, 64, 21, 2, 0), (1, 3, 192, 32, 4, 1, 0),
+                                                   (1, 3, 128, 64, 7, 1, 1)])       # keys quantised per channel
+def test_route_pack_paged(mq, ref, B, Hkv, N, G, C, freeze, kpc):
     rng = np.random.default_rng(B * 100 + N + C)
-    cfg, rcfg = T._cfgs(mq, ref, B, Hkv, Hkv, N, G, BITS, freeze)
+    cfg, rcfg = T._cfgs(mq, ref, B, Hkv, Hkv, N, G, BITS, freeze, kpc)
     BH = B * Hkv
     K, V = T._rand_kv(rng, B, Hkv, C * N)
     W = [(rng.standard_normal(s) * 0.3).astype(np.float16) for s in ((128, 4), (128, 4), (4, 4))]

@@ -31,8 +31,8 @@ def mq():
     return binding
 
 
-def _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, freeze):
-    return (mq.Cfg(B, Hq, Hkv, 128, N, G, bits, freeze), ref.RefCfg(B, Hq, Hkv, 128, N, G, bits, freeze))
+def _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, freeze, kpc=0):
+    return (mq.Cfg(B, Hq, Hkv, 128, N, G, bits, freeze, kpc), ref.RefCfg(B, Hq, Hkv, 128, N, G, bits, freeze, kpc))
 
 
 def _dev(a):
@@ -250,9 +250,9 @@ def test_pack_status_with_many_rows(mq, ref, BH):
 # decode attention
 # ----------------------------------------------------------------------------------------------
 
-def _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, bits, seed, scale=None, expert=None, freeze=1):
+def _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, bits, seed, scale=None, expert=None, freeze=1, kpc=0):
     rng = np.random.default_rng(seed)
-    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, freeze)
+    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, freeze, kpc)
     S = C * N + T
     K, V = _rand_kv(rng, B, Hkv, max(S, 1))
     q = rng.standard_normal((B, Hq, 128), dtype=np.float32).astype(np.float16)
@@ -329,6 +329,33 @@ def test_attention_rows_of_unequal_cost(mq, ref, heavy, B, Hkv, rep, N, C, T):
     expert[:, 1::7] = 1                                           # and a few 4-bit chunks in every row
     err = _attn_case(mq, ref, B, Hkv * rep, Hkv, N, 64, C, T, bits, seed=BH + C, expert=expert, freeze=0)
     assert err <= ATTN_TOL, err
+
+
+@pytest.mark.parametrize("B,H,N,G,C,T,bits", [
+    (1, 4, 128, 64, 21, 17, (2, 4, 8, 16)),
+    (2, 2, 64, 64, 30, 0, (2, 4, 8, 16)),          # short 2-bit units
+    (1, 2, 64, 32, 17, 5, (2, 4, 8, 16)),          # four token groups per 2-bit unit ... two per chunk
+    (1, 2, 256, 64, 6, 200, (2, 4, 8, 16)),
+    (1, 2, 32, 32, 40, 9, (2, 4, 8, 16)),          # chunks of 32 tokens
+    (1, 1, 128, 32, 5, 0, (2,)), (1, 1, 128, 64, 5, 0, (4,)), (1, 1, 192, 64, 5, 3, (8,)),
+])
+def test_per_channel_keys(mq, ref, B, H, N, G, C, T, bits):
+    """Keys quantised per channel (groups of G tokens of one dim): packed bytes bit-exact (checked inside _attn_case),
+    attention within the tolerance, one query head per KV head."""
+    err = _attn_case(mq, ref, B, H, H, N, G, C, T, bits, seed=N + C, freeze=0, kpc=1)
+    assert err <= ATTN_TOL, err
+
+
+def test_per_channel_keys_limits(mq):
+    cfg = mq.Cfg(1, 8, 2, 128, 128, 64, (2, 4, 8, 16), 1, 1)             # grouped queries: pack yes, decode no
+    assert mq.chunk_block_bytes(cfg, 2) == 10240 and mq.decode_workspace_bytes(mq.Cfg(1, 2, 2, 128, 128, 64, (2, 16), 1, 1), 4) > 0
+    q = torch.zeros((1, 8, 128), dtype=torch.float16, device="cuda"); out = torch.zeros((1, 8, 128), dtype=torch.float32, device="cuda")
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    Kt = torch.zeros((1, 2, 128, 128), dtype=torch.float16, device="cuda")
+    with pytest.raises(mq.MoqaeError) as e:
+        mq.decode_attn(cfg, q, None, None, None, 0, Kt, Kt, 5, 0.1, out, ws)
+    assert e.value.code == mq.E_INVAL
+    assert mq.chunk_block_bytes(mq.Cfg(1, 2, 2, 128, 32, 64, (2, 16), 1, 1), 2) == 0     # token groups must tile the chunk
 
 
 def test_attention_degenerate_cases(mq, ref):
