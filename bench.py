@@ -98,6 +98,11 @@ def main() -> int:
     ap.add_argument("--ragged", action="store_true",
                     help="decode attention over a batch of 16 sequences of 2k ... 32k tokens (one layer of the stack "
                          "workload's shape) through moqae_decode_attn_ragged, beside the uniform call at full length")
+    ap.add_argument("--per-channel", action="store_true",
+                    help="quantise the keys per channel (cfg.k_per_channel = 1: groups of G tokens of one dim) instead of per token")
+    ap.add_argument("--kquant-error", action="store_true",
+                    help="attention error against unquantised fp64 attention of caches quantised uniformly at 2, 4 and 8 bits, keys per "
+                         "token vs per channel, on the first 16k tokens of four heads of the chosen workload's synthetic K, V")
     ap.add_argument("--copy-probe", action="store_true",
                     help="counter calibration: run a plain elementwise kernel that reads 1 GiB and writes 1 GiB, "
                          "five times, and exit (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE are scaled by what they read for it)")
@@ -158,6 +163,9 @@ def main() -> int:
     if args.ragged:
         print(json.dumps(bench_ragged(args)), flush=True)
         return 0
+    if args.kquant_error:
+        print(json.dumps(kquant_error(args, w)), flush=True)
+        return 0
     res = bench_stack(args, w) if w.n_layers > 1 else bench_layer(args, w)
     print(json.dumps(res), flush=True)
     return 0
@@ -170,7 +178,8 @@ def bench_layer(args, w):
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     BH, C, T, M = w.batch * w.n_kv_heads, w.n_chunks, w.n_tail, len(w.expert_bits)
-    cfg = mq.Cfg(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.chunk, w.group, w.expert_bits, w.freeze_chunks)
+    cfg = mq.Cfg(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.chunk, w.group, w.expert_bits, w.freeze_chunks,
+                 1 if args.per_channel else 0)
 
     t0 = time.time()
     d = synth.make_workload(w)
@@ -277,7 +286,7 @@ def bench_layer(args, w):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": DTYPE[1 if w.n_q_heads == w.n_kv_heads else 0], "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "cached_tokens": w.seq, "chunk": w.chunk, "group": w.group,
-                   "expert_bits": list(w.expert_bits), "realised_mix": mix, "chunks": n_units,
+                   "expert_bits": list(w.expert_bits), "k_per_channel": int(args.per_channel), "realised_mix": mix, "chunks": n_units,
                    "packed_bytes": packed_bytes, "fp16_equiv_bytes": 2 * kv_bytes},
         # the dominant kernel, timed alone by a pair of HIP events the library records around it
         "roofline": dict(roof(attn_bytes, t_split), kernel="attn_split_kernel"),
@@ -349,6 +358,47 @@ def bench_layer(args, w):
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, scale)
     return res
+
+
+def kquant_error(args, w):
+    """How much the quantiser of the keys costs in attention accuracy on keys with outlier channels (the structure Sec. 2.2
+    quotes): uniform 2 / 4 / 8-bit caches, keys per token vs per channel, against fp64 attention over the raw fp16 K, V."""
+    import torch
+    from paper_2506_07533_amd import binding as mq, synth
+    dev = torch.device("cuda:0")
+    H, S = 4, 16384
+    ws_ = dataclasses.replace(w, batch=1, n_q_heads=H, n_kv_heads=H, seq=S, name=w.name + "/4heads16k")
+    d = synth.make_workload(ws_)
+    K, V, q = d["K"], d["V"], d["q"]
+    scale = 1.0 / float(np.sqrt(w.head_dim))
+    Kf, Vf, qf = K.astype(np.float64), V.astype(np.float64), q.astype(np.float64)
+    sc = scale * np.einsum("bhsd,bhd->bhs", Kf, qf); sc -= sc.max(-1, keepdims=True)
+    p = np.exp(sc); p /= p.sum(-1, keepdims=True)
+    o_ref = np.einsum("bhs,bhsd->bhd", p, Vf)
+    C = S // w.chunk
+    Kd, Vd, qd = (torch.from_numpy(x).to(dev) for x in (K, V, q))
+    rows = []
+    for bits in (2, 4, 8):
+        row = {"bits": bits}
+        for kpc in (0, 1):
+            cfg = mq.Cfg(1, H, H, w.head_dim, w.chunk, w.group, (bits, 16), 0, kpc)
+            expert = torch.zeros((H, C), dtype=torch.uint8, device=dev)
+            arena = torch.zeros(mq.arena_upper_bound(cfg, H * C), dtype=torch.uint8, device=dev)
+            used = torch.zeros(1, dtype=torch.int64, device=dev); status = torch.zeros(1, dtype=torch.int32, device=dev)
+            off = torch.zeros((H, C), dtype=torch.int64, device=dev)
+            mq.quantize_pack(cfg, Kd, Vd, 0, C, expert, arena, used, off, status)
+            out = torch.zeros((1, H, w.head_dim), dtype=torch.float32, device=dev)
+            wsb = torch.zeros(mq.decode_workspace_bytes(cfg, C), dtype=torch.uint8, device=dev)
+            mq.decode_attn(cfg, qd, arena, off, expert, C, None, None, 0, scale, out, wsb)
+            torch.cuda.synchronize()
+            assert int(status.item()) == 0
+            o = out.cpu().numpy().astype(np.float64)
+            err = np.abs(o - o_ref).max(-1) / np.abs(o_ref).max(-1)
+            row["per_channel" if kpc else "per_token"] = round(float(err.max()), 5)
+        rows.append(row)
+        log(f"[kquant] {row}")
+    return {"kquant_error": "max-norm relative error of the attention output against fp64 attention over the raw fp16 cache",
+            "workload": ws_.name, "chunk": w.chunk, "group": w.group, "data": "synthetic (four outlier channels per head, x10)", "rows": rows}
 
 
 def stream_ceiling(mq, dev):
