@@ -4,7 +4,9 @@
 // The ordered arena of moqae_quantize_pack puts a chunk's block where the blocks of all earlier chunks end,
 // so packing has to wait for every routing decision.  With one pool of equal pages per expert a chunk's place
 // is one atomic step on its pool's free ring, and the workgroup that has just routed the chunk quantises it at
-// once: K comes from HBM once (the second pass over the 16-64 KiB tile hits the L2 it was just read into).
+// once: the router's lanes leave the key rows they read in LDS and the quantiser takes them from there, so K comes
+// from memory once (a second pass over the tile through the caches was counted again by the L2's fetch counter:
+// with about 5 MB of tiles in flight per 4 MB L2 it does not stay there).
 //
 //   route_pack_kernel  one workgroup per (sequence, KV head, chunk): its first N/64 wavefronts route 64 tokens
 //                      each (route_tokens, the code of route_kernel), the votes are added up in LDS, one
@@ -23,7 +25,8 @@ namespace moqae {
 
 template <int M, int G, bool KPC>
 __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
-    extern __shared__ uint8_t vcodes[];               // V staging rows of pack_side
+    extern __shared__ uint4 dyn_lds[];                // the chunk's key rows as the router read them (N * kStageRow pieces), then
+    uint8_t *vcodes = reinterpret_cast<uint8_t *>(dyn_lds);   // the V staging rows of pack_side (N * kVRow bytes) in the same place
     __shared__ float w3f[72];
     __shared__ int votes_s[8];
     __shared__ unsigned long long page_off;
@@ -49,9 +52,9 @@ __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
     if (status_in != 0) return;                       // sticky error: the call is a no-op
     if (routed && wave * 64 < N) {
         int cnt[M];
-        route_tokens<M>(a.K + base + (int64_t)wave * 64 * a.stride_s, min(64, N - wave * 64), a.stride_s,
-                        reinterpret_cast<const uint32_t *>(a.W1), reinterpret_cast<const uint32_t *>(a.W2), w3f,
-                        a.bias != nullptr, lane, cnt);
+        route_tokens<M, true>(a.K + base + (int64_t)wave * 64 * a.stride_s, min(64, N - wave * 64), a.stride_s,
+                              reinterpret_cast<const uint32_t *>(a.W1), reinterpret_cast<const uint32_t *>(a.W2), w3f,
+                              a.bias != nullptr, lane, cnt, dyn_lds + wave * 64 * kStageRow);
 #pragma unroll
         for (int k = 0; k < M; k++) if (lane == k) atomicAdd(&votes_s[k], cnt[k]);
     }
@@ -99,7 +102,12 @@ __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
     // ---- (3) quantise and pack K, then V, into the page
     const int bits = a.bits_of[expert_s];
     uint8_t *blk = a.arena + page_off;
-    pack_side<G, KPC>(a.K + base, a.stride_s, N, bits, 0, blk, vcodes, tid, NT);
+    if (routed) {                                     // the keys are in LDS: K comes from memory once
+        pack_side<G, KPC>(reinterpret_cast<const uint16_t *>(dyn_lds), kStageRow * 8, N, bits, 0, blk, vcodes, tid, NT);
+        __syncthreads();                              // the key rows are consumed: the V staging rows take their place
+    } else {
+        pack_side<G, KPC>(a.K + base, a.stride_s, N, bits, 0, blk, vcodes, tid, NT);
+    }
     pack_side<G, KPC>(a.V + base, a.stride_s, N, bits, 1, blk, vcodes, tid, NT);
 }
 
@@ -161,6 +169,19 @@ template <int M>
 static hipError_t launch_rp(const PagedArgs &a, dim3 grid, size_t lds, hipStream_t s) {
     // as many wavefronts as the chunk has passes of 64 tokens: all of them route, then all of them pack
     const dim3 block((unsigned)(a.N <= 64 ? 64 : (a.N >= 256 ? 256 : (a.N + 63) / 64 * 64)));
+    if (lds > 65536) {                                // 256-token chunks: 68 KiB of key rows; above the default limit of dynamic LDS
+        static bool raised[2][2] = {{false, false}, {false, false}};
+        bool &r = raised[a.G == 32][a.kpc != 0];
+        if (!r) {
+            hipError_t e = hipSuccess;
+            if (a.kpc) e = a.G == 32 ? hipFuncSetAttribute((const void *)route_pack_kernel<M, 32, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                                     : hipFuncSetAttribute((const void *)route_pack_kernel<M, 64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            else       e = a.G == 32 ? hipFuncSetAttribute((const void *)route_pack_kernel<M, 32, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                                     : hipFuncSetAttribute((const void *)route_pack_kernel<M, 64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            r = true;
+        }
+    }
     if (a.kpc) {
         if (a.G == 32) hipLaunchKernelGGL((route_pack_kernel<M, 32, true>), grid, block, lds, s, a);
         else           hipLaunchKernelGGL((route_pack_kernel<M, 64, true>), grid, block, lds, s, a);
@@ -177,7 +198,7 @@ hipError_t launch_route_pack_paged(const PagedArgs &a, hipStream_t s) {
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
     dim3 grid((unsigned)a.n_chunks, (unsigned)a.BH);
-    const size_t lds = (size_t)a.N * kVRow;
+    const size_t lds = (size_t)a.N * (kStageRow * 16 > kVRow ? kStageRow * 16 : kVRow);
     switch (a.M) {
         case 1: return launch_rp<1>(a, grid, lds, s);
         case 2: return launch_rp<2>(a, grid, lds, s);

@@ -28,10 +28,13 @@ __device__ __forceinline__ float exp_pinned(float x) {
 // One wavefront routes the n_tok tokens whose key rows start at Kc (row stride stride_s elements), one lane per
 // token and pass of 64 tokens; W1w, W2w: the fp16 weight matrices as 32-bit words (wave-uniform loads), w3f: W3 as
 // binary32 (M*M values) and the optional bias at [64..64+M), in LDS.  Returns the votes per expert, the same in
-// every lane.
-template <int M>
+// every lane.  STAGE: every lane also leaves its rows in `stage` (LDS, kStageRow 16-byte pieces per row, row = token
+// counted from Kc), so that a quantiser that follows reads the keys from there and not from memory again.
+constexpr int kStageRow = 17;                     // 16 pieces of data + 1 of padding: the lanes' writes fall on different banks
+template <int M, bool STAGE = false>
 __device__ __forceinline__ void route_tokens(const uint16_t *Kc, int n_tok, int64_t stride_s, const uint32_t *W1w,
-                                             const uint32_t *W2w, const float *w3f, bool has_bias, int lane, int (&cnt)[M]) {
+                                             const uint32_t *W2w, const float *w3f, bool has_bias, int lane, int (&cnt)[M],
+                                             uint4 *stage = nullptr) {
 #pragma unroll
     for (int k = 0; k < M; k++) cnt[k] = 0;
 
@@ -56,6 +59,12 @@ __device__ __forceinline__ void route_tokens(const uint16_t *Kc, int n_tok, int6
         uint4 xr[8];
 #pragma unroll
         for (int p = 0; p < 8; p++) xr[p] = xn[p];
+        if constexpr (STAGE) {
+            if (active) {
+#pragma unroll
+                for (int p = 0; p < 8; p++) stage[(row0 + lane) * kStageRow + (hr & 1) * 8 + p] = xr[p];
+            }
+        }
         if (hr + 1 < n_half) {
             const uint4 *hp = half_ptr(hr + 1);
 #pragma unroll
