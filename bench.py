@@ -334,6 +334,23 @@ def bench_layer(args, w):
         res["route_pack_paged_chunks_per_s"] = round(n_units / (t_f.mean() * 1e-3), 1)
         del p_arena
 
+    if not args.decode_only and not args.per_channel and w.n_q_heads // w.n_kv_heads <= 2:
+        # four new tokens per sequence in one call (moqae_decode_attn_multi): the same bytes serve four queries
+        Qn = 4
+        qm = torch.randn((w.batch, Qn, w.n_q_heads, w.head_dim), dtype=torch.float16, device=dev)
+        om = torch.zeros((w.batch, Qn, w.n_q_heads, w.head_dim), dtype=torch.float32, device=dev)
+        wsm = torch.zeros(mq.decode_workspace_bytes_multi(cfg, C, Qn), dtype=torch.uint8, device=dev)
+        Ktm = torch.randn((w.batch, w.n_kv_heads, w.chunk, w.head_dim), dtype=torch.float16, device=dev); Vtm = torch.randn_like(Ktm)
+        mev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for i in range(23):
+            a = i & 1
+            if i >= 3: mev[i - 3][0].record()
+            mq.decode_attn_multi(cfg, qm, arenas[a], offs[a], expert, C, Ktm, Vtm, Qn, scale, om, wsm)
+            if i >= 3: mev[i - 3][1].record()
+        torch.cuda.synchronize()
+        t_m = np.array([a.elapsed_time(b) for a, b in mev])
+        res["decode_call_4_queries"] = dict(roof(attn_bytes, t_m), entry_point="moqae_decode_attn_multi", queries=Qn, samples=20)
+
     if not args.decode_only:
         # router fine-tuning (Sec. 3.3): loss and gradient over every cached key row of the layer, synthetic L_nll
         nll = torch.full((w.batch,), 2.0, dtype=torch.float32, device=dev)

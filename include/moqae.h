@@ -229,6 +229,25 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
 uint64_t moqae_decode_workspace_bytes_ragged(const moqae_cfg *cfg, int32_t max_chunks);   /* host; 0 if cfg invalid */
 
 /*
+ * Several new tokens per sequence in one call (speculative decoding, chunked prefill) over the same packed cache:
+ * q, out: [B, n_queries, Hq, D].  The new tokens' own K, V rows must already be the LAST n_queries valid rows of the
+ * FP16 residual (n_tail >= n_queries); query t (0-based) attends to every packed chunk and to the first
+ * n_tail - (n_queries - 1 - t) residual rows, i.e. causally among the new tokens.  n_queries * Hq / Hkv must be 1, 2,
+ * 4 or 8 (and, above 1, times D/G at most 16): the queries of a KV head share every byte read, as grouped query heads
+ * do.  Everything else as moqae_decode_attn; workspace: moqae_decode_workspace_bytes_multi(cfg, n_chunks, n_queries).
+ */
+int moqae_decode_attn_multi(const moqae_cfg *cfg,
+                            const void *q, int32_t n_queries,
+                            const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                            int64_t desc_stride, int32_t n_chunks,
+                            const void *K_tail, const void *V_tail, int32_t n_tail,
+                            float softmax_scale,
+                            float *out,
+                            void *workspace, uint64_t workspace_bytes,
+                            void *stream);
+uint64_t moqae_decode_workspace_bytes_multi(const moqae_cfg *cfg, int32_t n_chunks, int32_t n_queries);  /* host; 0 if invalid */
+
+/*
  * Router fine-tuning, Sec. 3.3: the loss of Eq. (3)-(5) and its gradient with respect to the router weights, over
  * the cached key rows [token_begin, token_end) of every (b, h) (T rows in all), with the language model frozen:
  *   L_model = (1/T) sum_i p^i_j * L_nll * penalty_model[j],   L_mem = (1/T) sum_i p^i_j * penalty_mem[j],

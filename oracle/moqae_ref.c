@@ -41,6 +41,8 @@
  *   decode attention   : 16-bit experts == unquantised attention (torch fp64
  *                        scaled_dot_product_attention), S = 1, uniform keys,
  *                        score-shift invariance
+ *   several queries    : an all-16-bit cache against torch fp64 attention with a causal
+ *                        mask over the new tokens
  *   router loss (3)-(5): gradient against central finite differences of the loss
  *                        in binary64, one expert (p = 1: constant loss, zero
  *                        gradient), lambda = 0 / 1 limits, linearity in L_nll
@@ -687,6 +689,40 @@ int moqae_decode_attn_ref(const moqae_ref_cfg *cfg,
         free(Kh); free(Vh); free(sc);
     }
     return bad ? REF_E_INVAL : REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Several new tokens per sequence at once (speculative decoding,       */
+/* chunked prefill): n_queries queries per head; their own K, V rows    */
+/* are the LAST n_queries valid rows of the FP16 residual, and query t  */
+/* (0-based) attends to every packed chunk and to the residual rows     */
+/* before and including its own: the first n_tail - (n_queries - 1 - t) */
+/* rows.  It is n_queries calls of the single-token attention above.    */
+/* q, out: [B, n_queries, Hq, D].                                       */
+/* ------------------------------------------------------------------ */
+int moqae_decode_attn_multi_ref(const moqae_ref_cfg *cfg,
+                                const uint16_t *q, int32_t n_queries,
+                                const uint8_t *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                                int64_t desc_stride_bh, int32_t n_chunks,
+                                const uint16_t *K_tail, const uint16_t *V_tail, int32_t n_tail,
+                                double softmax_scale,
+                                double *out)
+{
+    if (!cfg_ok(cfg) || !q || !out || n_queries < 1 || n_tail < n_queries) return REF_E_INVAL;
+    const int D = cfg->head_dim, Hq = cfg->n_q_heads, B = cfg->batch;
+    uint16_t *q1 = malloc(sizeof(uint16_t) * (size_t)B * Hq * D);
+    double *o1 = malloc(sizeof(double) * (size_t)B * Hq * D);
+    int rc = REF_OK;
+    for (int t = 0; t < n_queries && rc == REF_OK; t++) {
+        for (int b = 0; b < B; b++)
+            memcpy(q1 + (size_t)b * Hq * D, q + ((size_t)b * n_queries + t) * Hq * D, sizeof(uint16_t) * (size_t)Hq * D);
+        rc = moqae_decode_attn_ref(cfg, q1, arena, chunk_off, expert, desc_stride_bh, n_chunks, K_tail, V_tail,
+                                   n_tail - (n_queries - 1 - t), softmax_scale, o1);
+        for (int b = 0; b < B; b++)
+            memcpy(out + ((size_t)b * n_queries + t) * Hq * D, o1 + (size_t)b * Hq * D, sizeof(double) * (size_t)Hq * D);
+    }
+    free(q1); free(o1);
+    return rc;
 }
 
 /* ------------------------------------------------------------------ */

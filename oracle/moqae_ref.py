@@ -283,6 +283,23 @@ def pool_release(cfg: RefCfg, n_pages: Sequence[int], expert: np.ndarray, chunk_
         raise ValueError(f"moqae_pool_release_ref -> {rc}")
 
 
+def decode_attn_multi(cfg: RefCfg, q: np.ndarray, arena, chunk_off, expert, n_chunks: int, K_tail: np.ndarray, V_tail: np.ndarray,
+                      n_tail: int, softmax_scale: float) -> np.ndarray:
+    """q: [B, Q, Hq, D] fp16; the Q new tokens' rows are the last Q valid residual rows.  Returns float64 [B, Q, Hq, D]."""
+    q = np.ascontiguousarray(_h(q))
+    B, Q, Hq, D = q.shape
+    assert (B, Hq, D) == (cfg.batch, cfg.n_q_heads, cfg.head_dim)
+    K_tail = np.ascontiguousarray(_h(K_tail)); V_tail = np.ascontiguousarray(_h(V_tail))
+    out = np.zeros((B, Q, Hq, D), np.float64)
+    stride = 0 if expert is None else expert.shape[1]
+    rc = lib().moqae_decode_attn_multi_ref(C.byref(cfg.c()), _p(q), C.c_int32(Q), _p(arena), _p(chunk_off), _p(expert),
+                                           C.c_int64(stride), C.c_int32(n_chunks), _p(K_tail), _p(V_tail), C.c_int32(n_tail),
+                                           C.c_double(softmax_scale), _p(out))
+    if rc != 0:
+        raise ValueError(f"moqae_decode_attn_multi_ref -> {rc}")
+    return out
+
+
 def router_loss_grad(cfg: RefCfg, K: np.ndarray, token_begin: int, token_end: int, W1, W2, W3, bias, nll: np.ndarray,
                      pen_model: np.ndarray, pen_mem: np.ndarray, lam: float):
     """Eq. (3)-(5) over tokens [token_begin, token_end) of every (b, h).  Returns (loss[3] = L, L_model, L_mem,

@@ -65,7 +65,7 @@ EXPORTS = ["moqae_route_chunks", "moqae_quantize_pack", "moqae_decode_attn", "mo
            "moqae_decode_attn_static", "moqae_static_scratch_bytes",
            "moqae_pool_page_bytes", "moqae_pool_base", "moqae_pool_arena_bytes", "moqae_pool_state_bytes",
            "moqae_pool_init", "moqae_route_pack_paged", "moqae_pool_release", "moqae_pool_free_pages",
-           "moqae_router_loss_grad"]
+           "moqae_router_loss_grad", "moqae_decode_attn_multi", "moqae_decode_workspace_bytes_multi"]
 # measurement aids of include/moqae_bench.h (bench.py only)
 BENCH_EXPORTS = ["moqae_bench_time_decode_kernel", "moqae_bench_stream_read", "moqae_bench_stream_sink_words"]
 
@@ -106,6 +106,10 @@ def lib():
         L.moqae_route_pack_paged.restype = C.c_int
         L.moqae_route_pack_paged.argtypes = [C.POINTER(_Cfg), pcp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, i64, vp,
                                              vp, vp, vp, i64, vp, vp]
+        L.moqae_decode_attn_multi.restype = C.c_int
+        L.moqae_decode_attn_multi.argtypes = [C.POINTER(_Cfg), vp, i32, vp, vp, vp, i64, i32, vp, vp, i32, C.c_float, vp, vp, u64, vp]
+        L.moqae_decode_workspace_bytes_multi.restype = u64
+        L.moqae_decode_workspace_bytes_multi.argtypes = [C.POINTER(_Cfg), i32, i32]
         L.moqae_router_loss_grad.restype = C.c_int
         L.moqae_router_loss_grad.argtypes = [C.POINTER(_Cfg), vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp,
                                              C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_float, vp, vp, vp, vp, vp, vp]
@@ -341,6 +345,32 @@ def decode_attn(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_
               n_chunks, _ptr(K_tail), _ptr(V_tail), n_tail, float(softmax_scale), _ptr(out),
               _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "moqae_decode_attn_planned" if planned else "moqae_decode_attn")
+
+
+def decode_workspace_bytes_multi(cfg: Cfg, n_chunks: int, n_queries: int) -> int:
+    return int(lib().moqae_decode_workspace_bytes_multi(C.byref(cfg.c()), n_chunks, n_queries))
+
+
+def decode_attn_multi(cfg: Cfg, q: torch.Tensor, arena: Optional[torch.Tensor], chunk_off: Optional[torch.Tensor],
+                      expert: Optional[torch.Tensor], n_chunks: int, K_tail: torch.Tensor, V_tail: torch.Tensor, n_tail: int,
+                      softmax_scale: float, out: torch.Tensor, workspace: torch.Tensor) -> None:
+    """q: fp16 [B, Q, Hq, D] (Q new tokens whose K, V rows are the last Q valid residual rows); out: fp32 [B, Q, Hq, D]."""
+    assert q.is_cuda and q.dtype == torch.float16 and q.is_contiguous() and q.dim() == 4
+    B, Q, Hq, D = q.shape
+    assert (B, Hq, D) == (cfg.batch, cfg.n_q_heads, cfg.head_dim)
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+    stride = 0
+    if n_chunks > 0:
+        assert expert.dtype == torch.uint8 and chunk_off.dtype == torch.int64
+        assert expert.shape == chunk_off.shape and expert.is_contiguous() and chunk_off.is_contiguous()
+        stride = expert.shape[1]
+    for t in (K_tail, V_tail):
+        assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous()
+        assert t.shape == (cfg.batch, cfg.n_kv_heads, cfg.chunk, cfg.head_dim)
+    _check(lib().moqae_decode_attn_multi(C.byref(cfg.c()), _ptr(q), Q, _ptr(arena), _ptr(chunk_off), _ptr(expert), stride,
+                                         n_chunks, _ptr(K_tail), _ptr(V_tail), n_tail, float(softmax_scale), _ptr(out),
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "moqae_decode_attn_multi")
 
 
 def static_scratch_bytes() -> int:

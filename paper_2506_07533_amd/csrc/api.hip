@@ -252,7 +252,7 @@ static int decode_uniform(const moqae_cfg *cfg,
                           float softmax_scale,
                           float *out,
                           void *workspace, uint64_t workspace_bytes,
-                          void *stream, int planned) {
+                          void *stream, int planned, int nq = 1) {
     if (!cfg_ok(cfg) || !decode_ok(cfg) || !q || !out || !workspace) return MOQAE_E_INVAL;
     if (n_chunks < 0 || n_tail < 0 || n_tail >= cfg->chunk || n_chunks + n_tail <= 0) return MOQAE_E_INVAL;
     if (n_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride < n_chunks)) return MOQAE_E_INVAL;
@@ -267,6 +267,7 @@ static int decode_uniform(const moqae_cfg *cfg,
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
     a.seq_chunks = nullptr; a.seq_tail = nullptr; a.planned = planned; a.kpc = cfg->k_per_channel;
+    a.nq = nq; a.rep_in = cfg->n_q_heads / cfg->n_kv_heads / nq;
     a.counters = static_cast<unsigned int *>(workspace);
     a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, n_chunks)); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;
@@ -418,6 +419,24 @@ int moqae_router_loss_grad(const moqae_cfg *cfg,
     return launch_router_train(a, cu_count(), static_cast<hipStream_t>(stream)) == hipSuccess ? MOQAE_OK : MOQAE_E_HIP;
 }
 
+int moqae_decode_attn_multi(const moqae_cfg *cfg, const void *q, int32_t n_queries,
+                            const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
+                            int64_t desc_stride, int32_t n_chunks,
+                            const void *K_tail, const void *V_tail, int32_t n_tail,
+                            float softmax_scale, float *out, void *workspace, uint64_t workspace_bytes, void *stream) {
+    if (!cfg_ok(cfg) || n_queries < 1 || n_queries > 8 || n_tail < n_queries) return MOQAE_E_INVAL;
+    moqae_cfg c2 = *cfg;                                  // the queries of a KV head: n_queries * Hq / Hkv rows of the kernel's tile
+    c2.n_q_heads = cfg->n_q_heads * n_queries;
+    return decode_uniform(&c2, q, arena, chunk_off, expert, desc_stride, n_chunks, K_tail, V_tail, n_tail, softmax_scale,
+                          out, workspace, workspace_bytes, stream, 0, n_queries);
+}
+uint64_t moqae_decode_workspace_bytes_multi(const moqae_cfg *cfg, int32_t n_chunks, int32_t n_queries) {
+    if (!cfg_ok(cfg) || n_queries < 1 || n_queries > 8 || n_chunks < 0) return 0;
+    moqae_cfg c2 = *cfg;
+    c2.n_q_heads = cfg->n_q_heads * n_queries;
+    return moqae_decode_workspace_bytes(&c2, n_chunks);
+}
+
 int moqae_decode_attn_planned(const moqae_cfg *cfg, const void *q,
                               const void *arena, const uint64_t *chunk_off, const uint8_t *expert,
                               int64_t desc_stride, int32_t n_chunks,
@@ -468,6 +487,7 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
     a.seq_chunks = n_chunks_seq; a.seq_tail = n_tail_seq; a.planned = 0; a.kpc = 0;
+    a.nq = 1; a.rep_in = cfg->n_q_heads / cfg->n_kv_heads;
     a.counters = static_cast<unsigned int *>(workspace);
     a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, max_chunks)); a.out = out;
     a.scale_log2 = softmax_scale * 1.4426950408889634f;

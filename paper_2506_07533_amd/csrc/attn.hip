@@ -122,7 +122,7 @@ template <int BITS> __device__ __forceinline__ int pair_exp(int k) {
 template <int G, int REP>
 __device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_max, int lane) {
     const float m_new = fmaxf(st.m[r], unit_max);
-    const float alpha = fast_exp2(st.m[r] - m_new);       // first unit: exp2(-inf) = 0
+    const float alpha = (m_new == -INFINITY) ? 1.0f : fast_exp2(st.m[r] - m_new);   // first unit: exp2(-inf) = 0; nothing seen yet: unchanged
     st.m[r] = m_new;
     st.lsum[r] *= alpha; st.z[r] *= alpha; st.acc[r][0] *= alpha; st.acc[r][1] *= alpha;
     if constexpr (REP == 1) {
@@ -146,6 +146,7 @@ __device__ __forceinline__ void rescale(WaveState<REP> &st, int r, float unit_ma
 // wave-uniform and live in scalar registers; lgb = log2(bit-width) (1, 2, 3; 4 = raw fp16).
 struct Unit {
     int lgb, nsub, nvalid;                               // nvalid: valid rows of an fp16 unit
+    int tail_rows;                                       // residual units: valid residual rows from the unit's first row on (else huge)
     const uint8_t *kb, *vb;                              // bases: the chunk block (both), or the residual K and V rows of the row
     uint32_t kc, km, vc, vm;                             // byte offsets of the unit's K codes / K meta (from kb), V codes / V meta (from vb)
 };
@@ -234,13 +235,15 @@ __device__ __forceinline__ void value_weights(const VRegs<G> &v, int lane, int w
 // 16 rows: lane l holds dims 8*(l%16)..+7 of row 4*j + l/16, for K and for V alike.  Every lane of
 // a row ends up with the row's score, so the weights need no trip through LDS: the score phase
 // leaves p[r][j] in registers for the value phase.
+// Several queries per sequence (nq > 1; head r belongs to query r / rep_in): query t does not see the residual rows of
+// the queries after it, the last nq - 1 - t valid rows.
 template <int G, int REP, int NWV, typename KR>
-__device__ __forceinline__ void fp16_scores(const Unit &u, const KR &k, int lane, float scale_log2,
+__device__ __forceinline__ void fp16_scores(const Unit &u, const KR &k, int lane, float scale_log2, int nq, int rep_in,
                                             AttnLds<G, REP, NWV> &L, WaveState<REP> &st, float (&p4)[REP][4]) {
     const int part = lane & 15, tok_l = lane >> 4;
-    const int nvalid = u.nvalid;                          // an fp16 unit always spans 16 rows
 #pragma unroll
     for (int r = 0; r < REP; r++) {
+        const int nvalid = REP == 1 ? u.nvalid : min(u.nvalid, u.tail_rows - (nq - 1 - r / rep_in));   // an fp16 unit spans 16 rows
         const uint4 qv = *reinterpret_cast<const uint4 *>(&L.qtab[r][part * 4]);
         float s4[4], lmax = -INFINITY;
 #pragma unroll
@@ -256,7 +259,7 @@ __device__ __forceinline__ void fp16_scores(const Unit &u, const KR &k, int lane
         rescale<G, REP>(st, r, wave_max(lmax), lane);
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            p4[r][j] = fast_exp2(s4[j] - st.m[r]);                    // masked rows: exp2(-inf) = 0
+            p4[r][j] = (s4[j] == -INFINITY) ? 0.0f : fast_exp2(s4[j] - st.m[r]);   // masked rows
             if (part == 0) st.lsum[r] += p4[r][j];
         }
     }
@@ -1131,9 +1134,12 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
         uint64_t o_first[2] = {0ull, 0ull};
         {
             static_assert(REP * 64 <= NT, "one query word per thread");
-            const int bq = u / a.Hkv, hq0 = (u % a.Hkv) * REP;
-            const uint32_t *qrow32 = reinterpret_cast<const uint32_t *>(a.q + ((int64_t)bq * a.Hkv * REP + hq0) * kD);
-            if (tid < REP * 64) q_first = qrow32[tid];
+            // head r of the row = query r / rep_in, query head (u % Hkv) * rep_in + r % rep_in of q [B, nq, Hkv * rep_in, D]
+            if (tid < REP * 64) {
+                const int r = tid >> 6, bq = u / a.Hkv;
+                const int64_t qrow = ((int64_t)bq * a.nq + r / a.rep_in) * (a.Hkv * a.rep_in) + (u % a.Hkv) * a.rep_in + r % a.rep_in;
+                q_first = reinterpret_cast<const uint32_t *>(a.q)[qrow * 64 + (tid & 63)];
+            }
 #pragma unroll
             for (int k = 0; k < 2; k++) {
                 const int c = tid * KPT + k;
@@ -1295,7 +1301,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     const uint8_t *blk = a.arena + (((unsigned long long)dhi << 32) | (dlo & ~0xffu));
                     const int t0 = sidx << (8 - lgb);
                     un.lgb = lgb;
-                    un.nsub = min(4, (N - t0) >> (6 - lgb)); un.nvalid = un.nsub << (6 - lgb);
+                    un.nsub = min(4, (N - t0) >> (6 - lgb)); un.nvalid = un.nsub << (6 - lgb); un.tail_rows = 1 << 20;
                     un.kb = blk; un.vb = blk;
                     if (lgb == 4) {
                         un.kc = (uint32_t)t0 << 8; un.vc = un.kc + ((uint32_t)N << 8);
@@ -1309,7 +1315,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     }
                 } else {                                 // 16 rows of the FP16 residual
                     const int row0 = (int)(tk - n_chunk_units) * 16;
-                    un.lgb = 4; un.nsub = 4; un.nvalid = min(16, n_tail - row0);
+                    un.lgb = 4; un.nsub = 4; un.nvalid = min(16, n_tail - row0); un.tail_rows = n_tail - row0;
                     un.kb = reinterpret_cast<const uint8_t *>(a.K_tail) + (size_t)u * N * 256;
                     un.vb = reinterpret_cast<const uint8_t *>(a.V_tail) + (size_t)u * N * 256;
                     un.kc = un.vc = (uint32_t)row0 * 256u;
@@ -1353,7 +1359,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     if (lgb == 1)      pc_scores<2, G, NWV>(cur, kr, lane, wave, a.scale_log2, L, st);
                     else if (lgb == 2) pc_scores<4, G, NWV>(cur, kr, lane, wave, a.scale_log2, L, st);
                     else if (lgb == 3) pc_scores<8, G, NWV>(cur, kr, lane, wave, a.scale_log2, L, st);
-                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
+                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, a.nq, a.rep_in, L, st, p4);
                     load_keys(pf);                        // half a unit ahead
                     if (lgb == 1)      iq_values<2, G, NWV>(vc, lane, wave, iq_weights<2, G, NWV>(vc, lane, wave, L, st), L, st);
                     else if (lgb == 2) iq_values<4, G, NWV>(vc, lane, wave, iq_weights<4, G, NWV>(vc, lane, wave, L, st), L, st);
@@ -1363,7 +1369,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     if (lgb == 1)      iq_scores<2, G, NWV>(cur, kr, lane, wave, L, st);
                     else if (lgb == 2) iq_scores<4, G, NWV>(cur, kr, lane, wave, L, st);
                     else if (lgb == 3) iq_scores<8, G, NWV>(cur, kr, lane, wave, L, st);
-                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
+                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, a.nq, a.rep_in, L, st, p4);
                     load_keys(pf);                        // half a unit ahead
                     if (lgb == 1)      iq_values<2, G, NWV>(vc, lane, wave, iq_weights<2, G, NWV>(vc, lane, wave, L, st), L, st);
                     else if (lgb == 2) iq_values<4, G, NWV>(vc, lane, wave, iq_weights<4, G, NWV>(vc, lane, wave, L, st), L, st);
@@ -1373,7 +1379,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     if (lgb == 1)      mc_scores<2, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
                     else if (lgb == 2) mc_scores<4, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
                     else if (lgb == 3) mc_scores<8, G, REP, NWV>(cur, kr, ak, qp, lane, wave, scale24, L, st);
-                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, L, st, p4);
+                    else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, a.nq, a.rep_in, L, st, p4);
                     load_keys(pf);                        // half a unit ahead
                     if (lgb == 1)      value_weights<2, G, REP, NWV>(vc, lane, wave, L, st);
                     else if (lgb == 2) value_weights<4, G, REP, NWV>(vc, lane, wave, L, st);
@@ -1494,7 +1500,7 @@ constexpr int kMergeGroups = 8;
 __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const float *__restrict__ part,
                                                                        float *__restrict__ out, int rep,
                                                                        const uint32_t *__restrict__ row_wgs, int max_partials,
-                                                                       unsigned int *zero_counters, int n_seg) {
+                                                                       unsigned int *zero_counters, int n_seg, int Hkv, int nq, int rep_in) {
     __shared__ float numl[kMergeGroups][kD];
     __shared__ float denl[kMergeGroups], ml[kMergeGroups];
     const int row = (int)blockIdx.x, tid = (int)threadIdx.x, d = tid & (kD - 1), grp = tid >> 7;
@@ -1528,7 +1534,9 @@ __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const floa
             const float f = (ml[g] == -INFINITY) ? 0.0f : fast_exp2(ml[g] - M);
             n = fmaf(numl[g][d], f, n); dn = fmaf(denl[g], f, dn);
         }
-        out[(int64_t)row * kD + d] = dn > 0.0f ? n / dn : 0.0f;         // a sequence without tokens: zeros
+        const int rr = row % rep;                                       // out [B, nq, Hkv * rep_in, D]: head rr = query rr / rep_in
+        const int64_t orow = ((int64_t)(u / Hkv) * nq + rr / rep_in) * (Hkv * rep_in) + (u % Hkv) * rep_in + rr % rep_in;
+        out[orow * kD + d] = dn > 0.0f ? n / dn : 0.0f;                 // a sequence without tokens: zeros
     }
 }
 
@@ -1555,7 +1563,7 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
             hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)(a.BH * a.rep)), dim3(kD * kMergeGroups), 0, s,
                                (const float *)a.part, a.out, a.rep,
                                (const uint32_t *)(a.counters + (size_t)a.BH * n_seg * kCounterStride + a.BH), a.max_partials,
-                               a.planned ? a.counters : (unsigned int *)nullptr, n_seg);
+                               a.planned ? a.counters : (unsigned int *)nullptr, n_seg, a.Hkv, a.nq, a.rep_in);
             return hipGetLastError();
         }
     }
@@ -1572,7 +1580,7 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
     hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)(a.BH * a.rep)), dim3(kD * kMergeGroups), 0, s,
                        (const float *)a.part, a.out, a.rep,
                        (const uint32_t *)(a.counters + (size_t)a.BH * n_seg * kCounterStride + a.BH), a.max_partials,
-                       a.planned ? a.counters : (unsigned int *)nullptr, n_seg);
+                       a.planned ? a.counters : (unsigned int *)nullptr, n_seg, a.Hkv, a.nq, a.rep_in);
     return hipGetLastError();
 }
 

@@ -67,6 +67,7 @@ struct AttnArgs {
     float scale_log2;           // softmax_scale * log2(e)
     int n_chunks, n_tail, n_wg, max_partials, N, G, Hkv, rep, BH;
     int kpc;                    // keys quantised per channel
+    int nq, rep_in;             // queries per sequence (1: decode of one token) and query heads per KV head of one query; rep = nq * rep_in
     int planned;                // the workspace holds a plan: no prep kernel, the merge kernel zeroes the counters again
     int bits_of[8];
 };

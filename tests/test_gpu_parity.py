@@ -358,6 +358,44 @@ def test_per_channel_keys_limits(mq):
     assert mq.chunk_block_bytes(mq.Cfg(1, 2, 2, 128, 32, 64, (2, 16), 1, 1), 2) == 0     # token groups must tile the chunk
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,Q,N,G,C,T", [
+    (1, 2, 2, 4, 128, 64, 23, 50),       # four new tokens, one query head per KV head
+    (2, 4, 2, 2, 64, 64, 17, 2),         # grouped queries x2, two new tokens, nothing else in the residual
+    (1, 4, 1, 2, 64, 64, 9, 33),         # x4 heads x 2 tokens: eight rows per KV head; the new tokens straddle two 16-row units
+    (1, 1, 1, 8, 256, 64, 5, 8),         # eight new tokens
+    (1, 2, 2, 4, 32, 64, 41, 4),         # chunks of 32 tokens
+    (1, 3, 3, 1, 128, 64, 6, 7),         # one query: the plain decode call
+    (1, 2, 2, 4, 64, 64, 0, 20),         # no packed chunk yet
+])
+def test_attention_several_queries(mq, ref, B, Hq, Hkv, Q, N, G, C, T):
+    """moqae_decode_attn_multi: Q new tokens per sequence, causal among themselves, against the oracle."""
+    rng = np.random.default_rng(Q * 100 + C)
+    bits = (2, 4, 8, 16)
+    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, 1)
+    S = C * N + T
+    K, V = _rand_kv(rng, B, Hkv, S)
+    q = rng.standard_normal((B, Q, Hq, 128), dtype=np.float32).astype(np.float16)
+    Kt = np.zeros((B, Hkv, N, 128), np.float16); Vt = np.zeros_like(Kt)
+    Kt[:, :, :T] = K[:, :, C * N:]; Vt[:, :, :T] = V[:, :, C * N:]
+    Kt[:, :, T:] = np.float16(np.nan); Vt[:, :, T:] = np.float16(np.inf)
+    if C > 0:
+        expert = rng.integers(0, 4, (B * Hkv, C)).astype(np.uint8)
+        (arena, used, off, status), (arena_ref, used_ref, off_ref, st_ref) = _pack_both(mq, ref, cfg, rcfg, K, V, 0, C, expert)
+        ed = _dev(expert)
+    else:
+        expert = arena = off = ed = arena_ref = off_ref = None
+    scale = 1 / math.sqrt(128)
+    o_ref = ref.decode_attn_multi(rcfg, q, arena_ref, off_ref, expert, C, Kt, Vt, T, scale)
+    out = torch.full((B, Q, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(mq.decode_workspace_bytes_multi(cfg, C, Q), dtype=torch.uint8, device="cuda"); ws.fill_(0xFF)
+    mq.decode_attn_multi(cfg, _dev(q), arena, off, ed, C, _dev(Kt), _dev(Vt), T, scale, out, ws)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(o).all()
+    err = np.abs(o - o_ref).max(-1) / np.abs(o_ref).max(-1)
+    assert err.max() <= ATTN_TOL, err.max()
+
+
 def test_attention_degenerate_cases(mq, ref):
     # residual rows only (no packed chunk), down to a single cached token
     assert _attn_case(mq, ref, 1, 4, 2, 64, 32, 0, 1, (2, 16), seed=1) <= ATTN_TOL

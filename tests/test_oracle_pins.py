@@ -550,3 +550,28 @@ def test_per_channel_attention_is_attention_over_the_decoded_cache(ref):
         Kh[C * N:] = Kt[0, u, :T]; Vh[C * N:] = Vt[0, u, :T]
         sc = 0.1 * (Kh @ q[0, u].astype(np.float64)); p = np.exp(sc - sc.max()); p /= p.sum()
         assert np.allclose(o[0, u], p @ Vh, rtol=1e-10, atol=1e-12)
+
+
+def test_several_queries_are_causal_attention_over_the_new_tokens(ref):
+    """All-16-bit cache: Q new tokens against torch fp64 attention over [cache + residual] with a causal mask on the
+    new tokens (query t sees everything up to and including its own row)."""
+    rng = np.random.default_rng(31)
+    B, Hq, Hkv, N, C, T, Q = 2, 4, 2, 64, 3, 21, 4
+    cfg = ref.RefCfg(B, Hq, Hkv, 128, N, 64, (16,), 0)
+    S = C * N + T
+    K = rng.standard_normal((B, Hkv, S, 128)).astype(np.float16); V = rng.standard_normal((B, Hkv, S, 128)).astype(np.float16)
+    q = rng.standard_normal((B, Q, Hq, 128)).astype(np.float16)
+    expert = np.zeros((B * Hkv, C), np.uint8)
+    arena = np.zeros(B * Hkv * C * 2 * N * 128 * 2 + 4096, np.uint8); used = np.zeros(1, np.uint64); off = np.zeros((B * Hkv, C), np.uint64)
+    assert ref.quantize_pack(cfg, K, V, 0, C, expert, arena, used, off) == 0
+    Kt = np.zeros((B, Hkv, N, 128), np.float16); Vt = np.zeros_like(Kt)
+    Kt[:, :, :T] = K[:, :, C * N:]; Vt[:, :, :T] = V[:, :, C * N:]
+    o = ref.decode_attn_multi(cfg, q, arena, off, expert, C, Kt, Vt, T, 0.11)
+    rep = Hq // Hkv
+    Kx = torch.from_numpy(K.astype(np.float64)).repeat_interleave(rep, 1); Vx = torch.from_numpy(V.astype(np.float64)).repeat_interleave(rep, 1)
+    qx = torch.from_numpy(q.astype(np.float64)).permute(0, 2, 1, 3)                           # [B, Hq, Q, D]
+    mask = torch.ones(Q, S, dtype=torch.bool)
+    for t in range(Q):
+        mask[t, S - (Q - 1 - t):] = False
+    want = torch.nn.functional.scaled_dot_product_attention(qx, Kx, Vx, attn_mask=mask, scale=0.11).permute(0, 2, 1, 3).numpy()
+    assert np.allclose(o, want, rtol=1e-9, atol=1e-12)
