@@ -84,7 +84,9 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 150 for one layer, 10 for the stack)")
-    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 5; 2 for the stack)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed steps (default 60 for one layer: after the seconds of host-side input generation the GPU needs "
+                         "some 40 steps, about 40 ms, before its kernel times settle; 2 for the stack)")
     ap.add_argument("--workload", default="llama13b_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-only", action="store_true",
@@ -129,7 +131,7 @@ def main() -> int:
     if args.steps is None:
         args.steps = 10 if stack_like else 150
     if args.warmup is None:
-        args.warmup = 2 if stack_like else 5
+        args.warmup = 2 if stack_like else 60
     if args.sweep == "chunk":
         if w.n_layers > 1:
             print("bench.py: --sweep chunk takes a single-layer workload", file=sys.stderr)
