@@ -154,7 +154,7 @@ static int cfg_ok(const moqae_ref_cfg *c)
     if (c->n_q_heads % c->n_kv_heads) return 0;
     if (c->head_dim < 2 || c->head_dim % 2) return 0;
     if (c->group < 1 || c->head_dim % c->group) return 0;
-    if (c->chunk < 32 || c->chunk % 32) return 0;
+    if (c->chunk != 8 && c->chunk != 16 && (c->chunk < 32 || c->chunk % 32)) return 0;
     if (c->n_experts < 1 || c->n_experts > 8) return 0;
     for (int j = 0; j < c->n_experts; j++) if (!bits_ok(c->expert_bits[j])) return 0;
     if (c->freeze_chunks < 0) return 0;
@@ -169,15 +169,24 @@ static int first_16bit_expert(const moqae_ref_cfg *c)
     return -1;
 }
 
+/* Tokens the V code area has room for: the chunk's N, but at least one slice of the V layout
+ * (see v_code_pos: max(32/b, 8) tokens), so a chunk of 8 tokens at 2 bits is stored as a slice
+ * of 16 whose upper half holds zero codes.                                                    */
+static int v_token_room(int N, int b)
+{
+    int TQ = 32 / b > 8 ? 32 / b : 8;
+    return N < TQ ? TQ : N;
+}
+
 /* Bytes of one chunk block (K and V together) at bit-width b.
- * b < 16 : [K codes][K meta][V codes][V meta], codes N*D*b/8 bytes,
- *          meta one 32-bit word per (token, group);
+ * b < 16 : [K codes][K meta][V codes][V meta], K codes N*D*b/8 bytes, V codes
+ *          v_token_room(N, b)*D*b/8 bytes, meta one 32-bit word per (token, group);
  * b = 16 : [K raw fp16][V raw fp16].                                  */
 uint64_t moqae_ref_chunk_block_bytes(const moqae_ref_cfg *c, int32_t b)
 {
     uint64_t N = (uint64_t)c->chunk, D = (uint64_t)c->head_dim, G = (uint64_t)c->group;
     if (b == 16) return 2u * N * D * 2u;
-    return 2u * (N * D * (uint64_t)b / 8u + N * (D / G) * 4u);
+    return (N + (uint64_t)v_token_room(c->chunk, b)) * D * (uint64_t)b / 8u + 2u * N * (D / G) * 4u;
 }
 
 static uint64_t round_up_256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
@@ -320,16 +329,17 @@ void moqae_ref_quantize_group(const uint16_t *x, int G, int bits, uint8_t *codes
  *          64 slots x 4 words (1 KiB).  With TW = 32/b tokens per word, a slot
  *          holds a slice of TQ = max(TW, 8) consecutive tokens of one
  *          dimension (WD = TQ/TW words) for CPK = 4/WD dimensions that lie 16
- *          apart.  A token block is TB = min(4*TQ, N) tokens = QD = TB/TQ
- *          slices (QD = 4 except for 32-token chunks at 2 bits, where the whole
- *          chunk is one block of QD = 2 slices and a tile has 32 slots); token t
+ *          apart.  A token block is TB = min(4*TQ, max(N, TQ)) tokens = QD = TB/TQ
+ *          slices (QD = 4 for chunks of 64 tokens and more; a shorter chunk is one
+ *          block of QD = 1, 2 or 4 slices and a tile has 16*QD slots; a chunk of 8
+ *          tokens at 2 bits fills half of its one slice, the rest stays zero); token t
  *          of the chunk sits in block t / TB, slice qd = (t % TB) / TQ, and
  *          inside the slice in word w = (t % TQ) / TW at in-word index
  *          e = t % TW.  Dimension d = 16*ct + j belongs to tile cg = ct / CPK of
  *          its block (D / (16*CPK) tiles per block), slot 16*qd + j, word
  *          n = (ct % CPK) * WD + w of the slot:
  *              word index = ((block * D/(16*CPK) + cg) * 16*QD + 16*qd + j) * 4 + n.
- *          Needs D % 64 == 0 and N % 64 == 0 or N == 32.                     */
+ *          Needs D % 64 == 0 and N % 64 == 0 or N in {8, 16, 32}.            */
 static void k_code_pos(int t, int d, int D, int b, uint32_t *word, int *bit)
 {
     int n = 32 / b, e = d % n;
@@ -339,7 +349,8 @@ static void k_code_pos(int t, int d, int D, int b, uint32_t *word, int *bit)
 static void v_code_pos(int t, int d, int N, int D, int b, uint32_t *word, int *bit)
 {
     int TW = 32 / b, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD;
-    int TB = 4 * TQ < N ? 4 * TQ : N, QD = TB / TQ;
+    int room = N < TQ ? TQ : N;
+    int TB = 4 * TQ < room ? 4 * TQ : room, QD = TB / TQ;
     int block = t / TB, qd = (t % TB) / TQ, w = (t % TQ) / TW, e = t % TW;
     int ct = d / 16, j = d % 16, cg = ct / CPK, n = (ct % CPK) * WD + w;
     *word = (uint32_t)(((block * (D / (16 * CPK)) + cg) * (16 * QD) + 16 * qd + j) * 4 + n);
@@ -349,7 +360,7 @@ static void v_code_pos(int t, int d, int N, int D, int b, uint32_t *word, int *b
 static int layout_ok(const moqae_ref_cfg *c)
 {
     for (int j = 0; j < c->n_experts; j++)
-        if (c->expert_bits[j] < 16 && (c->head_dim % 64 || (c->chunk % 64 && c->chunk != 32))) return 0;
+        if (c->expert_bits[j] < 16 && (c->head_dim % 64 || (c->chunk % 64 && c->chunk != 32 && c->chunk != 16 && c->chunk != 8))) return 0;
     return 1;
 }
 
@@ -377,9 +388,10 @@ void moqae_ref_pack_chunk(const moqae_ref_cfg *cfg, int bits,
         return;
     }
     const size_t code_bytes = (size_t)N * D * bits / 8, meta_bytes = (size_t)N * NG * 4;
+    const size_t v_code_bytes = (size_t)v_token_room(N, bits) * D * bits / 8;
     uint8_t *k_codes = blk, *k_meta = k_codes + code_bytes;
-    uint8_t *v_codes = k_meta + meta_bytes, *v_meta = v_codes + code_bytes;
-    memset(blk, 0, 2 * (code_bytes + meta_bytes));
+    uint8_t *v_codes = k_meta + meta_bytes, *v_meta = v_codes + v_code_bytes;
+    memset(blk, 0, code_bytes + v_code_bytes + 2 * meta_bytes);
     uint8_t *codes = malloc((size_t)G);
     /* Keys quantised per channel (the outlier channels of key caches that Sec. 2.2 quotes from KIVI make a group
      * of dims share one huge range; along tokens a channel is homogeneous): a group is G consecutive tokens of one
@@ -434,8 +446,9 @@ void moqae_ref_decode_chunk(const moqae_ref_cfg *cfg, int bits, const uint8_t *b
         return;
     }
     const size_t code_bytes = (size_t)N * D * bits / 8, meta_bytes = (size_t)N * NG * 4;
+    const size_t v_code_bytes = (size_t)v_token_room(N, bits) * D * bits / 8;
     const uint8_t *k_codes = blk, *k_meta = k_codes + code_bytes;
-    const uint8_t *v_codes = k_meta + meta_bytes, *v_meta = v_codes + code_bytes;
+    const uint8_t *v_codes = k_meta + meta_bytes, *v_meta = v_codes + v_code_bytes;
     for (int t = 0; t < N; t++) for (int d = 0; d < D; d++) {
         uint32_t mk, mv, word; int bit;
         memcpy(&mk, k_meta + 4u * (size_t)(cfg->k_per_channel ? (t / G) * D + d : t * NG + d / G), 4);

@@ -143,7 +143,7 @@ def pack_chunk(cfg: RefCfg, bits: int, Kc: np.ndarray, Vc: np.ndarray) -> np.nda
     """Kc, Vc: [N, D] fp16 rows of one chunk -> the chunk block bytes."""
     Kc = np.ascontiguousarray(_h(Kc)); Vc = np.ascontiguousarray(_h(Vc))
     assert Kc.shape == (cfg.chunk, cfg.head_dim) == Vc.shape
-    assert bits == 16 or ((cfg.chunk % 64 == 0 or cfg.chunk == 32) and cfg.head_dim % 64 == 0), "V layout needs N % 64 == 0 or N == 32, and D % 64 == 0"
+    assert bits == 16 or ((cfg.chunk % 64 == 0 or cfg.chunk in (8, 16, 32)) and cfg.head_dim % 64 == 0), "V layout needs N % 64 == 0 or N in (8, 16, 32), and D % 64 == 0"
     blk = np.zeros(chunk_block_bytes(cfg, bits), np.uint8)
     lib().moqae_ref_pack_chunk(C.byref(cfg.c()), bits, _p(Kc), _p(Vc), cfg.head_dim, _p(blk))
     return blk
@@ -153,7 +153,7 @@ def decode_chunk(cfg: RefCfg, bits: int, blk: np.ndarray):
     """Chunk block bytes -> (K^, V^) as float64 [N, D]."""
     blk = np.ascontiguousarray(blk, np.uint8)
     assert blk.size >= chunk_block_bytes(cfg, bits)
-    assert bits == 16 or ((cfg.chunk % 64 == 0 or cfg.chunk == 32) and cfg.head_dim % 64 == 0), "V layout needs N % 64 == 0 or N == 32, and D % 64 == 0"
+    assert bits == 16 or ((cfg.chunk % 64 == 0 or cfg.chunk in (8, 16, 32)) and cfg.head_dim % 64 == 0), "V layout needs N % 64 == 0 or N in (8, 16, 32), and D % 64 == 0"
     Kh = np.zeros((cfg.chunk, cfg.head_dim), np.float64)
     Vh = np.zeros_like(Kh)
     lib().moqae_ref_decode_chunk(C.byref(cfg.c()), bits, _p(blk), _p(Kh), _p(Vh))

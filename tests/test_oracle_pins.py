@@ -86,7 +86,7 @@ def _brute_router(K, W1, W2, W3, bias=None):
     return votes, margin
 
 
-@pytest.mark.parametrize("N,D,M", [(32, 8, 3), (64, 16, 4), (32, 128, 4), (96, 64, 5)])
+@pytest.mark.parametrize("N,D,M", [(32, 8, 3), (64, 16, 4), (32, 128, 4), (96, 64, 5), (16, 128, 4), (8, 128, 4)])
 def test_router_brute_force(ref, N, D, M):
     """A dropped term, SiLU on the wrong operand, a transposed W3 or a wrong
     vote rule all change the counts."""
@@ -261,6 +261,12 @@ _GEN = {
     "n32_k_dt_v_3dt": (lambda t, d: (d + t) % 4, lambda t, d: (3 * d + t + t // 16) % 4),
     "n32_g32_zero": (lambda t, d: (d + t) % 16 + d // 32 + 4 * (t % 4),
                      lambda t, d: (d + 5 * t + t // 8) % 16 + 2 * (d // 32) + t % 2),
+    "n16_k_dt_v_3dt": (lambda t, d: (d + t) % 4, lambda t, d: (3 * d + t + t // 8) % 4),
+    "n16_g32_zero": (lambda t, d: (d + t) % 16 + d // 32 + 4 * (t % 4),
+                     lambda t, d: (d + 5 * t + t // 8) % 16 + 2 * (d // 32) + t % 2),
+    "n8_k_dt_v_3dt": (lambda t, d: (d + t) % 4, lambda t, d: (3 * d + t) % 4),
+    "n8_k_7dt_v_3d11t": (lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (7 * d + t) % 256)),
+                         lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (3 * d + 11 * t) % 256))),
     "n128_kpc": (lambda t, d: (t + d) % 4 + d % 4 + 4 * (t // 64), lambda t, d: (3 * d + t + t // 64) % 4),
     "n128_k_7dt_v_3d11t": (lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (7 * d + t) % 256)),
                            lambda t, d: np.where(d % 64 == 0, 0, np.where(d % 64 == 1, 255, (3 * d + 11 * t + t // 32) % 256))),
@@ -278,10 +284,12 @@ def test_pack_words_golden(ref):
         fk, fv = _GEN[name]
         blk = ref.pack_chunk(cfg, bits, fk(t, d).astype(np.float16), fv(t, d).astype(np.float16))
         cb, mb = N * D * bits // 8, N * (D // G) * 4
-        areas = {"kcodes": 0, "kmeta": cb, "vcodes": cb + mb, "vmeta": 2 * cb + mb}
-        assert blk.size == 2 * (cb + mb)
+        vcb = max(N, 32 // bits, 8) * D * bits // 8                       # a chunk shorter than one V slice is stored as one slice
+        areas = {"kcodes": 0, "kmeta": cb, "vcodes": cb + mb, "vmeta": cb + mb + vcb}
+        assert blk.size == cb + vcb + 2 * mb
+        assert any(N == 8 and b == 2 for (_, b, (N, _, _, _)) in cases), "no case with a padded V slice"
         for area, idx, val in probes:
-            assert 4 * idx < (cb if area.endswith("codes") else mb)
+            assert 4 * idx < {"kcodes": cb, "vcodes": vcb}.get(area, mb)
             got = int(blk[areas[area] + 4 * idx: areas[area] + 4 * idx + 4].view("<u4")[0])
             assert got == val, (name, area, idx, hex(got), hex(val))
 
@@ -289,27 +297,34 @@ def test_pack_words_golden(ref):
 @pytest.mark.parametrize("bits", [2, 4, 8])
 def test_pack_bit_coverage_is_a_bijection(ref, bits):
     """Every element owns b bits of the code area and no two elements share a bit."""
-    for N, D, G in ((64, 128, 32), (32, 128, 64)):
+    for N, D, G in ((64, 128, 32), (32, 128, 64), (16, 128, 64), (8, 128, 32)):
         _bijection(ref, bits, N, D, G)
 
 
 def _bijection(ref, bits, N, D, G):
     cfg = ref.RefCfg(1, 1, 1, D, N, G, (bits, 16), 0)
     cb, mb = N * D * bits // 8, N * (D // G) * 4
-    tot_k = np.zeros(cb, np.uint8); tot_v = np.zeros(cb, np.uint8)
+    vcb = max(N, 32 // bits, 8) * D * bits // 8
+    tot_k = np.zeros(cb, np.uint8); tot_v = np.zeros(vcb, np.uint8)
     pop = lambda a: int(np.unpackbits(a).sum())
     for i in range(G):                                                  # element i of every group is the only non-zero one
         x = np.zeros((N, D), np.float16); x[:, i::G] = 1
         blk = ref.pack_chunk(cfg, bits, x, x)
-        k, v = blk[:cb], blk[cb + mb: 2 * cb + mb]
+        k, v = blk[:cb], blk[cb + mb: cb + mb + vcb]
         assert pop(k) == bits * N * (D // G) == pop(v)
         assert not (tot_k & k).any() and not (tot_v & v).any()
         tot_k |= k; tot_v |= v
-    assert (tot_k == 0xFF).all() and (tot_v == 0xFF).all()
+    assert (tot_k == 0xFF).all()
+    if vcb == cb:
+        assert (tot_v == 0xFF).all()
+    else:                                                               # 8 tokens at 2 bits: in-word indices 0..7 of every word
+        assert vcb == 2 * cb and (tot_v.view("<u4") == 0x00FF00FF).all()
 
 
 @pytest.mark.parametrize("bits,G,N", [(2, 64, 64), (4, 64, 64), (8, 64, 64), (2, 32, 64), (4, 32, 64), (16, 64, 64),
-                                      (2, 64, 32), (4, 32, 32), (8, 64, 32), (16, 64, 32)])
+                                      (2, 64, 32), (4, 32, 32), (8, 64, 32), (16, 64, 32),
+                                      (2, 64, 16), (4, 32, 16), (8, 64, 16), (16, 64, 16),
+                                      (2, 32, 8), (4, 64, 8), (8, 32, 8), (16, 64, 8)])
 def test_pack_decode_roundtrip_bound(ref, bits, G, N):
     """decode(pack(x)) stays within scale/2 of x for every element of K and V:
     the decoder reads each code, scale and zero from where the packer put it."""
@@ -326,7 +341,9 @@ def test_pack_decode_roundtrip_bound(ref, bits, G, N):
         assert np.array_equal(Kh, Kc.astype(np.float64)) and np.array_equal(Vh, Vc.astype(np.float64))
         return
     cb, mb = N * D * bits // 8, N * (D // G) * 4
-    for x, xh, moff in [(Kc, Kh, cb), (Vc, Vh, 2 * cb + mb)]:
+    vcb = max(N, 32 // bits, 8) * D * bits // 8
+    assert blk.size == cb + vcb + 2 * mb
+    for x, xh, moff in [(Kc, Kh, cb), (Vc, Vh, cb + mb + vcb)]:
         meta = blk[moff: moff + mb].view("<u4").reshape(N, D // G)
         s = (meta & 0xffff).astype(np.uint16).view(np.float16).astype(np.float64)
         z = (meta >> 16).astype(np.uint16).view(np.float16).astype(np.float64)
@@ -345,6 +362,11 @@ def test_block_sizes_offsets_and_capacity(ref):
     assert [ref.chunk_block_bytes(cfg, b) for b in (2, 4, 8, 16)] == [10240, 18432, 34816, 65536]
     cfg32 = ref.RefCfg(1, 1, 1, 128, 64, 32, (2, 4, 8, 16), 0)
     assert [ref.chunk_block_bytes(cfg32, b) for b in (2, 4, 8, 16)] == [6144, 10240, 18432, 32768]
+    # small chunks: 2 * (N*D*b/8 + N*(D/G)*4), except 8 tokens at 2 bits, whose V codes take a whole slice of 16 tokens
+    cfg16 = ref.RefCfg(1, 1, 1, 128, 16, 64, (2, 4, 8, 16), 0)
+    assert [ref.chunk_block_bytes(cfg16, b) for b in (2, 4, 8, 16)] == [1280, 2304, 4352, 8192]
+    cfg8 = ref.RefCfg(1, 1, 1, 128, 8, 32, (2, 4, 8, 16), 0)
+    assert [ref.chunk_block_bytes(cfg8, b) for b in (2, 4, 8, 16)] == [256 + 128 + 512 + 128, 1280, 2304, 4096]
     rng = np.random.default_rng(4)
     C = 5
     K = rng.standard_normal((2, 3, C * 128 + 7, 128)).astype(np.float16)
@@ -406,7 +428,8 @@ def _packed(ref, cfg, K, V, expert, C):
     return arena, off
 
 
-@pytest.mark.parametrize("B,Hq,Hkv,S,N", [(1, 4, 4, 256, 64), (2, 8, 2, 64 * 3 + 17, 64), (1, 2, 1, 5, 64)])
+@pytest.mark.parametrize("B,Hq,Hkv,S,N", [(1, 4, 4, 256, 64), (2, 8, 2, 64 * 3 + 17, 64), (1, 2, 1, 5, 64),
+                                          (1, 4, 2, 16 * 5 + 11, 16), (2, 2, 2, 8 * 9 + 7, 8)])
 def test_attention_all_16bit_equals_unquantised(ref, B, Hq, Hkv, S, N):
     """With only the FP16 expert the path must reproduce plain attention
     (residual rows included, GQA head mapping included)."""
@@ -427,10 +450,11 @@ def test_attention_all_16bit_equals_unquantised(ref, B, Hq, Hkv, S, N):
     assert np.abs(out - want).max() < 1e-12
 
 
-def test_attention_quantised_is_attention_over_decoded_cache(ref):
+@pytest.mark.parametrize("N,C,T", [(64, 6, 9), (16, 13, 5), (8, 21, 7)])
+def test_attention_quantised_is_attention_over_decoded_cache(ref, N, C, T):
     """Mixed bit-widths: the result equals library attention over the decoded K^, V^."""
     rng = np.random.default_rng(9)
-    B, Hq, Hkv, N, D, C, T = 2, 4, 2, 64, 128, 6, 9
+    B, Hq, Hkv, D = 2, 4, 2, 128
     S = C * N + T
     K = rng.standard_normal((B, Hkv, S, D)).astype(np.float32); K[..., [1, 2, 3, 4]] *= 10
     K = K.astype(np.float16); V = rng.standard_normal((B, Hkv, S, D)).astype(np.float16)
