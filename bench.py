@@ -95,7 +95,7 @@ def main() -> int:
                     help="sweep aid (implies --decode-only): every chunk takes the expert of this bit-width")
     ap.add_argument("--sweep", choices=["chunk", "share"], default=None,
                     help="trend sweeps on synthetic data (the paper's ablations, Table 3 and Table 5): 'chunk' runs the "
-                         "chosen single-layer workload at chunk sizes 32, 64, 128 and 256; 'share' runs an 8-layer cut of the "
+                         "chosen single-layer workload at chunk sizes 8, 16, 32, 64, 128 and 256; 'share' runs an 8-layer cut of the "
                          "stack workload with routing-sharing groups of 1, 2, 4 and 8 layers")
     ap.add_argument("--ragged", action="store_true",
                     help="decode attention over a batch of 16 sequences of 2k ... 32k tokens (one layer of the stack "
@@ -138,7 +138,7 @@ def main() -> int:
             return 2
         args.no_cpu_baseline = True
         rows = []
-        for N in (32, 64, 128, 256):
+        for N in (8, 16, 32, 64, 128, 256):
             r = bench_layer(args, dataclasses.replace(w, chunk=N, name=f"{w.name}/chunk{N}"))
             rows.append({"chunk": N, "chunks": r["config"]["chunks"], "packed_bytes": r["config"]["packed_bytes"],
                          "realised_mix": r["config"]["realised_mix"],
@@ -207,7 +207,7 @@ def bench_layer(args, w):
     blk = {b: mq.chunk_block_bytes(cfg, b) for b in w.expert_bits}
     packed_bytes = int(sum(blk[b] * int((bits_of == b).sum()) for b in w.expert_bits))
     mix = {str(b): round(float((bits_of == b).mean()), 4) for b in w.expert_bits}
-    cap = packed_bytes + 4096
+    cap = int(sum(-(-blk[b] // 256) * 256 * int((bits_of == b).sum()) for b in w.expert_bits)) + 4096   # every block starts on a multiple of 256
     arenas = [torch.zeros(cap, dtype=torch.uint8, device=dev) for _ in range(2)]
     useds = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(2)]
     offs = [torch.zeros((BH, C), dtype=torch.int64, device=dev) for _ in range(2)]

@@ -27,18 +27,20 @@
  *
  * Packed chunk block (bit-width b, N tokens, D = head_dim, G = group):
  *   b < 16 : [K codes | K meta | V codes | V meta]
- *            codes area = N*D*b/8 bytes of little-endian 32-bit words, a word
- *            holds 32/b codes, the code with in-word index e sits at bit
- *            16*(e%2) + b*(e/2);
+ *            codes area = N*D*b/8 bytes of little-endian 32-bit words (V codes of
+ *            8-token chunks at 2 bits: twice that, see below), a word holds 32/b
+ *            codes, the code with in-word index e sits at bit 16*(e%2) + b*(e/2);
  *            K codes: token-major rows of D*b/32 words, dim d -> word d/(32/b),
  *                     in-word index d%(32/b);
  *            V codes: dimension-major tiles of up to 64 slots x 4 words (1 KiB).
  *                     With TW = 32/b tokens per word, a slot holds a slice of
  *                     TQ = max(TW, 8) consecutive tokens of one dim (WD = TQ/TW
  *                     words) for CPK = 4/WD dims that lie 16 apart.  A token block
- *                     is TB = min(4*TQ, N) tokens = QD = TB/TQ slices (QD = 4; only
- *                     32-token chunks at 2 bits have QD = 2: the chunk is one block
- *                     and a tile has 32 slots).  Token t: block t/TB, slice
+ *                     is TB = min(4*TQ, max(N, TQ)) tokens = QD = TB/TQ slices: QD = 4
+ *                     for N >= 64; a shorter chunk is one block of QD = 1, 2 or 4
+ *                     slices and a tile has 16*QD slots; 8 tokens at 2 bits fill half
+ *                     of their one slice of 16 (the rest holds zero codes, so that
+ *                     area has 16*D*2/8 bytes).  Token t: block t/TB, slice
  *                     qd = (t % TB)/TQ, word w = (t % TQ)/TW, in-word index t % TW.
  *                     Dim d = 16*ct + j: tile cg = ct/CPK of the block, slot
  *                     16*qd + j, word n = (ct % CPK)*WD + w; word index in the area =
@@ -79,9 +81,10 @@ typedef struct {
                                query head hq reads KV head hq / (Hq/Hkv)                       */
     int32_t n_kv_heads;     /* Hkv                                                             */
     int32_t head_dim;       /* D, must be 128                                                  */
-    int32_t chunk;          /* N tokens per chunk, 32..256: a multiple of 32 for routing; 32 (the
-                               paper's default, Sec. 4.1) or a multiple of 64 for pack and decode
-                               (the V token blocks span 64 tokens at 2 bits)                    */
+    int32_t chunk;          /* N tokens per chunk: 8, 16, 32 (the paper's default, Sec. 4.1; Table 3
+                               sweeps 8..128) or a multiple of 64 up to 256 for pack and decode (the
+                               V token blocks span 64 tokens at 2 bits); routing alone also takes
+                               96, 160, 224                                                       */
     int32_t group;          /* G elements per quantisation group along D: 32 or 64             */
     int32_t n_experts;      /* M, 1..8                                                         */
     int32_t expert_bits[MOQAE_MAX_EXPERTS]; /* B_j in {2,4,8,16}; index order = tie-break order */

@@ -27,7 +27,7 @@ bool cfg_ok(const moqae_cfg *c) {
     if ((int64_t)c->batch * c->n_kv_heads > 65535) return false;          // grid.y
     if (c->head_dim != kD) return false;
     if (c->group != 32 && c->group != 64) return false;
-    if (c->chunk < 32 || c->chunk > 256 || c->chunk % 32) return false;
+    if (c->chunk != 8 && c->chunk != 16 && (c->chunk < 32 || c->chunk > 256 || c->chunk % 32)) return false;
     if (c->n_experts < 1 || c->n_experts > MOQAE_MAX_EXPERTS) return false;
     for (int j = 0; j < c->n_experts; j++) if (!bits_ok(c->expert_bits[j])) return false;
     if (c->freeze_chunks < 0) return false;
@@ -36,11 +36,11 @@ bool cfg_ok(const moqae_cfg *c) {
     return true;
 }
 
-// The packed layout (pack and decode calls): V token blocks span up to 64 tokens (chunks of 32 tokens
-// have their own tile shape), and the decode kernel's matrix-core path for grouped queries holds
+// The packed layout (pack and decode calls): V token blocks span up to 64 tokens (chunks of 8, 16 and 32 tokens
+// are one block with its own tile shape), and the decode kernel's matrix-core path for grouped queries holds
 // (query head, group) pairs in the 16 rows of a tile.
 bool layout_ok(const moqae_cfg *c) {
-    if (c->chunk % 64 && c->chunk != 32) return false;
+    if (c->chunk % 64 && c->chunk != 32 && c->chunk != 16 && c->chunk != 8) return false;
     const int rep = c->n_q_heads / c->n_kv_heads;
     return rep == 1 || rep * (kD / c->group) <= 16;
 }

@@ -176,21 +176,28 @@ __device__ __forceinline__ uint32_t ld4(const uint8_t *sbase, uint32_t voff) {
 
 // The V side: the 16-byte slots 64*j + l of the unit's V KiBs and its (token, group) meta
 // words 64*jj + l, same conventions.
-// CH32 (chunks of 32 tokens): at 2 bits the chunk's V codes are two tiles of 32 slots (two token slices of 16);
-// lanes 0..31 take tile cg = 0 into c[0] and tile cg = 1 into c[1] as the lanes of slices 0 and 1 of a 64-token
-// block would, the lanes of the absent slices 2, 3 and the absent second block hold zeros.
-template <int G, bool CH32>
-__device__ __forceinline__ void load_v(const Unit &u, int lane, VRegs<G> &v) {
+// SMALL (chunks of 8, 16 or 32 tokens, one unit per quantised chunk): the chunk is one token block of QD = 1, 2 or
+// 4 slices, its V codes are 2 (8 bits: 4) tiles of 16*QD slots.  With QD < 4 lanes 0..16*QD-1 take tile i into c[i]
+// as the lanes of the first slices of a full block would; the lanes of the absent slices and the registers of the
+// absent tiles / second block hold zeros.  The meta words of a short chunk are fewer than 64: the lanes past
+// them read the last one (their tokens have weight 0).
+template <int G, bool SMALL>
+__device__ __forceinline__ void load_v(const Unit &u, int lane, VRegs<G> &v, int N) {
     constexpr int NG = kD / G;
-    const uint32_t vv = u.vc + (uint32_t)lane * 16u, vmo = u.vm + (uint32_t)lane * 4u;
-    const int nvm = u.lgb == 4 ? 1 : (u.nsub * NG) >> u.lgb;              // >= 1
-    if (CH32 && u.lgb == 1) {
-        const uint32_t vh = u.vc + (uint32_t)(lane & 31) * 16u;
-        const uint4 t0 = ld16(u.vb, vh), t1 = ld16(u.vb, vh + 512u);
-        const bool lo = lane < 32;
-        v.c[0] = uint4{lo ? t0.x : 0u, lo ? t0.y : 0u, lo ? t0.z : 0u, lo ? t0.w : 0u};
-        v.c[1] = uint4{lo ? t1.x : 0u, lo ? t1.y : 0u, lo ? t1.z : 0u, lo ? t1.w : 0u};
-        v.c[2] = uint4{0u, 0u, 0u, 0u}; v.c[3] = uint4{0u, 0u, 0u, 0u};
+    const int nw = u.nvalid * NG;                                         // SMALL: meta words of the unit (u.nsub counts whole KiB of codes)
+    const uint32_t vv = u.vc + (uint32_t)lane * 16u, vmo = u.vm + (uint32_t)(SMALL ? min(lane, nw - 1) : lane) * 4u;
+    const int nvm = u.lgb == 4 ? 1 : (SMALL ? max(nw >> 6, 1) : (u.nsub * NG) >> u.lgb);   // rows of 64 meta words, >= 1
+    const int ts = SMALL && u.lgb < 4 ? min(64, (max(N, u.lgb == 1 ? 16 : 8) << 4) >> (u.lgb == 1 ? 4 : 3)) : 64;   // slots per tile
+    if (SMALL && ts < 64) {
+        const int ntile = u.lgb == 3 ? 4 : 2;
+        const uint32_t vh = u.vc + (uint32_t)(lane & (ts - 1)) * 16u;
+        const bool lo = lane < ts;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const uint4 t = ld16(u.vb, vh + (uint32_t)(min(i, ntile - 1) * ts) * 16u);
+            const bool ok = lo && i < ntile;
+            v.c[i] = uint4{ok ? t.x : 0u, ok ? t.y : 0u, ok ? t.z : 0u, ok ? t.w : 0u};
+        }
     } else if (u.nsub == 4) {
 #pragma unroll
         for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vb + j * 1024, vv);
@@ -423,7 +430,7 @@ __device__ __forceinline__ void mc_build_q(const uint32_t *qraw32, int lane, int
 // K side of a unit for grouped queries.  Quantised units: lane (x, qd) takes quarter qd of the code row
 // of token 16*tile + x for every tile, and the meta words of its own tokens; raw fp16 units keep the
 // slot order of load_k.  Eight 8-byte loads whatever the bit-width, branch-free like load_k.
-template <int G, int REP>
+template <int G, int REP, bool SMALL>
 __device__ __forceinline__ void load_k_mc(const Unit &u, int lane, KRegsMC<G, REP> &k) {
     using M = MC<G, REP>;
     const int x = lane & 15, qd = lane >> 4;
@@ -446,11 +453,12 @@ __device__ __forceinline__ void load_k_mc(const Unit &u, int lane, KRegsMC<G, RE
     } else {
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            const uint32_t jc = (uint32_t)min(j, u.nsub - 1);
+            // 8 bits: a tile of 16 tokens is two pieces per lane, also when the chunk has only 8 tokens (1 KiB)
+            const uint32_t jc = (uint32_t)min(j, (SMALL && u.lgb == 3 ? max(u.nsub, 2) : u.nsub) - 1);
             k.c[j] = ld16(u.kb, u.kc + lane_off + (u.lgb == 3 ? (jc >> 1) * 2048u + (jc & 1u) * 16u : jc * 1024u));
         }
     }
-    const int TU = raw ? 16 : (u.nsub << (6 - u.lgb));    // tokens of the unit
+    const int TU = raw ? 16 : u.nvalid;                   // tokens of the unit
 #pragma unroll
     for (int s = 0; s < M::NSMAX; s++) {
         const int t = min(16 * (s * M::F + M::sel(qd)) + x, TU - 1);
@@ -475,7 +483,7 @@ __device__ __forceinline__ void mc_scores(const Unit &u, const KRegsMC<G, REP> &
     constexpr int TL = 16 / BITS;                         // tiles of a full unit: 8, 4, 2
     constexpr int NS = (TL + F - 1) / F;
     const int x = lane & 15, qd = lane >> 4, sel = M::sel(qd);
-    const int TU = u.nsub << (6 - u.lgb);
+    const int TU = u.nvalid;
     float sv[NS][HPL], hmax[HPL];
 #pragma unroll
     for (int h = 0; h < HPL; h++) hmax[h] = -INFINITY;
@@ -635,7 +643,7 @@ __device__ __forceinline__ uint32_t word_of(const uint4 &c, int i) {
 // raw fp16 units keep the slot order and have no meta.
 // KPC (keys quantised per channel): the meta words are [token group][dim]; lane l takes the words of dims 2l, 2l+1 of
 // the (up to four) token groups the unit's tokens lie in.
-template <int G, bool KPC>
+template <int G, bool KPC, bool SMALL>
 __device__ __forceinline__ void load_k_iq(const Unit &u, int lane, KRegs<G> &k) {
     constexpr int NG = kD / G;
     const uint32_t xq = (uint32_t)lane >> 4, c = (uint32_t)lane & 15u;
@@ -671,7 +679,7 @@ __device__ __forceinline__ void load_k_iq(const Unit &u, int lane, KRegs<G> &k) 
     } else if (u.lgb == 2) {
         const uint32_t vm = u.km + (c * NG + (NG == 2 ? (xq >> 1) : xq)) * 4u;
 #pragma unroll
-        for (int j = 0; j < 4; j++) k.m[j][0] = ld4(u.kb + j * 16 * NG * 4, vm);
+        for (int j = 0; j < 4; j++) k.m[j][0] = ld4(u.kb + (SMALL ? min(j, u.nsub - 1) : j) * 16 * NG * 4, vm);   // a short chunk's block ends early
     } else if (u.lgb == 3) {
         const uint32_t vm = u.km + (c * NG + (NG == 2 ? 0u : (xq >> 1))) * 4u;
 #pragma unroll
@@ -703,7 +711,9 @@ __device__ __forceinline__ void iq_regroup(const KRegs<G> &k, int lane, int wave
 }
 
 // Scores of a quantised unit -> L.sc (log2 domain), running maximum updated.
-template <int BITS, int G, int NWV>
+// SMALL: the unit may hold fewer tokens than a KiB of codes does (chunks of 8 and 16 tokens); the scores of the
+// tokens past u.nvalid are masked one by one.
+template <int BITS, int G, int NWV, bool SMALL>
 __device__ __forceinline__ void iq_scores(const Unit &u, const KRegs<G> &k, int lane, int wave,
                                           AttnLds<G, 1, NWV> &L, WaveState<1> &st) {
     constexpr int NG = kD / G;
@@ -740,7 +750,8 @@ __device__ __forceinline__ void iq_scores(const Unit &u, const KRegs<G> &k, int 
                 ps = fmaf(half_bits_to_float(k.m[j][gi] >> 16), qp[gi], ps);
             }
             ps += __shfl_xor(ps, 16);
-            s4[j] = (j < u.nsub) ? ps * sc : -INFINITY;   // KiB past a short unit: ignored
+            const bool ok = SMALL ? 32 * j + 16 * (xq >> 1) + c < u.nvalid : j < u.nsub;   // KiB past a short unit: ignored
+            s4[j] = ok ? ps * sc : -INFINITY;
             lmax = fmaxf(lmax, s4[j]);
         }
         rescale<G, 1>(st, 0, wave_max(lmax), lane);
@@ -763,7 +774,8 @@ __device__ __forceinline__ void iq_scores(const Unit &u, const KRegs<G> &k, int 
             ps = fmaf(half_bits_to_float(k.m[j][0] & 0xffffu), iq_combine(acc), ps);
             ps += __shfl_xor(ps, 16);
             ps += __shfl_xor(ps, 32);
-            s4[j] = (j < u.nsub) ? ps * sc : -INFINITY;    // KiB past a short unit (32-token chunks): ignored
+            const bool ok = SMALL ? 16 * j + c < u.nvalid : j < u.nsub;   // KiB past a short unit: ignored
+            s4[j] = ok ? ps * sc : -INFINITY;
             lmax = fmaxf(lmax, s4[j]);
         }
         rescale<G, 1>(st, 0, wave_max(lmax), lane);
@@ -789,7 +801,7 @@ __device__ __forceinline__ void iq_scores(const Unit &u, const KRegs<G> &k, int 
             }
             ps += __shfl_xor(ps, 16);
             ps += __shfl_xor(ps, 32);
-            s2[jj] = ps * sc;
+            s2[jj] = (!SMALL || 16 * jj + c < u.nvalid) ? ps * sc : -INFINITY;
             lmax = fmaxf(lmax, s2[jj]);
         }
         rescale<G, 1>(st, 0, wave_max(lmax), lane);
@@ -1053,12 +1065,12 @@ __device__ __forceinline__ int lgb_of_bits(int bits) { return bits == 2 ? 1 : (b
 __device__ __forceinline__ uint32_t units_of_chunk(int N, int lgb) { return (uint32_t)((N + (256 >> lgb) - 1) >> (8 - lgb)); }
 
 // Chunks per row segment: at most kDescCap, and at most kUnitCap units if all of them were FP16.
-__host__ __device__ inline int attn_segment_chunks(int N) { return min(kDescCap, kUnitCap / (N / 16)); }
+__host__ __device__ inline int attn_segment_chunks(int N) { return min(kDescCap, kUnitCap / max(N / 16, 1)); }
 
 // RAGGED: the sequences of the batch have their own numbers of chunks and residual rows (a.seq_chunks,
 // a.seq_tail, device arrays indexed by sequence); a.n_chunks is then the bound that sizes the segments.
-// CH32: chunks of 32 tokens (a.N == 32), see load_v.  KPC: keys quantised per channel (REP == 1 only), see pc_scores.
-template <int G, int REP, int NWV, bool RAGGED, bool CH32, bool KPC>
+// SMALL: chunks of 8, 16 or 32 tokens (a.N < 64), see load_v.  KPC: keys quantised per channel (REP == 1 only), see pc_scores.
+template <int G, int REP, int NWV, bool RAGGED, bool SMALL, bool KPC>
 __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
     static_assert(!KPC || REP == 1, "per-channel keys: one query head per KV head");
     __shared__ AttnLds<G, REP, NWV> L;
@@ -1301,7 +1313,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     const uint8_t *blk = a.arena + (((unsigned long long)dhi << 32) | (dlo & ~0xffu));
                     const int t0 = sidx << (8 - lgb);
                     un.lgb = lgb;
-                    un.nsub = min(4, (N - t0) >> (6 - lgb)); un.nvalid = un.nsub << (6 - lgb); un.tail_rows = 1 << 20;
+                    un.nsub = max(min(4, (N - t0) >> (6 - lgb)), 1); un.nvalid = min(N - t0, 256 >> lgb); un.tail_rows = 1 << 20;
                     un.kb = blk; un.vb = blk;
                     if (lgb == 4) {
                         un.kc = (uint32_t)t0 << 8; un.vc = un.kc + ((uint32_t)N << 8);
@@ -1311,11 +1323,11 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                         un.kc = (uint32_t)t0 << (4 + lgb);
                         un.km = KPC ? cb + (uint32_t)(t0 / G) * (kD * 4u) : cb + (uint32_t)t0 * NG * 4;
                         un.vc = un.kc + cb + mb;
-                        un.vm = 2u * cb + mb + (uint32_t)t0 * NG * 4;
+                        un.vm = cb + mb + (SMALL ? (uint32_t)max(N, lgb == 1 ? 16 : 8) << (4 + lgb) : cb) + (uint32_t)t0 * NG * 4;   // 8 tokens at 2 bits: V codes of a whole slice
                     }
                 } else {                                 // 16 rows of the FP16 residual
                     const int row0 = (int)(tk - n_chunk_units) * 16;
-                    un.lgb = 4; un.nsub = 4; un.nvalid = min(16, n_tail - row0); un.tail_rows = n_tail - row0;
+                    un.lgb = 4; un.nsub = SMALL ? min(4, N >> 2) : 4; un.nvalid = min(16, n_tail - row0); un.tail_rows = n_tail - row0;   // the buffers hold N rows
                     un.kb = reinterpret_cast<const uint8_t *>(a.K_tail) + (size_t)u * N * 256;
                     un.vb = reinterpret_cast<const uint8_t *>(a.V_tail) + (size_t)u * N * 256;
                     un.kc = un.vc = (uint32_t)row0 * 256u;
@@ -1331,9 +1343,9 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             VRegs<G> va, vb;
             bool have = next_unit(cur);
             auto load_keys = [&](const Unit &un) {
-                if constexpr (REP == 1) load_k_iq<G, KPC>(un, lane, kr); else load_k_mc<G, REP>(un, lane, kr);
+                if constexpr (REP == 1) load_k_iq<G, KPC, SMALL>(un, lane, kr); else load_k_mc<G, REP, SMALL>(un, lane, kr);
             };
-            if (have) { load_keys(cur); load_v<G, CH32>(cur, lane, va); }
+            if (have) { load_keys(cur); load_v<G, SMALL>(cur, lane, va, N); }
             if (seg == 0) {                              // the q tables, behind the first units' loads
                 if constexpr (kLateTables) build_q_tables();
                 if constexpr (REP > 1) {
@@ -1354,7 +1366,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
 #pragma unroll
                     for (int mi = 0; mi < 4; mi++) ak[mi] = L.qmc[bi][mi][lane];
                 }
-                load_v<G, CH32>(pf, lane, vn);                  // a whole unit ahead
+                load_v<G, SMALL>(pf, lane, vn, N);              // a whole unit ahead
                 if constexpr (REP == 1 && KPC) {
                     if (lgb == 1)      pc_scores<2, G, NWV>(cur, kr, lane, wave, a.scale_log2, L, st);
                     else if (lgb == 2) pc_scores<4, G, NWV>(cur, kr, lane, wave, a.scale_log2, L, st);
@@ -1366,9 +1378,9 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
                     else if (lgb == 3) iq_values<8, G, NWV>(vc, lane, wave, iq_weights<8, G, NWV>(vc, lane, wave, L, st), L, st);
                     else                fp16_values<G, REP, NWV>(cur, vc, lane, wave, L, st, p4);
                 } else if constexpr (REP == 1) {
-                    if (lgb == 1)      iq_scores<2, G, NWV>(cur, kr, lane, wave, L, st);
-                    else if (lgb == 2) iq_scores<4, G, NWV>(cur, kr, lane, wave, L, st);
-                    else if (lgb == 3) iq_scores<8, G, NWV>(cur, kr, lane, wave, L, st);
+                    if (lgb == 1)      iq_scores<2, G, NWV, SMALL>(cur, kr, lane, wave, L, st);
+                    else if (lgb == 2) iq_scores<4, G, NWV, SMALL>(cur, kr, lane, wave, L, st);
+                    else if (lgb == 3) iq_scores<8, G, NWV, SMALL>(cur, kr, lane, wave, L, st);
                     else                fp16_scores<G, REP, NWV>(cur, kr, lane, a.scale_log2, a.nq, a.rep_in, L, st, p4);
                     load_keys(pf);                        // half a unit ahead
                     if (lgb == 1)      iq_values<2, G, NWV>(vc, lane, wave, iq_weights<2, G, NWV>(vc, lane, wave, L, st), L, st);
@@ -1555,7 +1567,7 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
     const dim3 grid((unsigned)a.n_wg), block(NWV * 64);
     if constexpr (REP == 1) {
         if (a.kpc) {                                      // uniform calls only (checked by the caller)
-            if (a.N == 32) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true, true>), grid, block, 0, s, a);
+            if (a.N < 64) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true, true>), grid, block, 0, s, a);
             else           hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, false, true>), grid, block, 0, s, a);
             hipError_t ek = hipGetLastError();
             if (ek != hipSuccess) return ek;
@@ -1567,7 +1579,7 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
             return hipGetLastError();
         }
     }
-    if (a.N == 32) {
+    if (a.N < 64) {
         if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, true, false>), grid, block, 0, s, a);
         else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true, false>), grid, block, 0, s, a);
     } else {

@@ -98,10 +98,16 @@ __device__ __forceinline__ float wave_max(float x) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Tokens the V code area of a chunk has room for: N, but at least one slice of the V layout (max(32/b, 8) tokens):
+// 8 tokens at 2 bits take a slice of 16 whose upper half holds zero codes.
+__host__ __device__ inline int v_token_room(int N, int b) {
+    const int TQ = 32 / b > 8 ? 32 / b : 8;
+    return N < TQ ? TQ : N;
+}
 // Bytes of one chunk block (K and V) at bit-width b.
 __host__ __device__ inline uint64_t block_bytes(int N, int G, int b) {
     return b == 16 ? (uint64_t)N * kD * 4u
-                   : 2u * ((uint64_t)N * kD * (uint64_t)b / 8u + (uint64_t)N * (kD / G) * 4u);
+                   : (uint64_t)(N + v_token_room(N, b)) * kD * (uint64_t)b / 8u + 2u * (uint64_t)N * (kD / G) * 4u;
 }
 
 }  // namespace moqae

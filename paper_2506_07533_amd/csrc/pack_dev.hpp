@@ -201,10 +201,11 @@ __device__ __forceinline__ void pack_side(const uint16_t *src, int64_t stride_s,
     }
 
     constexpr int NG = kD / G;                        // groups per row
-    const size_t code_bytes = (size_t)N * kD * bits / 8, meta_bytes = (size_t)N * NG * 4;
-    uint8_t *area = blk + (isV ? code_bytes + meta_bytes : 0);
+    const int room = isV ? v_token_room(N, bits) : N;  // tokens the code area has room for (V: at least one slice)
+    const size_t k_code_bytes = (size_t)N * kD * bits / 8, meta_bytes = (size_t)N * NG * 4;
+    uint8_t *area = blk + (isV ? k_code_bytes + meta_bytes : 0);
     uint32_t *codes_w = reinterpret_cast<uint32_t *>(area);
-    uint32_t *meta_w = reinterpret_cast<uint32_t *>(area + code_bytes);
+    uint32_t *meta_w = reinterpret_cast<uint32_t *>(area + (size_t)room * kD * bits / 8);
 
     if (KPC && !isV) {                               // keys quantised per channel: one wavefront per group of G tokens
         for (int tg = tid >> 6; tg < N / G; tg += NT >> 6) {
@@ -228,17 +229,19 @@ __device__ __forceinline__ void pack_side(const uint16_t *src, int64_t stride_s,
     __syncthreads();
     // V: dimension-major tiles of 16*QD slots x 4 words.  A slot holds TQ = max(TW, 8) consecutive tokens
     // (TW = 32/bits per word, WD = TQ/TW words) of CPK = 4/WD dimensions that lie 16 apart; a token block is
-    // TB = min(4*TQ, N) tokens = QD slices (QD = 4, i.e. 1-KiB tiles, except for 32-token chunks at 2 bits: QD = 2);
-    // slot 16*qd + j of tile cg of a block: dims 16*(cg*CPK + n/WD) + j, token slice qd.
+    // TB = min(4*TQ, room) tokens = QD slices (QD = 4, i.e. 1-KiB tiles, for N >= 64; a shorter chunk is one block of
+    // 1, 2 or 4 slices; 8 tokens at 2 bits fill half a slice); slot 16*qd + j of tile cg of a block: dims
+    // 16*(cg*CPK + n/WD) + j, token slice qd.
     const int TW = 32 / bits, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, NCG = kD / (16 * CPK);
-    const int TB = min(4 * TQ, N), QD = TB / TQ;
-    const int n_groups = N * kD * bits / 128;         // a thread builds the words of four adjacent dims at a time
+    const int TB = min(4 * TQ, room), QD = TB / TQ;
+    const int n_groups = room * kD * bits / 128;      // a thread builds the words of four adjacent dims at a time
     for (int g = tid; g < n_groups; g += NT) {
         const int n = g & 3, jq = (g >> 2) & 3, qd = (g >> 4) & (QD - 1), tile = g / (16 * QD);
         const int cg = tile % NCG, block = tile / NCG;
         const int d0 = 16 * (cg * CPK + n / WD) + 4 * jq, t0 = block * TB + qd * TQ + (n % WD) * TW;
         uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
-        for (int e = 0; e < TW; e++) {
+        const int te = min(TW, N - t0);               // tokens past the chunk (half a slice): zero codes
+        for (int e = 0; e < te; e++) {
             const uint32_t v4 = *reinterpret_cast<const uint32_t *>(vcodes + (t0 + e) * kVRow + d0);   // codes of dims d0..d0+3
             const int sh = code_shift(e, bits);
             w0 |= (v4 & 0xffu) << sh; w1 |= ((v4 >> 8) & 0xffu) << sh; w2 |= ((v4 >> 16) & 0xffu) << sh; w3 |= (v4 >> 24) << sh;

@@ -45,6 +45,7 @@ def _check_pages(mq, ref, cfg, rcfg, pages, K, V, expert_h, off_h, arena_h, c0, 
 
 @pytest.mark.parametrize("B,Hkv,N,G,C,freeze,kpc", [(1, 8, 64, 32, 12, 1, 0), (2, 3, 128, 64, 9, 1, 0), (1, 2, 256, 64, 5, 0, 0),
                                                    (2, 2, 32, 64, 21, 2, 0), (1, 3, 192, 32, 4, 1, 0),
+                                                   (2, 2, 16, 64, 25, 1, 0), (1, 3, 8, 32, 30, 1, 0),       # small chunks
                                                    (1, 3, 128, 64, 7, 1, 1)])       # keys quantised per channel
 def test_route_pack_paged(mq, ref, B, Hkv, N, G, C, freeze, kpc):
     rng = np.random.default_rng(B * 100 + N + C)

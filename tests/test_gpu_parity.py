@@ -60,6 +60,8 @@ def _rand_kv(rng, B, Hkv, S, outliers=True):
     (1, 2, 96, 4, 1, 0, 0.3, False),        # one expert; chunk not a multiple of 64
     (2, 2, 160, 3, 5, 1, 0.5, False),       # two LDS slabs with a ragged second one
     (1, 4, 128, 6, 2, 0, 1.0, True),
+    (2, 2, 16, 9, 4, 1, 0.3, False),        # the small chunks of Table 3's sweep
+    (1, 3, 8, 21, 4, 1, 0.3, True),
 ])
 def test_route_bit_exact(mq, ref, B, Hkv, N, C, M, freeze, std, use_bias):
     rng = np.random.default_rng(N * 100 + M)
@@ -125,7 +127,9 @@ def _pack_both(mq, ref, cfg, rcfg, K, V, c0, c1, expert, start=0, slack=0):
 
 @pytest.mark.parametrize("B,Hkv,N,G,C", [(1, 8, 64, 32, 32), (2, 2, 128, 64, 9), (1, 3, 64, 32, 6),
                                          (1, 2, 256, 64, 5), (1, 1, 192, 32, 8), (1, 2, 64, 64, 7),
-                                         (2, 3, 32, 64, 21), (1, 2, 32, 32, 10)])     # the paper's default chunk size
+                                         (2, 3, 32, 64, 21), (1, 2, 32, 32, 10),      # the paper's default chunk size
+                                         (2, 2, 16, 64, 30), (1, 2, 16, 32, 13),      # one V block of 1 or 2 slices
+                                         (1, 3, 8, 64, 40), (1, 2, 8, 32, 17)])       # 2 bits: half a V slice, the rest zero codes
 def test_pack_bit_exact(mq, ref, B, Hkv, N, G, C):
     rng = np.random.default_rng(N + G + C)
     cfg, rcfg = _cfgs(mq, ref, B, Hkv, Hkv, N, G, (2, 4, 8, 16), 1)
@@ -297,6 +301,14 @@ def _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, bits, seed, scale=None, expert=N
     (1, 8, 2, 32, 64, 50, 31),       # ... with grouped queries x4
     (1, 4, 2, 32, 32, 9, 5),
     (1, 2, 2, 32, 64, 2500, 3),      # ... and several row segments (more than 1024 chunks per row)
+    (1, 4, 4, 16, 64, 90, 11),       # chunks of 16 tokens: units shorter than a KiB of codes at 2 bits
+    (2, 2, 2, 16, 32, 41, 0),
+    (1, 8, 2, 16, 64, 70, 15),       # ... with grouped queries x4
+    (1, 4, 4, 8, 64, 150, 5),        # chunks of 8 tokens: short units at 2 and 4 bits, padded V slice at 2 bits, 8-row FP16 units
+    (2, 2, 2, 8, 32, 77, 7),
+    (1, 8, 2, 8, 64, 120, 3),        # ... with grouped queries x4
+    (1, 4, 2, 8, 32, 60, 0),
+    (1, 1, 1, 8, 64, 2100, 1),       # ... and several row segments
 ])
 def test_attention_mixed_bits(mq, ref, B, Hq, Hkv, N, G, C, T):
     err = _attn_case(mq, ref, B, Hq, Hkv, N, G, C, T, (2, 4, 8, 16), seed=C * 7 + T)
@@ -304,9 +316,10 @@ def test_attention_mixed_bits(mq, ref, B, Hq, Hkv, N, G, C, T):
 
 
 @pytest.mark.parametrize("bits", [(2,), (4,), (8,), (16,)])
-@pytest.mark.parametrize("N,G,rep", [(128, 64, 1), (64, 32, 4), (192, 32, 1), (256, 64, 2), (32, 64, 1), (32, 64, 8), (32, 32, 2)])
+@pytest.mark.parametrize("N,G,rep", [(128, 64, 1), (64, 32, 4), (192, 32, 1), (256, 64, 2), (32, 64, 1), (32, 64, 8), (32, 32, 2),
+                                     (16, 64, 1), (16, 32, 2), (16, 64, 8), (8, 64, 1), (8, 32, 1), (8, 64, 4), (8, 32, 4)])
 def test_attention_single_bit_width(mq, ref, bits, N, G, rep):
-    err = _attn_case(mq, ref, 1, 2 * rep, 2, N, G, 12, 17, bits, seed=bits[0] + N, freeze=0)
+    err = _attn_case(mq, ref, 1, 2 * rep, 2, N, G, 12, min(17, N - 1), bits, seed=bits[0] + N, freeze=0)
     assert err <= ATTN_TOL, err
 
 
@@ -364,6 +377,8 @@ def test_per_channel_keys_limits(mq):
     (1, 4, 1, 2, 64, 64, 9, 33),         # x4 heads x 2 tokens: eight rows per KV head; the new tokens straddle two 16-row units
     (1, 1, 1, 8, 256, 64, 5, 8),         # eight new tokens
     (1, 2, 2, 4, 32, 64, 41, 4),         # chunks of 32 tokens
+    (1, 2, 2, 4, 8, 64, 37, 6),          # chunks of 8 tokens: the residual buffers hold 8 rows
+    (1, 4, 2, 2, 16, 64, 29, 3),
     (1, 3, 3, 1, 128, 64, 6, 7),         # one query: the plain decode call
     (1, 2, 2, 4, 64, 64, 0, 20),         # no packed chunk yet
 ])
@@ -487,6 +502,8 @@ def _ragged_case(mq, ref, Hq, Hkv, N, G, lens, bits=(2, 4, 8, 16), seed=0):
     (2, 1, 64, 64, [64 * 300, 64 * 2 + 1, 5]),                              # grouped queries x2, one row much longer than the rest
     (3, 3, 128, 64, [0, 0, 77]),                                            # almost everything empty
     (4, 2, 32, 64, [32 * 50 + 7, 31, 32 * 3, 0]),                           # chunks of 32 tokens, grouped queries x2
+    (2, 2, 8, 64, [8 * 200 + 7, 5, 8 * 3, 0]),                              # chunks of 8 tokens
+    (4, 1, 16, 32, [16 * 90 + 15, 16, 1]),
 ])
 def test_attention_ragged_batch(mq, ref, Hq, Hkv, N, G, lens):
     err = _ragged_case(mq, ref, Hq, Hkv, N, G, lens, seed=len(lens) * 31 + N)
