@@ -33,9 +33,10 @@ class LayerCache:
         self.arena = torch.zeros(cap, dtype=torch.uint8, device=dev)
         self.arena_used = torch.zeros(1, dtype=torch.int64, device=dev)
         self.status = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.expert = torch.zeros((self.BH, max_chunks), dtype=torch.uint8, device=dev)
-        self.votes = torch.zeros((self.BH, max_chunks, len(cfg.expert_bits)), dtype=torch.int32, device=dev)
-        self.chunk_off = torch.zeros((self.BH, max_chunks), dtype=torch.int64, device=dev)
+        cols = (max_chunks + 15) // 16 * 16                   # table rows of whole 16-byte pieces: the pack call then plans one row per workgroup
+        self.expert = torch.zeros((self.BH, cols), dtype=torch.uint8, device=dev)
+        self.votes = torch.zeros((self.BH, cols, len(cfg.expert_bits)), dtype=torch.int32, device=dev)
+        self.chunk_off = torch.zeros((self.BH, cols), dtype=torch.int64, device=dev)
         shape = (cfg.batch, cfg.n_kv_heads, cfg.chunk, cfg.head_dim)
         self.K_tail = torch.zeros(shape, dtype=torch.float16, device=dev)
         self.V_tail = torch.zeros(shape, dtype=torch.float16, device=dev)

@@ -20,7 +20,7 @@ def test_random_shapes(mq, ref):
     worst = 0.0
     for n in range(N_CASES):
         kind = n % 3
-        N = int(rng.choice([32, 64, 128, 192, 256])); G = int(rng.choice([32, 64]))
+        N = int(rng.choice([8, 16, 32, 64, 128, 192, 256])); G = int(rng.choice([32, 64]))
         Hkv = int(rng.choice([1, 2, 3, 4])); rep = int(rng.choice([1, 1, 2, 4] if G == 64 else [1, 1, 2]))
         Hq = Hkv * rep; B = int(rng.choice([1, 2, 3]))
         seed = int(rng.integers(1 << 30))

@@ -57,10 +57,10 @@ def _full_parity(env, name, n_decode=1, check_mix=False):
     lc.compress_prefill(K, V, router=router)
     torch.cuda.synchronize()
     lc.check_status()
-    assert np.array_equal(lc.votes.cpu().numpy(), v_ref)
-    assert np.array_equal(lc.expert.cpu().numpy(), e_ref)
+    assert np.array_equal(lc.votes.cpu().numpy()[:, :C], v_ref)      # the cache's tables have whole 16-byte rows: C columns in use
+    assert np.array_equal(lc.expert.cpu().numpy()[:, :C], e_ref)
     assert int(lc.arena_used.item()) == int(used_ref[0])
-    assert np.array_equal(lc.chunk_off.cpu().numpy().astype(np.uint64), off_ref)
+    assert np.array_equal(lc.chunk_off.cpu().numpy()[:, :C].astype(np.uint64), off_ref)
     got = lc.arena.cpu().numpy()
     bad = np.nonzero(got != arena_ref)[0]
     assert bad.size == 0, f"{bad.size} packed bytes differ, first at {bad[:4]}"
