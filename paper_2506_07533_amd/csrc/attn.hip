@@ -198,10 +198,7 @@ __device__ __forceinline__ void load_v(const Unit &u, int lane, VRegs<G> &v, int
             const bool ok = lo && i < ntile;
             v.c[i] = uint4{ok ? t.x : 0u, ok ? t.y : 0u, ok ? t.z : 0u, ok ? t.w : 0u};
         }
-    } else if (u.nsub == 4) {
-#pragma unroll
-        for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vb + j * 1024, vv);
-    } else {
+    } else {                                              // short unit: the last KiB is read again (ignored); one code path, so that the waits can be counted
 #pragma unroll
         for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vb, vv + (uint32_t)min(j, u.nsub - 1) * 1024u);
     }
@@ -648,13 +645,8 @@ __device__ __forceinline__ void load_k_iq(const Unit &u, int lane, KRegs<G> &k) 
     constexpr int NG = kD / G;
     const uint32_t xq = (uint32_t)lane >> 4, c = (uint32_t)lane & 15u;
     const uint32_t vk = u.kc + (uint32_t)lane * 16u;
-    if (u.nsub == 4) {
 #pragma unroll
-        for (int j = 0; j < 4; j++) k.c[j] = ld16(u.kb + j * 1024, vk);
-    } else {                                              // short unit: the last KiB is read again (ignored)
-#pragma unroll
-        for (int j = 0; j < 4; j++) k.c[j] = ld16(u.kb, vk + (uint32_t)min(j, u.nsub - 1) * 1024u);
-    }
+    for (int j = 0; j < 4; j++) k.c[j] = ld16(u.kb, vk + (uint32_t)min(j, u.nsub - 1) * 1024u);   // short unit: the last KiB is read again (ignored)
     if constexpr (KPC) {
         if (u.lgb < 4) {
             const int t0 = (int)(u.kc >> (4 + u.lgb)), TU = u.nsub << (6 - u.lgb);
@@ -667,23 +659,22 @@ __device__ __forceinline__ void load_k_iq(const Unit &u, int lane, KRegs<G> &k) 
         }
         return;
     }
-    if (u.lgb == 1) {
-        const uint32_t tok = 16u * (xq >> 1) + c, part = xq & 1u;
-        const uint32_t vm = u.km + (tok * NG + part * (NG / 2)) * 4u;
+    // The same number of loads whatever the unit (a raw fp16 unit reads four words of its rows and ignores them) and
+    // no branch: the waits on everything requested after these loads can then be counted exactly.
+    // word of the lane's (token, group) per bit-width, and the step from register j to j + 1 (8 bits: two steps)
+    const uint32_t w1 = (16u * (xq >> 1) + c) * NG + (xq & 1u) * (NG / 2);
+    const uint32_t w2 = c * NG + (NG == 2 ? (xq >> 1) : xq);
+    const uint32_t w3 = c * NG + (NG == 2 ? 0u : (xq >> 1));
+    const uint32_t vm = u.lgb == 4 ? u.kc + c * 4u : u.km + (u.lgb == 1 ? w1 : (u.lgb == 2 ? w2 : w3)) * 4u;
+    const int jmax = (SMALL || u.lgb == 1) ? u.nsub - 1 : 3;   // a short unit's block ends early
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const uint32_t jo = (uint32_t)min(j, u.nsub - 1) * (32u * NG * 4u);
-            k.m[j][0] = ld4(u.kb, vm + jo);
-            if constexpr (NG == 4) k.m[j][1] = ld4(u.kb, vm + jo + 4u);
-        }
-    } else if (u.lgb == 2) {
-        const uint32_t vm = u.km + (c * NG + (NG == 2 ? (xq >> 1) : xq)) * 4u;
-#pragma unroll
-        for (int j = 0; j < 4; j++) k.m[j][0] = ld4(u.kb + (SMALL ? min(j, u.nsub - 1) : j) * 16 * NG * 4, vm);   // a short chunk's block ends early
-    } else if (u.lgb == 3) {
-        const uint32_t vm = u.km + (c * NG + (NG == 2 ? 0u : (xq >> 1))) * 4u;
-#pragma unroll
-        for (int j = 0; j < 4; j++) k.m[j][0] = ld4(u.kb + (j >> 1) * 16 * NG * 4 + (j & 1) * (NG / 2) * 4, vm);
+    for (int j = 0; j < 4; j++) {
+        const uint32_t jc = (uint32_t)min(j, jmax);
+        const uint32_t o1 = jc * (32u * NG * 4u), o2 = jc * (16u * NG * 4u);
+        const uint32_t o3 = (uint32_t)(j >> 1) * (16u * NG * 4u) + (uint32_t)(j & 1) * ((NG / 2) * 4u);
+        const uint32_t oj = u.lgb == 4 ? 0u : (u.lgb == 1 ? o1 : (u.lgb == 2 ? o2 : o3));
+        k.m[j][0] = ld4(u.kb, vm + oj);
+        if constexpr (NG == 4) k.m[j][1] = ld4(u.kb, vm + oj + (u.lgb == 1 ? 4u : 0u));
     }
 }
 
