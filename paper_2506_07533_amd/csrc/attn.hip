@@ -647,15 +647,15 @@ __device__ __forceinline__ void load_k_iq(const Unit &u, int lane, KRegs<G> &k) 
     const uint32_t vk = u.kc + (uint32_t)lane * 16u;
 #pragma unroll
     for (int j = 0; j < 4; j++) k.c[j] = ld16(u.kb, vk + (uint32_t)min(j, u.nsub - 1) * 1024u);   // short unit: the last KiB is read again (ignored)
-    if constexpr (KPC) {
-        if (u.lgb < 4) {
-            const int t0 = (int)(u.kc >> (4 + u.lgb)), TU = u.nsub << (6 - u.lgb);
-            const int ngu = (t0 % G + TU + G - 1) / G;
+    if constexpr (KPC) {                                  // four loads for every unit (a raw fp16 unit reads its own rows and ignores them)
+        const int lgq = min(u.lgb, 3);
+        const int t0 = (int)(u.kc >> (4 + lgq)), TU = u.nsub << (6 - lgq);
+        const int ngu = u.lgb == 4 ? 1 : (t0 % G + TU + G - 1) / G;
+        const uint32_t mbase = u.lgb == 4 ? u.kc : u.km;
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const uint2 mm = ld8(u.kb, u.km + (uint32_t)min(j, ngu - 1) * (kD * 4u) + (uint32_t)lane * 8u);
-                k.m[j][0] = mm.x; k.m[j][1] = mm.y;
-            }
+        for (int j = 0; j < 4; j++) {
+            const uint2 mm = ld8(u.kb, mbase + (uint32_t)min(j, ngu - 1) * (kD * 4u) + (uint32_t)lane * 8u);
+            k.m[j][0] = mm.x; k.m[j][1] = mm.y;
         }
         return;
     }
