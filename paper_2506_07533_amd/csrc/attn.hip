@@ -187,20 +187,17 @@ __device__ __forceinline__ void load_v(const Unit &u, int lane, VRegs<G> &v, int
     const int nw = u.nvalid * NG;                                         // SMALL: meta words of the unit (u.nsub counts whole KiB of codes)
     const uint32_t vv = u.vc + (uint32_t)lane * 16u, vmo = u.vm + (uint32_t)(SMALL ? min(lane, nw - 1) : lane) * 4u;
     const int nvm = u.lgb == 4 ? 1 : (SMALL ? max(nw >> 6, 1) : (u.nsub * NG) >> u.lgb);   // rows of 64 meta words, >= 1
-    const int ts = SMALL && u.lgb < 4 ? min(64, (max(N, u.lgb == 1 ? 16 : 8) << 4) >> (u.lgb == 1 ? 4 : 3)) : 64;   // slots per tile
-    if (SMALL && ts < 64) {
-        const int ntile = u.lgb == 3 ? 4 : 2;
-        const uint32_t vh = u.vc + (uint32_t)(lane & (ts - 1)) * 16u;
-        const bool lo = lane < ts;
+    // slots per tile (64 for whole 1-KiB tiles) and tiles of the chunk's one block; one code path for both shapes, so
+    // that the waits on the loads around these can be counted exactly
+    const int ts = SMALL && u.lgb < 4 ? min(64, (max(N, u.lgb == 1 ? 16 : 8) << 4) >> (u.lgb == 1 ? 4 : 3)) : 64;
+    const bool part = SMALL && ts < 64;
+    const int ntile = u.lgb == 3 ? 4 : 2;
+    const uint32_t vh = u.vc + (uint32_t)(lane & (ts - 1)) * 16u;
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const uint4 t = ld16(u.vb, vh + (uint32_t)(min(i, ntile - 1) * ts) * 16u);
-            const bool ok = lo && i < ntile;
-            v.c[i] = uint4{ok ? t.x : 0u, ok ? t.y : 0u, ok ? t.z : 0u, ok ? t.w : 0u};
-        }
-    } else {                                              // short unit: the last KiB is read again (ignored); one code path, so that the waits can be counted
-#pragma unroll
-        for (int j = 0; j < 4; j++) v.c[j] = ld16(u.vb, vv + (uint32_t)min(j, u.nsub - 1) * 1024u);
+    for (int i = 0; i < 4; i++) {
+        const uint4 t = ld16(u.vb, vh + (part ? (uint32_t)(min(i, ntile - 1) * ts) * 16u : (uint32_t)min(i, u.nsub - 1) * 1024u));
+        const bool ok = !part || (lane < ts && i < ntile);
+        v.c[i] = SMALL ? uint4{ok ? t.x : 0u, ok ? t.y : 0u, ok ? t.z : 0u, ok ? t.w : 0u} : t;
     }
 #pragma unroll
     for (int jj = 0; jj < VRegs<G>::MV; jj++) v.m[jj] = ld4(u.vb, vmo + (uint32_t)min(jj, nvm - 1) * 256u);
@@ -1215,7 +1212,9 @@ __global__ __launch_bounds__(NWV * 64) void attn_split_kernel(AttnArgs a) {
             unsigned int *counter = a.counters + ((size_t)u * n_seg + seg) * kCounterStride;
             // no cap for a workgroup whose whole interval lies in this row, or that covers the whole row
             const uint32_t quota = whole ? 0xffffffffu : (uint32_t)(((unsigned long long)T * ov + ru - 1) / ru);
-            if (seg == 0 && tid == 0) {                  // the batch asked for during the row set-up
+            if (P == 1u) {                               // nobody shares the row: every ticket is this workgroup's, no counter in memory needed
+                if (tid == 0) { L.bl[0] = 0u; L.bg[0] = 0u; L.nb = 1u; L.limit = T; L.g_seen = T; L.done = 1u; }
+            } else if (seg == 0 && tid == 0) {           // the batch asked for during the row set-up
                 const uint32_t granted = g_first < T ? min((uint32_t)NWV, T - g_first) : 0u;
                 L.g_seen = g_first + (uint32_t)NWV;
                 if (granted) { L.bl[0] = 0u; L.bg[0] = g_first; L.nb = 1u; L.limit = granted; }
