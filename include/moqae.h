@@ -94,8 +94,8 @@ typedef struct {
                                (as the values'); 1: G consecutive tokens of one dim (the outlier
                                channels of key caches, Sec. 2.2): needs N % G == 0; the K meta
                                area is then indexed [token group][dim], the codes keep their
-                               places; decode attention: one query head per KV head and the
-                               uniform calls only                                              */
+                               places; decode attention: one query head per KV head, one
+                               query per sequence (uniform and ragged calls alike)             */
 } moqae_cfg;
 
 /*

@@ -472,7 +472,7 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
                              float *out,
                              void *workspace, uint64_t workspace_bytes,
                              void *stream) {
-    if (!cfg_ok(cfg) || !layout_ok(cfg) || cfg->k_per_channel || !q || !out || !workspace || !n_chunks_seq || !n_tail_seq) return MOQAE_E_INVAL;
+    if (!cfg_ok(cfg) || !decode_ok(cfg) || !q || !out || !workspace || !n_chunks_seq || !n_tail_seq) return MOQAE_E_INVAL;
     if (max_chunks < 0) return MOQAE_E_INVAL;
     if (max_chunks > 0 && (!arena || !chunk_off || !expert || desc_stride < max_chunks)) return MOQAE_E_INVAL;
     if (!K_tail || !V_tail) return MOQAE_E_INVAL;
@@ -486,7 +486,7 @@ int moqae_decode_attn_ragged(const moqae_cfg *cfg,
     a.q = static_cast<const uint16_t *>(q); a.arena = static_cast<const uint8_t *>(arena);
     a.chunk_off = chunk_off; a.expert = expert; a.desc_stride = desc_stride;
     a.K_tail = static_cast<const uint16_t *>(K_tail); a.V_tail = static_cast<const uint16_t *>(V_tail);
-    a.seq_chunks = n_chunks_seq; a.seq_tail = n_tail_seq; a.planned = 0; a.kpc = 0;
+    a.seq_chunks = n_chunks_seq; a.seq_tail = n_tail_seq; a.planned = 0; a.kpc = cfg->k_per_channel;
     a.nq = 1; a.rep_in = cfg->n_q_heads / cfg->n_kv_heads;
     a.counters = static_cast<unsigned int *>(workspace);
     a.part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counters_bytes(cfg, max_chunks)); a.out = out;

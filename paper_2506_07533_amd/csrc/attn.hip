@@ -1544,10 +1544,24 @@ __global__ __launch_bounds__(kD *kMergeGroups) void attn_merge_kernel(const floa
 
 template <int REP> constexpr int waves_per_wg() { return 8; }
 
+// The split kernel of a call: the instantiation for its batch shape (uniform / ragged) and chunk size.
+template <int G, int REP, bool KPC>
+static void launch_split(const AttnArgs &a, dim3 grid, dim3 block, hipStream_t s) {
+    constexpr int NWV = waves_per_wg<REP>();
+    if (a.N < 64) {
+        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, true, KPC>), grid, block, 0, s, a);
+        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true, KPC>), grid, block, 0, s, a);
+    } else {
+        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, false, KPC>), grid, block, 0, s, a);
+        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, false, KPC>), grid, block, 0, s, a);
+    }
+}
+
 template <int G, int REP>
 static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     constexpr int NWV = waves_per_wg<REP>();
     const int n_seg = attn_row_segments(a.n_chunks, a.N);
+    if (a.kpc && REP != 1) return hipErrorInvalidValue;  // per-channel keys: one query head per KV head (checked by the caller)
     if (!a.planned) {
         hipLaunchKernelGGL(attn_prep_kernel, dim3((unsigned)a.BH), dim3(256), 0, s, a, n_seg);
         hipError_t e0 = hipGetLastError();
@@ -1556,25 +1570,10 @@ static hipError_t launch_gr(const AttnArgs &a, hipStream_t s, hipEvent_t ev_begi
     if (ev_begin && hipEventRecord(ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
     const dim3 grid((unsigned)a.n_wg), block(NWV * 64);
     if constexpr (REP == 1) {
-        if (a.kpc) {                                      // uniform calls only (checked by the caller)
-            if (a.N < 64) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true, true>), grid, block, 0, s, a);
-            else           hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, false, true>), grid, block, 0, s, a);
-            hipError_t ek = hipGetLastError();
-            if (ek != hipSuccess) return ek;
-            if (ev_end && hipEventRecord(ev_end, s) != hipSuccess) return hipErrorInvalidValue;
-            hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)(a.BH * a.rep)), dim3(kD * kMergeGroups), 0, s,
-                               (const float *)a.part, a.out, a.rep,
-                               (const uint32_t *)(a.counters + (size_t)a.BH * n_seg * kCounterStride + a.BH), a.max_partials,
-                               a.planned ? a.counters : (unsigned int *)nullptr, n_seg, a.Hkv, a.nq, a.rep_in);
-            return hipGetLastError();
-        }
-    }
-    if (a.N < 64) {
-        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, true, false>), grid, block, 0, s, a);
-        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, true, false>), grid, block, 0, s, a);
+        if (a.kpc) launch_split<G, REP, true>(a, grid, block, s);
+        else       launch_split<G, REP, false>(a, grid, block, s);
     } else {
-        if (a.seq_chunks) hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, true, false, false>), grid, block, 0, s, a);
-        else              hipLaunchKernelGGL((attn_split_kernel<G, REP, NWV, false, false, false>), grid, block, 0, s, a);
+        launch_split<G, REP, false>(a, grid, block, s);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

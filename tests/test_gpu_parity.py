@@ -455,15 +455,15 @@ def test_argument_errors(mq):
 # decode attention over a batch of sequences of different lengths
 # ----------------------------------------------------------------------------------------------
 
-def _ragged_case(mq, ref, Hq, Hkv, N, G, lens, bits=(2, 4, 8, 16), seed=0):
+def _ragged_case(mq, ref, Hq, Hkv, N, G, lens, bits=(2, 4, 8, 16), seed=0, kpc=0):
     """lens: tokens per sequence.  Every sequence's cache is packed up to its own last full chunk; the oracle is
     called per sequence (batch 1) on that sequence's slice of the tables."""
     rng = np.random.default_rng(seed)
     B = len(lens)
     Cs = [L // N for L in lens]; Ts = [L % N for L in lens]
     Cmax = max(max(Cs), 1)
-    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, 1)
-    _, rcfg1 = _cfgs(mq, ref, 1, Hq, Hkv, N, G, bits, 1)
+    cfg, rcfg = _cfgs(mq, ref, B, Hq, Hkv, N, G, bits, 1, kpc)
+    _, rcfg1 = _cfgs(mq, ref, 1, Hq, Hkv, N, G, bits, 1, kpc)
     K, V = _rand_kv(rng, B, Hkv, Cmax * N + N)
     q = rng.standard_normal((B, Hq, 128), dtype=np.float32).astype(np.float16)
     expert = rng.integers(0, len(bits), (B * Hkv, Cmax)).astype(np.uint8)
@@ -507,6 +507,18 @@ def _ragged_case(mq, ref, Hq, Hkv, N, G, lens, bits=(2, 4, 8, 16), seed=0):
 ])
 def test_attention_ragged_batch(mq, ref, Hq, Hkv, N, G, lens):
     err = _ragged_case(mq, ref, Hq, Hkv, N, G, lens, seed=len(lens) * 31 + N)
+    assert err <= ATTN_TOL, err
+
+
+@pytest.mark.parametrize("H,N,G,lens", [
+    (2, 128, 64, [128 * 33 + 100, 128 * 3, 90, 0, 128 * 17 + 1]),
+    (3, 64, 32, [64 * 70 + 5, 17, 64 * 7, 64 * 12 + 63]),
+    (2, 32, 32, [32 * 50 + 7, 31, 32 * 3, 0]),                              # chunks of 32 tokens
+    (1, 256, 64, [256 * 9 + 255, 256, 255]),
+])
+def test_per_channel_keys_ragged_batch(mq, ref, H, N, G, lens):
+    """Keys quantised per channel in a batch of sequences of different lengths."""
+    err = _ragged_case(mq, ref, H, H, N, G, lens, seed=len(lens) * 17 + N, kpc=1)
     assert err <= ATTN_TOL, err
 
 
