@@ -4,14 +4,18 @@
 // The ordered arena of moqae_quantize_pack puts a chunk's block where the blocks of all earlier chunks end,
 // so packing has to wait for every routing decision.  With one pool of equal pages per expert a chunk's place
 // is one atomic step on its pool's free ring, and the workgroup that has just routed the chunk quantises it at
-// once: the router's lanes leave the key rows they read in LDS and the quantiser takes them from there, so K comes
-// from memory once (a second pass over the tile through the caches was counted again by the L2's fetch counter:
-// with about 5 MB of tiles in flight per 4 MB L2 it does not stay there).
+// once, so K comes from memory once.
 //
-//   route_pack_kernel  one workgroup per (sequence, KV head, chunk): its first N/64 wavefronts route 64 tokens
-//                      each (route_tokens, the code of route_kernel), the votes are added up in LDS, one
-//                      thread takes a page of the routed expert's pool, then all threads pack K and V
-//                      (pack_side, the code of pack_kernel).
+//   route_pack_kernel  one workgroup per (sequence, KV head, chunk), one thread per token.  Keys per token: the thread
+//                      requests its whole key row (sixteen 16-byte pieces), routes it (route_row, the operations of
+//                      route_kernel in the same order), the votes are added up in LDS, one thread takes a page of the
+//                      routed expert's pool, then every thread quantises the row it still holds in registers and
+//                      after it its value row (pack_row, the arithmetic of pack_kernel).  A thread's codes are pieces
+//                      of lines, so the K codes and the V codes both go through staging rows in LDS and leave in
+//                      whole lines (k_flush, v_gather).  No key row is kept in LDS: 18 KiB per 128-token workgroup,
+//                      nine workgroups per compute unit.
+//                      Keys per channel (a group runs over G tokens, so a thread cannot quantise its own row): the
+//                      routing wavefronts leave the key rows in LDS (route_tokens) and pack_side takes them from there.
 //   pool_*_kernel      the free rings.  Device-wide atomic steps on ONE address run at about nine per microsecond on
 //                      this eight-die chip (40 960 chunks on four pool counters took 3.5 ms, 0.8 ms without them), so
 //                      every pool's free pages are spread over kPoolShards rings: a chunk starts at a ring chosen by
@@ -25,8 +29,8 @@ namespace moqae {
 
 template <int M, int G, bool KPC>
 __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
-    extern __shared__ uint4 dyn_lds[];                // the chunk's key rows as the router read them (N * kStageRow pieces), then
-    uint8_t *vcodes = reinterpret_cast<uint8_t *>(dyn_lds);   // the V staging rows of pack_side (N * kVRow bytes) in the same place
+    extern __shared__ uint4 dyn_lds[];                // keys per channel: the chunk's key rows as the router read them (N * kStageRow
+    uint8_t *vcodes = reinterpret_cast<uint8_t *>(dyn_lds);   // pieces); then the staging rows of the codes (K: k_stage_row, V: kVRow bytes per token)
     __shared__ float w3f[72];
     __shared__ int votes_s[8];
     __shared__ unsigned long long page_off;
@@ -50,7 +54,23 @@ __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
     }
     __syncthreads();
     if (status_in != 0) return;                       // sticky error: the call is a no-op
-    if (routed && wave * 64 < N) {
+    // Keys per token: thread t owns token t.  Its whole key row stays in registers from the router to the quantiser.
+    uint4 x[16], xv[16];
+    const bool own = tid < N;
+    if constexpr (!KPC) {
+        const uint4 *krow = reinterpret_cast<const uint4 *>(a.K + base + (int64_t)(own ? tid : 0) * a.stride_s);
+#pragma unroll
+        for (int j = 0; j < 16; j++) x[j] = krow[j];
+        if (routed) {
+            const int top = route_row<M>(x, reinterpret_cast<const uint32_t *>(a.W1), reinterpret_cast<const uint32_t *>(a.W2), w3f,
+                                         a.bias != nullptr);
+#pragma unroll
+            for (int k = 0; k < M; k++) {
+                const int n = __popcll(__ballot(own && top == k));
+                if (lane == k) atomicAdd(&votes_s[k], n);
+            }
+        }
+    } else if (routed && wave * 64 < N) {
         int cnt[M];
         route_tokens<M, true>(a.K + base + (int64_t)wave * 64 * a.stride_s, min(64, N - wave * 64), a.stride_s,
                               reinterpret_cast<const uint32_t *>(a.W1), reinterpret_cast<const uint32_t *>(a.W2), w3f,
@@ -102,13 +122,30 @@ __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
     // ---- (3) quantise and pack K, then V, into the page
     const int bits = a.bits_of[expert_s];
     uint8_t *blk = a.arena + page_off;
-    if (routed) {                                     // the keys are in LDS: K comes from memory once
-        pack_side<G, KPC>(reinterpret_cast<const uint16_t *>(dyn_lds), kStageRow * 8, N, bits, 0, blk, vcodes, tid, NT);
-        __syncthreads();                              // the key rows are consumed: the V staging rows take their place
+    if constexpr (!KPC) {
+        if (own) pack_row<G>(x, tid, N, bits, 0, blk, vcodes);
+        const uint4 *vrow = reinterpret_cast<const uint4 *>(a.V + base + (int64_t)(own ? tid : 0) * a.stride_s);
+#pragma unroll
+        for (int j = 0; j < 16; j++) xv[j] = vrow[j];   // in flight while the K codes leave
+        if (bits != 16) {
+            __syncthreads();
+            k_flush(N, bits, blk, vcodes, tid, NT);
+            __syncthreads();                          // the K staging rows are consumed: the V staging rows take their place
+        }
+        if (own) pack_row<G>(xv, tid, N, bits, 1, blk, vcodes);
+        if (bits == 16) return;
+        __syncthreads();
+        const int room = v_token_room(N, bits);
+        v_gather(N, bits, room, reinterpret_cast<uint32_t *>(blk + (size_t)N * kD * bits / 8 + (size_t)N * (kD / G) * 4), vcodes, tid, NT);
     } else {
-        pack_side<G, KPC>(a.K + base, a.stride_s, N, bits, 0, blk, vcodes, tid, NT);
+        if (routed) {                                 // the keys are in LDS: K comes from memory once
+            pack_side<G, KPC>(reinterpret_cast<const uint16_t *>(dyn_lds), kStageRow * 8, N, bits, 0, blk, vcodes, tid, NT);
+            __syncthreads();                          // the key rows are consumed: the V staging rows take their place
+        } else {
+            pack_side<G, KPC>(a.K + base, a.stride_s, N, bits, 0, blk, vcodes, tid, NT);
+        }
+        pack_side<G, KPC>(a.V + base, a.stride_s, N, bits, 1, blk, vcodes, tid, NT);
     }
-    pack_side<G, KPC>(a.V + base, a.stride_s, N, bits, 1, blk, vcodes, tid, NT);
 }
 
 // Before every call: the status word is latched for the call's workgroups, and heads that ran past their tails on
@@ -198,7 +235,10 @@ hipError_t launch_route_pack_paged(const PagedArgs &a, hipStream_t s) {
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
     dim3 grid((unsigned)a.n_chunks, (unsigned)a.BH);
-    const size_t lds = (size_t)a.N * (kStageRow * 16 > kVRow ? kStageRow * 16 : kVRow);
+    // keys per token: the V staging rows only; keys per channel: the key rows as the router read them, then the V rows
+        // keys per token: the staging rows of the K codes, then of the V codes; keys per channel: the key rows as the router
+    // read them, then the V rows
+    const size_t lds = (size_t)a.N * (a.kpc ? (kStageRow * 16 > kVRow ? kStageRow * 16 : kVRow) : (k_stage_row(8) > kVRow ? k_stage_row(8) : kVRow));
     switch (a.M) {
         case 1: return launch_rp<1>(a, grid, lds, s);
         case 2: return launch_rp<2>(a, grid, lds, s);

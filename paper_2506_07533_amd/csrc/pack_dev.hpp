@@ -64,18 +64,12 @@ constexpr uint32_t kMagicBits = 0x4B400000u;
 // words are sums of bits(t + magic) << shift, i.e. of the codes plus a constant that is taken off at
 // the end; no code is ever masked.  No clamp is needed: the scale is rounded up, so that
 // (x - min) * (1/scale) <= qmax * (1 + 2e-7) and rounds to at most qmax, and x >= min.
-template <int G, int BITS>
-__device__ __forceinline__ void pack_item(const uint4 *__restrict__ p, bool isV, uint32_t *__restrict__ meta_dst,
-                                          uint32_t *__restrict__ k_dst, uint32_t *__restrict__ v_lds) {
-    constexpr int NW = G / 2;                        // input words (fp16 pairs) of the item
+// STAGED: meta_dst is a register of the caller and k_dst a staging row in LDS (plain stores), see pack_row.
+template <int G, int BITS, bool STAGED = false>
+__device__ __forceinline__ void pack_item_regs(const uint32_t *w, bool isV, uint32_t *__restrict__ meta_dst,
+                                               uint32_t *__restrict__ k_dst, uint32_t *__restrict__ v_lds) {
+    constexpr int NW = G / 2;                        // input words (fp16 pairs) of the item, w[0..NW)
     static_assert(NW >= 16, "G >= 32");
-    uint32_t w[NW];
-#pragma unroll
-    for (int j = 0; j < G / 8; j++) {                // the whole item is requested at once: its 128-byte line arrives once
-        // (ordinary loads: the lane's eight loads share the line through the cache; streaming loads here fetch it eight times)
-        const uint4 t = p[j];
-        w[4 * j] = t.x; w[4 * j + 1] = t.y; w[4 * j + 2] = t.z; w[4 * j + 3] = t.w;
-    }
     uint32_t mn4[4], mx4[4];                          // four independent chains, folded at the end
 #pragma unroll
     for (int k = 0; k < 4; k++) { mn4[k] = pk_min_f16(w[k], w[k + 4]); mx4[k] = pk_max_f16(w[k], w[k + 4]); }
@@ -94,7 +88,8 @@ __device__ __forceinline__ void pack_item(const uint4 *__restrict__ p, bool isV,
     if (half_bits_to_float(s16) < s32) s16 += 1;      // the scale is rounded up
     if (s16 == 0) s16 = 0x3C00u;                      // constant group: scale 1
     const float inv = __fdiv_rn(1.0f, half_bits_to_float(s16));
-    nt_store(meta_dst, s16 | (float_to_half_bits(mn) << 16));
+    if constexpr (STAGED) *meta_dst = s16 | (float_to_half_bits(mn) << 16);
+    else                  nt_store(meta_dst, s16 | (float_to_half_bits(mn) << 16));
     const float nmn = -mn;
     auto ubits = [&](int d) -> uint32_t {             // kMagicBits + code of dim d of the item
         const float diff = (d & 1) ? add_hi_f16(w[d >> 1], nmn) : add_lo_f16(w[d >> 1], nmn);
@@ -124,13 +119,31 @@ __device__ __forceinline__ void pack_item(const uint4 *__restrict__ p, bool isV,
         }
         if constexpr (WPL >= 4) {
 #pragma unroll
-            for (int k = 0; k < WPL; k += 4)
-                nt_store(reinterpret_cast<uint4 *>(k_dst + k), uint4{out[k], out[k + 1], out[k + 2], out[k + 3]});
+            for (int k = 0; k < WPL; k += 4) {
+                const uint4 o = uint4{out[k], out[k + 1], out[k + 2], out[k + 3]};
+                if constexpr (STAGED) *reinterpret_cast<uint4 *>(k_dst + k) = o;
+                else                  nt_store(reinterpret_cast<uint4 *>(k_dst + k), o);
+            }
         } else {
             static_assert(WPL == 2, "G = 32 at 2 bits");
-            nt_store(reinterpret_cast<uint2 *>(k_dst), uint2{out[0], out[1]});
+            if constexpr (STAGED) *reinterpret_cast<uint2 *>(k_dst) = uint2{out[0], out[1]};
+            else                  nt_store(reinterpret_cast<uint2 *>(k_dst), uint2{out[0], out[1]});
         }
     }
+}
+
+// The same from memory: p = the item's G fp16 values.
+template <int G, int BITS>
+__device__ __forceinline__ void pack_item(const uint4 *__restrict__ p, bool isV, uint32_t *__restrict__ meta_dst,
+                                          uint32_t *__restrict__ k_dst, uint32_t *__restrict__ v_lds) {
+    uint32_t w[G / 2];
+#pragma unroll
+    for (int j = 0; j < G / 8; j++) {                // the whole item is requested at once: its 128-byte line arrives once
+        // (ordinary loads: the lane's eight loads share the line through the cache; streaming loads here fetch it eight times)
+        const uint4 t = p[j];
+        w[4 * j] = t.x; w[4 * j + 1] = t.y; w[4 * j + 2] = t.z; w[4 * j + 3] = t.w;
+    }
+    pack_item_regs<G, BITS>(w, isV, meta_dst, k_dst, v_lds);
 }
 
 // Keys quantised per channel: a group is G consecutive tokens of one dim.  One wavefront per token group, lane l owns
@@ -185,6 +198,108 @@ __device__ __forceinline__ void pack_k_channel_group(const uint16_t *src, int64_
     }
 }
 
+// The V codes of a chunk from the staging rows (vcodes: one code per byte, kVRow bytes per token row) into the
+// dimension-major tile layout at codes_w, by NT threads; room = v_token_room(N, bits).
+// V: dimension-major tiles of 16*QD slots x 4 words.  A slot holds TQ = max(TW, 8) consecutive tokens
+// (TW = 32/bits per word, WD = TQ/TW words) of CPK = 4/WD dimensions that lie 16 apart; a token block is
+// TB = min(4*TQ, room) tokens = QD slices (QD = 4, i.e. 1-KiB tiles, for N >= 64; a shorter chunk is one block of
+// 1, 2 or 4 slices; 8 tokens at 2 bits fill half a slice); slot 16*qd + j of tile cg of a block: dims
+// 16*(cg*CPK + n/WD) + j, token slice qd.
+template <int BITS>
+__device__ __forceinline__ void v_gather_bits(int N, int room, uint32_t *codes_w, const uint8_t *vcodes, int tid, int NT) {
+    constexpr int TW = 32 / BITS, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, NCG = kD / (16 * CPK);
+    const int TB = min(4 * TQ, room), QD = TB / TQ;
+    const int n_groups = room * kD * BITS / 128;      // a thread builds the words of four adjacent dims at a time
+    for (int g = tid; g < n_groups; g += NT) {
+        const int n = g & 3, jq = (g >> 2) & 3, qd = (g >> 4) & (QD - 1), tile = g / (16 * QD);
+        const int cg = tile % NCG, block = tile / NCG;
+        const int d0 = 16 * (cg * CPK + n / WD) + 4 * jq, t0 = block * TB + qd * TQ + (n % WD) * TW;
+        uint32_t wk[4] = {0u, 0u, 0u, 0u};
+        const uint8_t *src = vcodes + t0 * kVRow + d0;                  // the codes of dims d0..d0+3 of token t0 + e: word e*kVRow
+        if (t0 + TW <= N) {
+            // tokens 2k (low half-word) and 2k+1 (high) of a word share the shift BITS*k: one byte permute puts the two
+            // codes of a dim in place, one shift-or adds the pair to the dim's word
+#pragma unroll
+            for (int k = 0; k < TW / 2; k++) {
+                const uint32_t ev = *reinterpret_cast<const uint32_t *>(src + (2 * k) * kVRow);
+                const uint32_t od = *reinterpret_cast<const uint32_t *>(src + (2 * k + 1) * kVRow);
+#pragma unroll
+                for (int j = 0; j < 4; j++)           // bytes 0..3 of the selector's source are `ev`, 4..7 `od`; 0x0c gives zero
+                    wk[j] |= __builtin_amdgcn_perm(od, ev, 0x0c000c00u | (uint32_t)j | ((uint32_t)(4 + j) << 16)) << (BITS * k);
+            }
+        } else {                                      // tokens past the chunk (half a slice): zero codes
+            const int te = min(TW, N - t0);
+            for (int e = 0; e < te; e++) {
+                const uint32_t v4 = *reinterpret_cast<const uint32_t *>(src + e * kVRow);
+                const int sh = code_shift(e, BITS);
+                wk[0] |= (v4 & 0xffu) << sh; wk[1] |= ((v4 >> 8) & 0xffu) << sh; wk[2] |= ((v4 >> 16) & 0xffu) << sh; wk[3] |= (v4 >> 24) << sh;
+            }
+        }
+        // thread n = 0..3 of a quad holds word n of the slots 16*qd + 4*jq + k, k = 0..3: a 4 x 4 transpose inside
+        // the quad leaves every thread with one whole slot, stored with one 16-byte store
+#pragma unroll
+        for (int k = 0; k < 4; k += 2) {
+            const uint32_t r = dpp_u<DPP_XOR1>((n & 1) ? wk[k] : wk[k + 1]);
+            if (n & 1) wk[k] = r; else wk[k + 1] = r;
+        }
+#pragma unroll
+        for (int k = 0; k < 2; k++) {
+            const uint32_t r = dpp_u<DPP_XOR2>((n & 2) ? wk[k] : wk[k + 2]);
+            if (n & 2) wk[k] = r; else wk[k + 2] = r;
+        }
+        nt_store(reinterpret_cast<uint4 *>(codes_w + (tile * 16 * QD + 16 * qd + 4 * jq + n) * 4), uint4{wk[0], wk[1], wk[2], wk[3]});
+    }
+}
+__device__ __forceinline__ void v_gather(int N, int bits, int room, uint32_t *codes_w, const uint8_t *vcodes, int tid, int NT) {
+    if (bits == 2)      v_gather_bits<2>(N, room, codes_w, vcodes, tid, NT);
+    else if (bits == 4) v_gather_bits<4>(N, room, codes_w, vcodes, tid, NT);
+    else                v_gather_bits<8>(N, room, codes_w, vcodes, tid, NT);
+}
+
+// One token row (sixteen 16-byte pieces, in registers) of a chunk's K (isV = 0) or V (isV = 1) -> the chunk's block at
+// bit-width `bits`: its NG items as pack_side would pack them, by the thread that owns the row.  Consecutive lanes own
+// consecutive rows, so what a lane would store itself are pieces of lines: the row's meta words leave as one
+// store per lane (a contiguous run over the wavefront), the K codes go to staging rows in LDS (`stage`, kKStageRow(bits)
+// bytes per row) from where k_flush writes them out in whole lines, the V codes to the staging rows of v_gather.
+__host__ __device__ __forceinline__ constexpr int k_stage_row(int bits) { return kD * bits / 8 + 16; }   // + 16: rows start on different banks
+template <int G>
+__device__ __forceinline__ void pack_row(const uint4 (&x)[16], int row, int N, int bits, int isV, uint8_t *blk, uint8_t *stage) {
+    if (bits == 16) {                                 // FP16 expert: the row copied verbatim (through the cache: it merges the pieces)
+        uint4 *dst = reinterpret_cast<uint4 *>(blk + (isV ? (size_t)N * kD * 2 : 0)) + row * 16;
+#pragma unroll
+        for (int j = 0; j < 16; j++) dst[j] = x[j];
+        return;
+    }
+    constexpr int NG = kD / G, NW = G / 2;
+    const int room = isV ? v_token_room(N, bits) : N;
+    const size_t k_code_bytes = (size_t)N * kD * bits / 8, meta_bytes = (size_t)N * NG * 4;
+    uint8_t *area = blk + (isV ? k_code_bytes + meta_bytes : 0);
+    uint32_t *meta_w = reinterpret_cast<uint32_t *>(area + (size_t)room * kD * bits / 8);
+    uint32_t w[kD / 2], mw[NG];
+#pragma unroll
+    for (int j = 0; j < 16; j++) { w[4 * j] = x[j].x; w[4 * j + 1] = x[j].y; w[4 * j + 2] = x[j].z; w[4 * j + 3] = x[j].w; }
+#pragma unroll
+    for (int g = 0; g < NG; g++) {
+        uint32_t *vl = reinterpret_cast<uint32_t *>(stage + row * kVRow + g * G);
+        uint32_t *kl = reinterpret_cast<uint32_t *>(stage + row * k_stage_row(bits) + g * (G * bits / 8));
+        if (bits == 2)      pack_item_regs<G, 2, true>(&w[g * NW], isV, &mw[g], kl, vl);
+        else if (bits == 4) pack_item_regs<G, 4, true>(&w[g * NW], isV, &mw[g], kl, vl);
+        else                pack_item_regs<G, 8, true>(&w[g * NW], isV, &mw[g], kl, vl);
+    }
+    if constexpr (NG == 2) nt_store(reinterpret_cast<uint2 *>(meta_w + row * NG), uint2{mw[0], mw[1]});
+    else                   nt_store(reinterpret_cast<uint4 *>(meta_w + row * NG), uint4{mw[0], mw[1], mw[2], mw[3]});
+}
+
+// The K codes of a chunk from the staging rows of pack_row to their token-major place, 16 bytes per thread and step.
+__device__ __forceinline__ void k_flush(int N, int bits, uint8_t *blk, const uint8_t *stage, int tid, int NT) {
+    const int ppr = kD * bits / 128, srow = k_stage_row(bits);     // 16-byte pieces per row: 2, 4, 8
+    uint4 *dst = reinterpret_cast<uint4 *>(blk);
+    for (int p = tid; p < N * ppr; p += NT) {
+        const int row = p / ppr, col = p % ppr;
+        nt_store(&dst[p], *reinterpret_cast<const uint4 *>(stage + row * srow + col * 16));
+    }
+}
+
 // K (isV = 0) or V (isV = 1) of one chunk -> its block `blk` at bit-width `bits`, by one workgroup of NT threads
 // (a multiple of 64).  src: the chunk's first row (row stride stride_s elements); vcodes: N * kVRow bytes of LDS (V only).
 // KPC: the keys' groups run along tokens (pack_k_channel_group); a template flag so that its G registers per lane stay out
@@ -227,40 +342,7 @@ __device__ __forceinline__ void pack_side(const uint16_t *src, int64_t stride_s,
     if (!isV) return;
 
     __syncthreads();
-    // V: dimension-major tiles of 16*QD slots x 4 words.  A slot holds TQ = max(TW, 8) consecutive tokens
-    // (TW = 32/bits per word, WD = TQ/TW words) of CPK = 4/WD dimensions that lie 16 apart; a token block is
-    // TB = min(4*TQ, room) tokens = QD slices (QD = 4, i.e. 1-KiB tiles, for N >= 64; a shorter chunk is one block of
-    // 1, 2 or 4 slices; 8 tokens at 2 bits fill half a slice); slot 16*qd + j of tile cg of a block: dims
-    // 16*(cg*CPK + n/WD) + j, token slice qd.
-    const int TW = 32 / bits, TQ = TW > 8 ? TW : 8, WD = TQ / TW, CPK = 4 / WD, NCG = kD / (16 * CPK);
-    const int TB = min(4 * TQ, room), QD = TB / TQ;
-    const int n_groups = room * kD * bits / 128;      // a thread builds the words of four adjacent dims at a time
-    for (int g = tid; g < n_groups; g += NT) {
-        const int n = g & 3, jq = (g >> 2) & 3, qd = (g >> 4) & (QD - 1), tile = g / (16 * QD);
-        const int cg = tile % NCG, block = tile / NCG;
-        const int d0 = 16 * (cg * CPK + n / WD) + 4 * jq, t0 = block * TB + qd * TQ + (n % WD) * TW;
-        uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
-        const int te = min(TW, N - t0);               // tokens past the chunk (half a slice): zero codes
-        for (int e = 0; e < te; e++) {
-            const uint32_t v4 = *reinterpret_cast<const uint32_t *>(vcodes + (t0 + e) * kVRow + d0);   // codes of dims d0..d0+3
-            const int sh = code_shift(e, bits);
-            w0 |= (v4 & 0xffu) << sh; w1 |= ((v4 >> 8) & 0xffu) << sh; w2 |= ((v4 >> 16) & 0xffu) << sh; w3 |= (v4 >> 24) << sh;
-        }
-        // thread n = 0..3 of a quad holds word n of the slots 16*qd + 4*jq + k, k = 0..3: a 4 x 4 transpose inside
-        // the quad leaves every thread with one whole slot, stored with one 16-byte store
-        uint32_t wk[4] = {w0, w1, w2, w3};
-#pragma unroll
-        for (int k = 0; k < 4; k += 2) {
-            const uint32_t r = dpp_u<DPP_XOR1>((n & 1) ? wk[k] : wk[k + 1]);
-            if (n & 1) wk[k] = r; else wk[k + 1] = r;
-        }
-#pragma unroll
-        for (int k = 0; k < 2; k++) {
-            const uint32_t r = dpp_u<DPP_XOR2>((n & 2) ? wk[k] : wk[k + 2]);
-            if (n & 2) wk[k] = r; else wk[k + 2] = r;
-        }
-        nt_store(reinterpret_cast<uint4 *>(codes_w + (tile * 16 * QD + 16 * qd + 4 * jq + n) * 4), uint4{wk[0], wk[1], wk[2], wk[3]});
-    }
+    v_gather(N, bits, room, codes_w, vcodes, tid, NT);
 }
 
 }  // namespace moqae

@@ -25,6 +25,77 @@ __device__ __forceinline__ float exp_pinned(float x) {
     return __fmul_rn(p, s);
 }
 
+// 64 dims of a key row (eight 16-byte pieces xr[0..7], dims dbase..dbase+63) into the two running sums per expert,
+// in ascending order of the dims.  W1w, W2w: the fp16 weight matrices as 32-bit words (wave-uniform loads).
+template <int M>
+__device__ __forceinline__ void route_half_row(const uint4 *xr, int dbase, const uint32_t *W1w, const uint32_t *W2w,
+                                               float (&accA)[M], float (&accB)[M]) {
+    // two key dims (two rows of the weight matrices) per step so that the fp16 pairs fall on 32-bit words
+#pragma unroll
+    for (int p = 0; p < 8; p++) {
+        const uint32_t xw[4] = {xr[p].x, xr[p].y, xr[p].z, xr[p].w};
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const int d = dbase + p * 8 + e;      // even; rows d, d+1 of W = 2*M halves = M words
+            const float x0 = half_bits_to_float(xw[e >> 1] & 0xffffu);
+            const float x1 = half_bits_to_float(xw[e >> 1] >> 16);
+            uint32_t w1[M], w2[M];
+#pragma unroll
+            for (int m = 0; m < M; m++) { w1[m] = W1w[d / 2 * M + m]; w2[m] = W2w[d / 2 * M + m]; }
+#pragma unroll
+            for (int m = 0; m < M; m++) {
+                const int i0 = m, i1 = M + m;     // half index inside the two-row block
+                const float wa0 = half_bits_to_float((w1[i0 >> 1] >> (16 * (i0 & 1))) & 0xffffu);
+                const float wb0 = half_bits_to_float((w2[i0 >> 1] >> (16 * (i0 & 1))) & 0xffffu);
+                accA[m] = fmaf(x0, wa0, accA[m]);
+                accB[m] = fmaf(x0, wb0, accB[m]);
+                const float wa1 = half_bits_to_float((w1[i1 >> 1] >> (16 * (i1 & 1))) & 0xffffu);
+                const float wb1 = half_bits_to_float((w2[i1 >> 1] >> (16 * (i1 & 1))) & 0xffffu);
+                accA[m] = fmaf(x1, wa1, accA[m]);
+                accB[m] = fmaf(x1, wb1, accB[m]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);        // keeps the uniform weight loads of later steps from piling up
+    }
+}
+
+// The token's expert from the two sums per expert: SiLU of their product, times W3 (plus the bias), first maximum.
+// w3f: W3 as binary32 (M*M values) and the optional bias at [64..64+M), in LDS.
+template <int M>
+__device__ __forceinline__ int route_top(const float (&accA)[M], const float (&accB)[M], const float *w3f, bool has_bias) {
+    float hid[M];
+#pragma unroll
+    for (int m = 0; m < M; m++) {
+        const float z = __fmul_rn(accA[m], accB[m]);
+        const float e = exp_pinned(-z);
+        hid[m] = __fdiv_rn(z, __fadd_rn(1.0f, e));              // SiLU(z) = z / (1 + exp(-z))
+    }
+    int top = 0; float ptop = 0.0f;
+#pragma unroll
+    for (int k = 0; k < M; k++) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int j = 0; j < M; j++) acc = __fadd_rn(acc, __fmul_rn(hid[j], w3f[j * M + k]));
+        if (has_bias) acc = __fadd_rn(acc, w3f[64 + k]);
+        if (k == 0) ptop = acc;
+        else if (acc > ptop) { top = k; ptop = acc; }           // strict: the first maximum wins
+    }
+    return top;
+}
+
+// One token's expert from its whole key row in registers (sixteen 16-byte pieces): the same operations in the same
+// order as route_tokens.
+template <int M>
+__device__ __forceinline__ int route_row(const uint4 (&x)[16], const uint32_t *W1w, const uint32_t *W2w, const float *w3f,
+                                         bool has_bias) {
+    float accA[M], accB[M];
+#pragma unroll
+    for (int m = 0; m < M; m++) { accA[m] = 0.0f; accB[m] = 0.0f; }
+    route_half_row<M>(&x[0], 0, W1w, W2w, accA, accB);
+    route_half_row<M>(&x[8], 64, W1w, W2w, accA, accB);
+    return route_top<M>(accA, accB, w3f, has_bias);
+}
+
 // One wavefront routes the n_tok tokens whose key rows start at Kc (row stride stride_s elements), one lane per
 // token and pass of 64 tokens; W1w, W2w: the fp16 weight matrices as 32-bit words (wave-uniform loads), w3f: W3 as
 // binary32 (M*M values) and the optional bias at [64..64+M), in LDS.  Returns the votes per expert, the same in
@@ -74,52 +145,9 @@ __device__ __forceinline__ void route_tokens(const uint16_t *Kc, int n_tok, int6
 #pragma unroll
             for (int m = 0; m < M; m++) { accA[m] = 0.0f; accB[m] = 0.0f; }
         }
-        // two key dims (two rows of the weight matrices) per step so that the fp16 pairs fall on 32-bit words
-        const int dbase = (hr & 1) * 64;
-#pragma unroll
-        for (int p = 0; p < 8; p++) {
-            const uint32_t xw[4] = {xr[p].x, xr[p].y, xr[p].z, xr[p].w};
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const int d = dbase + p * 8 + e;      // even; rows d, d+1 of W = 2*M halves = M words
-                const float x0 = half_bits_to_float(xw[e >> 1] & 0xffffu);
-                const float x1 = half_bits_to_float(xw[e >> 1] >> 16);
-                uint32_t w1[M], w2[M];
-#pragma unroll
-                for (int m = 0; m < M; m++) { w1[m] = W1w[d / 2 * M + m]; w2[m] = W2w[d / 2 * M + m]; }
-#pragma unroll
-                for (int m = 0; m < M; m++) {
-                    const int i0 = m, i1 = M + m;     // half index inside the two-row block
-                    const float wa0 = half_bits_to_float((w1[i0 >> 1] >> (16 * (i0 & 1))) & 0xffffu);
-                    const float wb0 = half_bits_to_float((w2[i0 >> 1] >> (16 * (i0 & 1))) & 0xffffu);
-                    accA[m] = fmaf(x0, wa0, accA[m]);
-                    accB[m] = fmaf(x0, wb0, accB[m]);
-                    const float wa1 = half_bits_to_float((w1[i1 >> 1] >> (16 * (i1 & 1))) & 0xffffu);
-                    const float wb1 = half_bits_to_float((w2[i1 >> 1] >> (16 * (i1 & 1))) & 0xffffu);
-                    accA[m] = fmaf(x1, wa1, accA[m]);
-                    accB[m] = fmaf(x1, wb1, accB[m]);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);        // keeps the uniform weight loads of later steps from piling up
-        }
+        route_half_row<M>(xr, (hr & 1) * 64, W1w, W2w, accA, accB);
         if (!(hr & 1)) continue;
-        float hid[M];
-#pragma unroll
-        for (int m = 0; m < M; m++) {
-            const float z = __fmul_rn(accA[m], accB[m]);
-            const float e = exp_pinned(-z);
-            hid[m] = __fdiv_rn(z, __fadd_rn(1.0f, e));              // SiLU(z) = z / (1 + exp(-z))
-        }
-        int top = 0; float ptop = 0.0f;
-#pragma unroll
-        for (int k = 0; k < M; k++) {
-            float acc = 0.0f;
-#pragma unroll
-            for (int j = 0; j < M; j++) acc = __fadd_rn(acc, __fmul_rn(hid[j], w3f[j * M + k]));
-            if (has_bias) acc = __fadd_rn(acc, w3f[64 + k]);
-            if (k == 0) ptop = acc;
-            else if (acc > ptop) { top = k; ptop = acc; }           // strict: the first maximum wins
-        }
+        const int top = route_top<M>(accA, accB, w3f, has_bias);
 #pragma unroll
         for (int k = 0; k < M; k++) cnt[k] += __popcll(__ballot(active && top == k));
     }
