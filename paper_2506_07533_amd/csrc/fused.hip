@@ -7,7 +7,8 @@
 // once, so K comes from memory once.
 //
 //   route_pack_kernel  one workgroup per (sequence, KV head, chunk), one thread per token.  Keys per token: the thread
-//                      requests its whole key row (sixteen 16-byte pieces), routes it (route_row, the operations of
+//                      gets its whole key row (a wavefront reads its 64 rows in whole lines and hands every lane its
+//                      own through LDS: rows_request, rows_transpose), routes it (route_row, the operations of
 //                      route_kernel in the same order), the votes are added up in LDS, one thread takes a page of the
 //                      routed expert's pool, then every thread quantises the row it still holds in registers and
 //                      after it its value row (pack_row, the arithmetic of pack_kernel).  A thread's codes are pieces
@@ -58,9 +59,8 @@ __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
     uint4 x[16], xv[16];
     const bool own = tid < N;
     if constexpr (!KPC) {
-        const uint4 *krow = reinterpret_cast<const uint4 *>(a.K + base + (int64_t)(own ? tid : 0) * a.stride_s);
-#pragma unroll
-        for (int j = 0; j < 16; j++) x[j] = krow[j];
+        rows_request(a.K + base, a.stride_s, N, wave, lane, xv);
+        rows_transpose(xv, vcodes, wave, lane, x);
         if (routed) {
             const int top = route_row<M>(x, reinterpret_cast<const uint32_t *>(a.W1), reinterpret_cast<const uint32_t *>(a.W2), w3f,
                                          a.bias != nullptr);
@@ -124,15 +124,15 @@ __global__ __launch_bounds__(kPackThreads) void route_pack_kernel(PagedArgs a) {
     uint8_t *blk = a.arena + page_off;
     if constexpr (!KPC) {
         if (own) pack_row<G>(x, tid, N, bits, 0, blk, vcodes);
-        const uint4 *vrow = reinterpret_cast<const uint4 *>(a.V + base + (int64_t)(own ? tid : 0) * a.stride_s);
-#pragma unroll
-        for (int j = 0; j < 16; j++) xv[j] = vrow[j];   // in flight while the K codes leave
+        rows_request(a.V + base, a.stride_s, N, wave, lane, xv);   // in flight while the K codes leave
         if (bits != 16) {
             __syncthreads();
             k_flush(N, bits, blk, vcodes, tid, NT);
-            __syncthreads();                          // the K staging rows are consumed: the V staging rows take their place
+            __syncthreads();                          // the K staging rows are consumed: the buffers of the transposition take their place
         }
-        if (own) pack_row<G>(xv, tid, N, bits, 1, blk, vcodes);
+        rows_transpose(xv, vcodes, wave, lane, x);
+        if (bits != 16) __syncthreads();              // every wavefront has its rows: the V staging rows take the buffers' place
+        if (own) pack_row<G>(x, tid, N, bits, 1, blk, vcodes);
         if (bits == 16) return;
         __syncthreads();
         const int room = v_token_room(N, bits);
@@ -235,10 +235,11 @@ hipError_t launch_route_pack_paged(const PagedArgs &a, hipStream_t s) {
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
     dim3 grid((unsigned)a.n_chunks, (unsigned)a.BH);
-    // keys per token: the V staging rows only; keys per channel: the key rows as the router read them, then the V rows
-        // keys per token: the staging rows of the K codes, then of the V codes; keys per channel: the key rows as the router
-    // read them, then the V rows
-    const size_t lds = (size_t)a.N * (a.kpc ? (kStageRow * 16 > kVRow ? kStageRow * 16 : kVRow) : (k_stage_row(8) > kVRow ? k_stage_row(8) : kVRow));
+    // keys per token: a transposition buffer per wavefront, then the staging rows of the K codes, then of the V codes;
+    // keys per channel: the key rows as the router read them, then the V rows
+    const int nt = a.N <= 64 ? 64 : (a.N >= 256 ? 256 : (a.N + 63) / 64 * 64);   // threads of a workgroup (launch_rp)
+    const size_t lds = a.kpc ? (size_t)a.N * (kStageRow * 16 > kVRow ? kStageRow * 16 : kVRow)
+                             : (size_t)nt * (k_stage_row(8) > kTRow ? k_stage_row(8) : kTRow);
     switch (a.M) {
         case 1: return launch_rp<1>(a, grid, lds, s);
         case 2: return launch_rp<2>(a, grid, lds, s);

@@ -256,6 +256,43 @@ __device__ __forceinline__ void v_gather(int N, int bits, int room, uint32_t *co
     else                v_gather_bits<8>(N, room, codes_w, vcodes, tid, NT);
 }
 
+// Token rows of a chunk from memory into the registers of the threads that own them (thread 64*wave + lane: row
+// 64*wave + lane), in two steps.  A lane that reads its own row alone touches lines nobody else in the wavefront
+// touches, sixteen times over: a read-only kernel of that shape moves 4.9 TB/s on this chip, one of whole lines per
+// group of eight lanes 7.0 TB/s.  rows_request: load instruction 8h + j reads the half rows h of rows 8j .. 8j+7 of the
+// wavefront, lane l the 16-byte piece l%8 of row 8j + l/8 (streaming loads: nothing is read twice).
+// rows_transpose: through a buffer of 64 rows of kTRow bytes per wavefront in LDS (tbuf: the workgroup's buffers),
+// half a row at a time, every lane takes the sixteen pieces of its own row.  Rows past the chunk's N read row N - 1.
+constexpr int kTRow = 128 + 16;                      // + 16: the rows start on different banks
+__device__ __forceinline__ void rows_request(const uint16_t *chunk, int64_t stride_s, int N, int wave, int lane, uint4 (&v)[16]) {
+    const int r8 = lane >> 3, p = lane & 7;
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int row = min(wave * 64 + 8 * j + r8, N - 1);
+            v[8 * h + j] = nt_load(reinterpret_cast<const uint4 *>(chunk + (int64_t)row * stride_s + h * 64) + p);
+        }
+    }
+}
+__device__ __forceinline__ void wave_lds_sync() {     // orders a wavefront's own LDS traffic between two phases
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+__device__ __forceinline__ void rows_transpose(const uint4 (&v)[16], uint8_t *tbuf, int wave, int lane, uint4 (&x)[16]) {
+    const int r8 = lane >> 3, p = lane & 7;
+    uint8_t *mine = tbuf + wave * (64 * kTRow);
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) *reinterpret_cast<uint4 *>(mine + (8 * j + r8) * kTRow + p * 16) = v[8 * h + j];
+        wave_lds_sync();
+#pragma unroll
+        for (int k = 0; k < 8; k++) x[8 * h + k] = *reinterpret_cast<const uint4 *>(mine + lane * kTRow + k * 16);
+        wave_lds_sync();
+    }
+}
+
 // One token row (sixteen 16-byte pieces, in registers) of a chunk's K (isV = 0) or V (isV = 1) -> the chunk's block at
 // bit-width `bits`: its NG items as pack_side would pack them, by the thread that owns the row.  Consecutive lanes own
 // consecutive rows, so what a lane would store itself are pieces of lines: the row's meta words leave as one
