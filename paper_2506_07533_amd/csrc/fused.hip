@@ -14,7 +14,7 @@
 //                      after it its value row (pack_row, the arithmetic of pack_kernel).  A thread's codes are pieces
 //                      of lines, so the K codes and the V codes both go through staging rows in LDS and leave in
 //                      whole lines (k_flush, v_gather).  No key row is kept in LDS: 18 KiB per 128-token workgroup,
-//                      nine workgroups per compute unit.
+//                      eight workgroups per compute unit.
 //                      Keys per channel (a group runs over G tokens, so a thread cannot quantise its own row): the
 //                      routing wavefronts leave the key rows in LDS (route_tokens) and pack_side takes them from there.
 //   pool_*_kernel      the free rings.  Device-wide atomic steps on ONE address run at about nine per microsecond on

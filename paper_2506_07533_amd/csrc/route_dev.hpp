@@ -126,7 +126,7 @@ __device__ __forceinline__ void route_tokens(const uint16_t *Kc, int n_tok, int6
 #pragma unroll 1
     for (int hr = 0; hr < n_half; hr++) {
         const int row0 = (hr >> 1) * 64;
-        const bool active = row0 + lane < n_tok;        // N is a multiple of 32: the last pass may be half empty
+        const bool active = row0 + lane < n_tok;        // the last pass may be partly empty
         uint4 xr[8];
 #pragma unroll
         for (int p = 0; p < 8; p++) xr[p] = xn[p];
