@@ -96,6 +96,51 @@ def test_gqa8b_128k_tables_reused_over_decode_calls(env):
     _full_parity(env, "gqa8b_128k", n_decode=3, check_mix=True)
 
 
+@pytest.mark.parametrize("name", ["llama13b_128k", "gqa8b_128k"])
+def test_route_pack_paged_full_size(env, name):
+    """The fused route + pack call at full size: decisions and votes of every chunk against the oracle, every chunk on a
+    page of its own in its expert's pool, the bytes of sampled pages against the oracle's block of that chunk."""
+    mq, cache, synth, R = env
+    w = synth.WORKLOADS[name]
+    d = synth.make_workload(w)
+    C, BH, M = w.n_chunks, w.batch * w.n_kv_heads, len(w.expert_bits)
+    cfg = mq.Cfg(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.chunk, w.group, w.expert_bits, w.freeze_chunks)
+    rcfg = R.RefCfg(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.chunk, w.group, w.expert_bits, w.freeze_chunks)
+    e_ref, v_ref = R.route_chunks(rcfg, d["K"], 0, C, d["W1"], d["W2"], d["W3"])
+    pages = tuple(int((e_ref == j).sum()) + 5 for j in range(M))
+    arena = torch.zeros(mq.pool_arena_bytes(cfg, pages), dtype=torch.uint8, device="cuda")
+    state = torch.zeros(mq.pool_state_bytes(cfg, pages) // 4, dtype=torch.int32, device="cuda")
+    mq.pool_init(cfg, pages, state)
+    expert = torch.full((BH, C), 255, dtype=torch.uint8, device="cuda")
+    votes = torch.full((BH, C, M), -1, dtype=torch.int32, device="cuda")
+    off = torch.zeros((BH, C), dtype=torch.int64, device="cuda"); status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    K = torch.from_numpy(d["K"]).cuda(); V = torch.from_numpy(d["V"]).cuda()
+    router = tuple(torch.from_numpy(d[k]).cuda() for k in ("W1", "W2", "W3")) + (None,)
+    mq.route_pack_paged(cfg, pages, K, V, 0, C, router, expert, votes, arena, state, off, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    assert np.array_equal(expert.cpu().numpy(), e_ref) and np.array_equal(votes.cpu().numpy(), v_ref)
+    assert mq.pool_free_pages(cfg, pages, state) == [5] * M
+    off_h = off.cpu().numpy().astype(np.uint64)
+    assert np.unique(off_h).size == BH * C                            # no page handed out twice
+    for j in range(M):                                                # every chunk in its expert's pool, on a page boundary
+        o = off_h[e_ref == j].astype(np.int64) - mq.pool_base(cfg, pages, j)
+        pb = mq.pool_page_bytes(cfg, j)
+        assert ((o >= 0) & (o < pages[j] * pb) & (o % pb == 0)).all(), j
+    rng = np.random.default_rng(7)
+    N = w.chunk
+    picks = [(int(rng.integers(BH)), int(rng.integers(C))) for _ in range(48)] + [(0, 0), (BH - 1, C - 1)]
+    for j in range(M):                                                # and at least two chunks of every bit-width
+        us, cs = np.nonzero(e_ref == j)
+        picks += [(int(us[i]), int(cs[i])) for i in rng.choice(us.size, min(2, us.size), replace=False)]
+    for u, c in picks:
+        b, h = divmod(u, w.n_kv_heads)
+        blk = R.pack_chunk(rcfg, w.expert_bits[int(e_ref[u, c])], d["K"][b, h, c * N:(c + 1) * N], d["V"][b, h, c * N:(c + 1) * N])
+        o = int(off_h[u, c])
+        got = arena[o:o + blk.size].cpu().numpy()
+        assert np.array_equal(got, blk), (u, c, int(e_ref[u, c]))
+
+
 @pytest.mark.parametrize("extra_tokens,flush_step", [(0, None), (96, 32)])
 def test_stack32_sampled(env, extra_tokens, flush_step):
     """32 layers, routing shared by groups of 4, 64 decode steps that append one token per step.
