@@ -334,6 +334,10 @@ def bench_layer(args, w):
         res["roofline_route_pack_paged"] = dict(roof(fused_bytes, t_f), kernel="route_pack_kernel (router + page + quantiser, one pass)",
                                                 samples=n_f)
         res["route_pack_paged_chunks_per_s"] = round(n_units / (t_f.mean() * 1e-3), 1)
+        # the second half of the headline metric, both ways of doing the same work
+        res["quantize_route_chunks_per_s"] = {"two_calls (moqae_route_chunks + moqae_quantize_pack)": res["route_pack_chunks_per_s"],
+                                              "one_call (moqae_route_pack_paged)": res["route_pack_paged_chunks_per_s"],
+                                              "best": max(res["route_pack_chunks_per_s"], res["route_pack_paged_chunks_per_s"])}
         del p_arena
 
     if not args.decode_only and not args.per_channel and w.n_q_heads // w.n_kv_heads <= 2:
